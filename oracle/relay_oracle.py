@@ -1,0 +1,371 @@
+"""CPU oracle for the selective-recompute prefill of RelayCaching.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain statement of what the
+HIP library must compute.  Only the tests, the smoke check and the benchmark's
+CPU-baseline leg may import it; the product path never does, and this module
+imports nothing from the product.
+
+Everything is numpy float64, one step after another in the paper's order, with
+no blocking, fusion or reordering.  `numpy.matmul` and `numpy.lexsort` are the
+only library primitives used as steps.
+
+What follows the paper, and where:
+  * deviation score            -- Section 4.2, Eq. (1)
+  * layer-wise similarity      -- Section 4.2, Eq. (2)
+  * layer roles (reuse / dense detect / sparse rectify) -- Section 4.2, the
+    paragraph after Eq. (4); Figure "Overview of RelayCaching", item (3)
+  * pre-RoPE key storage, hidden states cached at L_start -- Figure "Overview
+    of RelayCaching", item (2); Section 4.2 "Start layer"
+  * budget selection top floor(budget*S) -- the floor convention of the
+    CacheBlend setting in Appendix "Baseline Descriptions"
+  * threshold / influence / suffix selection -- Section 4.3, Eq. (5)-(10)
+  * FULL and ZERO baselines    -- Appendix "Baseline Descriptions"
+  * reuse rate                 -- Section 5.1 "Metrics"
+
+The paper runs stock decoder models and does not restate their arithmetic; the
+decoder layer here is the usual pre-norm one (RMSNorm, rotary GQA attention,
+SwiGLU), with the rotate-half rotary convention.
+
+Readings taken where the paper is silent (all restated in the design notes):
+  * H in Eq. (1) counts KV heads (value vectors exist per KV head).
+  * cos(a, b) = a.b / max(|a||b|, 1e-12).
+  * The layer triple is 0-based; h_start is the input of layer l_start; layers
+    [l_start, l_det) are dense, [l_det, l_end] sparse, both ends of the latter
+    included.
+  * New tokens (prefix, optional suffix) are active in every layer.
+  * With no suffix, the last segment token is always active from l_start to
+    the last layer: it carries the first-token logits.  It is not counted in k
+    and not reported among the selected indices.
+  * Selected rows write their fresh K/V into the cache before any row of that
+    layer attends.
+  * k = 0 skips the dense detect layers as well (pure reuse).
+
+Pins: tests/test_oracle_pins.py.  No function here is unpinned, except that
+nothing fixes the numeric values of scores on trained models (the paper prints
+none): that part is "parity unpinned" by necessity.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------
+# model container
+# --------------------------------------------------------------------------
+@dataclass
+class OracleModel:
+    n_layers: int
+    d_model: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    d_ffn: int
+    vocab: int
+    rope_base: float
+    rms_eps: float
+    layers: List[dict]        # each: wq wk wv wo w_gate w_up w_down ([out][in]), g_attn g_ffn
+    g_final: np.ndarray
+    w_lm: np.ndarray          # [vocab][d]
+
+    @staticmethod
+    def from_shape(shape, weights: dict) -> "OracleModel":
+        return OracleModel(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads,
+                           shape.head_dim, shape.d_ffn, shape.vocab, float(shape.rope_base),
+                           float(shape.rms_eps), weights["layers"], weights["g_final"], weights["w_lm"])
+
+
+def linear(x: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """y = x W^T with W stored [out][in]; float64."""
+    return np.matmul(np.asarray(x, F64), np.asarray(w, F64).T)
+
+
+# --------------------------------------------------------------------------
+# decoder-layer pieces
+# --------------------------------------------------------------------------
+def rmsnorm(x: np.ndarray, g: np.ndarray, eps: float) -> np.ndarray:
+    x = np.asarray(x, F64)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * np.asarray(g, F64)
+
+
+def rope_rotate(x: np.ndarray, angle_pos: np.ndarray, base: float) -> np.ndarray:
+    """Rotate vectors x[n][heads][head_dim] by the rotary angles of `angle_pos[n]`.
+
+    Pair i couples elements (i, i + head_dim/2); its angle is pos * base^(-2i/head_dim).
+    `angle_pos` may be negative or a difference of positions: rotations compose
+    additively, which is what moving a key from an old to a new position uses.
+    """
+    x = np.asarray(x, F64)
+    dh = x.shape[-1]
+    half = dh // 2
+    theta = np.asarray(base, F64) ** (-2.0 * np.arange(half, dtype=F64) / dh)
+    ang = np.asarray(angle_pos, F64)[:, None] * theta[None, :]          # [n][half]
+    c, s = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+    x1, x2 = x[..., :half], x[..., half:]
+    return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
+
+
+def causal_gqa_attention(q: np.ndarray, q_pos: np.ndarray, k_cache: np.ndarray,
+                         v_cache: np.ndarray) -> np.ndarray:
+    """Attention of arbitrary query rows over a cache whose row index is the position.
+
+    q[n][Hq][dh] at positions q_pos[n]; k_cache, v_cache [T][Hkv][dh].  Query
+    head i reads KV head i // (Hq/Hkv).  A query at position p sees rows 0..p.
+    Returns [n][Hq][dh].
+    """
+    n, hq, dh = q.shape
+    t, hkv, _ = k_cache.shape
+    g = hq // hkv
+    visible = np.arange(t)[None, :] <= np.asarray(q_pos)[:, None]       # [n][T]
+    out = np.empty((n, hq, dh), F64)
+    for h in range(hq):
+        kh, vh = k_cache[:, h // g, :], v_cache[:, h // g, :]
+        s = np.matmul(q[:, h, :], kh.T) / np.sqrt(F64(dh))
+        s = np.where(visible, s, -np.inf)
+        s = s - np.max(s, axis=-1, keepdims=True)
+        p = np.exp(s)
+        p = p / np.sum(p, axis=-1, keepdims=True)
+        out[:, h, :] = np.matmul(p, vh)
+    return out
+
+
+def silu(x: np.ndarray) -> np.ndarray:
+    return x / (1.0 + np.exp(-x))
+
+
+def decoder_layer(m: OracleModel, l: int, h: np.ndarray, pos: np.ndarray,
+                  k_cache: np.ndarray, v_cache: np.ndarray, rope_shift: int = 0) -> np.ndarray:
+    """One pre-norm decoder layer on the rows h[n][d] sitting at positions pos[n].
+
+    The rows' fresh K (rotated to `pos`) and V are written into the layer's cache
+    first; then every row attends over cache rows 0..its own position.
+    k_cache / v_cache [T][Hkv][dh] are updated in place.  Returns the new h.
+    `rope_shift` adds a constant to the rotary positions only (cache rows and the
+    causal mask still use `pos`); it exists to state shift invariance in a test.
+    """
+    w = m.layers[l]
+    n = h.shape[0]
+    a = rmsnorm(h, w["g_attn"], m.rms_eps)
+    q = linear(a, w["wq"]).reshape(n, m.n_q_heads, m.head_dim)
+    k = linear(a, w["wk"]).reshape(n, m.n_kv_heads, m.head_dim)
+    v = linear(a, w["wv"]).reshape(n, m.n_kv_heads, m.head_dim)
+    q = rope_rotate(q, pos + rope_shift, m.rope_base)
+    k = rope_rotate(k, pos + rope_shift, m.rope_base)
+    k_cache[pos] = k
+    v_cache[pos] = v
+    o = causal_gqa_attention(q, pos, k_cache, v_cache).reshape(n, m.n_q_heads * m.head_dim)
+    h = h + linear(o, w["wo"])
+    f = rmsnorm(h, w["g_ffn"], m.rms_eps)
+    h = h + linear(silu(linear(f, w["w_gate"])) * linear(f, w["w_up"]), w["w_down"])
+    return h
+
+
+def first_token_logits(m: OracleModel, h_last: np.ndarray) -> np.ndarray:
+    return linear(rmsnorm(h_last, m.g_final, m.rms_eps), m.w_lm)
+
+
+# --------------------------------------------------------------------------
+# FULL baseline and the earlier agent's record
+# --------------------------------------------------------------------------
+@dataclass
+class PrefillResult:
+    k_cache: np.ndarray       # [L][T][Hkv][dh] keys rotated to their positions
+    v_cache: np.ndarray       # [L][T][Hkv][dh]
+    k_pre_rope: np.ndarray    # [L][T][Hkv][dh] keys before rotation
+    h_in: np.ndarray          # [L+1][T][d]: h_in[l] enters layer l; h_in[L] leaves the last
+    logits: np.ndarray        # [vocab] from the last position
+
+
+def full_prefill(m: OracleModel, x: np.ndarray, pos0: int = 0) -> PrefillResult:
+    """FULL baseline: every token of x[T][d] runs through every layer, causally.
+
+    `pos0` shifts every rotary position by a constant (default 0)."""
+    x = np.asarray(x, F64)
+    t = x.shape[0]
+    pos = np.arange(t)
+    shape = (m.n_layers, t, m.n_kv_heads, m.head_dim)
+    kc, vc, kpre = np.zeros(shape, F64), np.zeros(shape, F64), np.zeros(shape, F64)
+    h_in = np.empty((m.n_layers + 1, t, m.d_model), F64)
+    h = x
+    for l in range(m.n_layers):
+        h_in[l] = h
+        a = rmsnorm(h, m.layers[l]["g_attn"], m.rms_eps)
+        kpre[l][pos] = linear(a, m.layers[l]["wk"]).reshape(t, m.n_kv_heads, m.head_dim)
+        h = decoder_layer(m, l, h, pos, kc[l], vc[l], rope_shift=pos0)
+    h_in[m.n_layers] = h
+    return PrefillResult(kc, vc, kpre, h_in, first_token_logits(m, h[-1]))
+
+
+@dataclass
+class SegmentRecord:
+    """What the earlier agent's cache manager keeps for the shared segment."""
+    k: np.ndarray             # [L][S][Hkv][dh]: pre-RoPE keys, or keys rotated at old positions
+    v: np.ndarray             # [L][S][Hkv][dh]
+    h_start: np.ndarray       # [S][d] hidden states entering layer l_start
+    k_is_pre_rope: bool
+    old_start_pos: int        # position of the segment's first token in the earlier run
+
+
+def decode_record(m: OracleModel, x_alt: np.ndarray, x_seg: np.ndarray, l_start: int,
+                  k_is_pre_rope: bool = True) -> SegmentRecord:
+    """The segment record of an earlier agent that saw `x_alt` before the segment.
+
+    Under causal attention the K/V and hidden state of a token depend only on
+    the tokens before it, so token-by-token decoding and a prefill of
+    [x_alt ; x_seg] give the same segment rows.
+    """
+    n_alt = x_alt.shape[0]
+    r = full_prefill(m, np.concatenate([np.asarray(x_alt, F64), np.asarray(x_seg, F64)], axis=0))
+    k = r.k_pre_rope if k_is_pre_rope else r.k_cache
+    return SegmentRecord(k[:, n_alt:].copy(), r.v_cache[:, n_alt:].copy(),
+                         r.h_in[l_start][n_alt:].copy(), k_is_pre_rope, n_alt)
+
+
+# --------------------------------------------------------------------------
+# scoring and selection
+# --------------------------------------------------------------------------
+def vdev_score(v_reuse: np.ndarray, v_full: np.ndarray) -> np.ndarray:
+    """Eq. (1): d_j = 1 - (1/H) sum_h cos(v_reuse[j][h], v_full[j][h]); inputs [S][H][dh]."""
+    a, b = np.asarray(v_reuse, F64), np.asarray(v_full, F64)
+    dot = np.sum(a * b, axis=-1)
+    na = np.sqrt(np.sum(a * a, axis=-1))
+    nb = np.sqrt(np.sum(b * b, axis=-1))
+    cos = dot / np.maximum(na * nb, 1e-12)
+    return 1.0 - np.mean(cos, axis=-1)
+
+
+def layer_similarity(d_jl: np.ndarray) -> np.ndarray:
+    """Eq. (2): s_l = mean_j (1 - d_{j,l}); d_jl is [S][L]."""
+    return np.mean(1.0 - np.asarray(d_jl, F64), axis=0)
+
+
+def topk_select(score: Sequence[float], k: int) -> np.ndarray:
+    """Indices of the k largest scores, equal scores resolved to the lower index; ascending."""
+    score = np.asarray(score)
+    order = np.lexsort((np.arange(score.shape[0]), -score))      # by -score, then by index
+    return np.sort(order[:k]).astype(np.int32)
+
+
+def threshold_select(score: Sequence[float], tau: float) -> np.ndarray:
+    """Eq. (5) / Eq. (7): {j : score_j >= tau * mean(score)}; ascending."""
+    score = np.asarray(score, F64)
+    return np.nonzero(score >= tau * np.mean(score))[0].astype(np.int32)
+
+
+def final_selection(s_dev: Sequence[float], s_inf: Optional[Sequence[float]], tau_dev: float,
+                    tau_inf: float, k_suf: int) -> np.ndarray:
+    """Eq. (5)-(10): I_dev united with I_inf-score and the last k_suf tokens; ascending."""
+    n = len(s_dev)
+    chosen = set(threshold_select(s_dev, tau_dev).tolist())
+    if s_inf is not None:
+        chosen |= set(threshold_select(s_inf, tau_inf).tolist())
+    chosen |= set(range(max(0, n - k_suf), n))
+    return np.array(sorted(chosen), dtype=np.int32)
+
+
+def reuse_rate(n_layers: int, n_seg: int, l_start: int, l_det: int, l_end: int, k: int) -> float:
+    """Fraction of the segment's KV entries kept as they came from the earlier agent."""
+    recomputed = (l_det - l_start) * n_seg + (l_end - l_det + 1) * k
+    return 1.0 - recomputed / float(n_layers * n_seg)
+
+
+# --------------------------------------------------------------------------
+# the selective-recompute prefill
+# --------------------------------------------------------------------------
+@dataclass
+class RelayResult:
+    k_cache: np.ndarray       # [L][T][Hkv][dh], T = P + S + n_suffix
+    v_cache: np.ndarray
+    sel_idx: np.ndarray       # selected segment indices, ascending (int32)
+    score: Optional[np.ndarray]   # [S] deviation at l_det (None when k = 0)
+    logits: np.ndarray        # [vocab]
+    active_rows: List[int]    # rows run in each layer (for accounting)
+
+
+def relay_prefill(m: OracleModel, x_prefix: np.ndarray, seg: SegmentRecord, l_start: int,
+                  l_det: int, l_end: int, k: int, x_suffix: Optional[np.ndarray] = None,
+                  forced_idx: Optional[Sequence[int]] = None) -> RelayResult:
+    """Prefill of [x_prefix ; segment ; x_suffix] that takes over the segment's KV.
+
+    1. every layer: reused keys moved to positions P..P+S-1, values copied;
+    2. new tokens (prefix, suffix) run through every layer;
+    3. layers [l_start, l_det): all S segment tokens recomputed from seg.h_start;
+    4. at l_det: fresh values of all S tokens -> Eq. (1) score -> top-k;
+    5. layers [l_det, l_end]: only the selected tokens (and the logits-carrying
+       last token when there is no suffix) are recomputed, their K/V rows written
+       back before that layer's attention;
+    6. layers > l_end: only new tokens (and that last token) continue.
+    `forced_idx` replaces the top-k result (the score is still computed).
+    """
+    assert 0 <= l_start < l_det <= l_end < m.n_layers
+    x_prefix = np.asarray(x_prefix, F64)
+    p, s = x_prefix.shape[0], seg.v.shape[1]
+    n_suf = 0 if x_suffix is None else x_suffix.shape[0]
+    t = p + s + n_suf
+    assert 0 <= k <= s
+    shape = (m.n_layers, t, m.n_kv_heads, m.head_dim)
+    kc, vc = np.zeros(shape, F64), np.zeros(shape, F64)
+
+    # 1. take over the segment: keys re-rotated to the new positions, values as they are
+    seg_pos = p + np.arange(s)
+    for l in range(m.n_layers):
+        if seg.k_is_pre_rope:
+            kc[l][seg_pos] = rope_rotate(seg.k[l], seg_pos, m.rope_base)
+        else:
+            old_pos = seg.old_start_pos + np.arange(s)
+            kc[l][seg_pos] = rope_rotate(seg.k[l], seg_pos - old_pos, m.rope_base)
+        vc[l][seg_pos] = np.asarray(seg.v[l], F64)
+
+    h_pre = x_prefix
+    pos_pre = np.arange(p)
+    h_suf = np.zeros((0, m.d_model), F64) if n_suf == 0 else np.asarray(x_suffix, F64)
+    pos_suf = p + s + np.arange(n_suf)
+    carries_logits = n_suf == 0           # last segment token stands in for a suffix
+
+    seg_rows = np.zeros(0, dtype=np.int64)        # segment indices active in the current layer
+    h_seg = np.zeros((0, m.d_model), F64)
+    score = None
+    sel = np.zeros(0, dtype=np.int32)
+    active_rows = []
+
+    for l in range(m.n_layers):
+        if l == l_start:
+            if k > 0:
+                seg_rows = np.arange(s)
+                h_seg = np.asarray(seg.h_start, F64).copy()
+            elif carries_logits:
+                seg_rows = np.array([s - 1])
+                h_seg = np.asarray(seg.h_start, F64)[s - 1:s].copy()
+        if l == l_det and k > 0:
+            w = m.layers[l]
+            v_fresh = linear(rmsnorm(h_seg, w["g_attn"], m.rms_eps), w["wv"])
+            v_fresh = v_fresh.reshape(s, m.n_kv_heads, m.head_dim)
+            score = vdev_score(vc[l][seg_pos], v_fresh)
+            sel = topk_select(score, k) if forced_idx is None else np.sort(np.asarray(forced_idx, np.int32))
+            keep = set(sel.tolist())
+            if carries_logits:
+                keep.add(s - 1)
+            keep = np.array(sorted(keep), dtype=np.int64)
+            h_seg, seg_rows = h_seg[keep], keep
+        if l == l_end + 1:
+            if carries_logits:
+                h_seg, seg_rows = h_seg[-1:], seg_rows[-1:]       # s-1 is the largest index
+            else:
+                h_seg, seg_rows = h_seg[:0], seg_rows[:0]
+
+        h_all = np.concatenate([h_pre, h_seg, h_suf], axis=0)
+        pos_all = np.concatenate([pos_pre, p + seg_rows, pos_suf]).astype(np.int64)
+        active_rows.append(int(h_all.shape[0]))
+        h_all = decoder_layer(m, l, h_all, pos_all, kc[l], vc[l])
+        n_seg_rows = seg_rows.shape[0]
+        h_pre = h_all[:p]
+        h_seg = h_all[p:p + n_seg_rows]
+        h_suf = h_all[p + n_seg_rows:]
+
+    h_last = h_suf[-1] if n_suf > 0 else h_seg[-1]
+    return RelayResult(kc, vc, sel, score, first_token_logits(m, h_last), active_rows)
