@@ -1,0 +1,236 @@
+/*
+ * relaycache.h -- C ABI of the MI355X (gfx950) selective-recompute prefill.
+ *
+ * The library implements the prefill side of RelayCaching (Section 4; Figure
+ * "Overview of RelayCaching", item 3): a later agent takes over the KV cache
+ * that an earlier agent produced for a shared segment, moves the reused keys
+ * to their new positions, recomputes the layers [l_start, l_det) for every
+ * segment token from cached hidden states, scores each token's value
+ * deviation at l_det (Eq. 1), picks a budget of k tokens, recomputes only
+ * those tokens through [l_det, l_end], writes their K/V rows back into a paged
+ * cache and returns first-token logits.
+ *
+ * General conventions
+ *   - Structs are host memory and are only read during the call.  Every data
+ *     pointer inside them is DEVICE memory owned by the caller unless the field
+ *     comment says "host".  The library never frees or keeps caller memory.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and is asynchronous: outputs are valid after the
+ *     caller synchronises the stream.
+ *   - Argument errors are detected on the host before anything is launched and
+ *     reported as a negative rc_status; nothing aborts or throws across the ABI.
+ *   - Element type `T` is float (RC_F32) or bfloat16 (RC_BF16).  RC_BF16 needs
+ *     head_dim == 128; RC_F32 needs head_dim <= 128 and a multiple of 4.
+ *   - Weights are row-major [out][in]: y = x W^T.
+ *   - One layer's K (or V) pool is [n_blocks][n_kv_heads][block_size][head_dim]
+ *     of T.  Position p of sequence s lives in block block_table[s][p / block_size]
+ *     at slot p % block_size.  A contiguous cache is the special case of one
+ *     block per sequence with block_size >= sequence length.
+ *   - Block-table entries outside [0, n_blocks) are clamped by the kernels
+ *     (wrong data, never a wild access).
+ */
+#ifndef RELAYCACHE_H
+#define RELAYCACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RC_API __attribute__((visibility("default")))
+
+typedef enum {
+  RC_OK = 0,
+  RC_E_INVALID_ARG = -1, /* null pointer, negative size, inconsistent shape, bad layer triple */
+  RC_E_UNSUPPORTED = -2, /* valid request the kernels do not cover (e.g. head_dim) */
+  RC_E_WORKSPACE = -3,   /* workspace pointer null/misaligned or too small */
+  RC_E_HIP = -4,         /* a HIP runtime call failed */
+  RC_E_CAPACITY = -5     /* too many requests in one call, sequence longer than its block table */
+} rc_status;
+
+typedef enum { RC_F32 = 0, RC_BF16 = 1 } rc_dtype;
+
+#define RC_MAX_REQ 32      /* requests per rc_reuse / rc_prefill call */
+#define RC_MAX_LAYERS 128
+
+RC_API const char* rc_status_str(rc_status s);
+/* Library version, and the gfx target the kernels were compiled for ("gfx950"). */
+RC_API const char* rc_build_info(void);
+
+/* ------------------------------------------------------------------ model */
+
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rope_base; /* rotary base; pair i of a head couples elements (i, i+head_dim/2) */
+  float rms_eps;
+  int32_t dtype;   /* rc_dtype of weights, activations handed in, and KV pools */
+} rc_model_desc;
+
+typedef struct {
+  const void *wq, *wk, *wv; /* [Hq*dh][d], [Hkv*dh][d], [Hkv*dh][d] of T */
+  const void *wo;           /* [d][Hq*dh] */
+  const void *w_gate, *w_up;/* [F][d] */
+  const void *w_down;       /* [d][F] */
+  const void *g_attn, *g_ffn; /* RMSNorm gains [d] of T */
+} rc_layer_w;
+
+typedef struct rc_model rc_model;
+
+/* Records shapes and weight pointers (no copy; the buffers must outlive the handle).
+ * layers: host array [n_layers].  g_final [d], w_lm_head [vocab][d] of T. */
+RC_API rc_status rc_model_create(const rc_model_desc* desc, const rc_layer_w* layers, const void* g_final,
+                          const void* w_lm_head, rc_model** out);
+RC_API rc_status rc_model_destroy(rc_model* m);
+
+/* --------------------------------------------------------------- KV cache */
+
+typedef struct {
+  void* const* k_pool;        /* host array [n_layers] of device pointers */
+  void* const* v_pool;        /* host array [n_layers] of device pointers */
+  int32_t n_blocks;           /* blocks in every pool */
+  int32_t block_size;         /* tokens per block */
+  const int32_t* block_table; /* device [n_seq][max_blocks_per_seq] */
+  int32_t n_seq;
+  int32_t max_blocks_per_seq;
+} rc_paged_kv;
+
+/* One layer of a paged cache, for the stage-level calls. */
+typedef struct {
+  void* k;
+  void* v;
+  int32_t n_blocks, block_size;
+  const int32_t* block_table; /* device [n_seq][max_blocks_per_seq] */
+  int32_t n_seq, max_blocks_per_seq;
+  int32_t n_kv_heads, head_dim;
+  int32_t dtype;
+} rc_kv_layer;
+
+/* ---------------------------------------------------------------- request */
+
+/* One later-agent prefill: [new prefix ; reused segment ; optional new suffix].
+ * Positions: prefix 0..P-1, segment P..P+S-1, suffix P+S.. */
+typedef struct {
+  int32_t n_prefix;      /* P >= 0 */
+  const void* x_prefix;  /* [P][d] of T: layer-0 inputs of the new prefix */
+  int32_t n_seg;         /* S >= 0 */
+  const void* h_start;   /* [S][d] of T: segment hidden states entering layer l_start, cached by the
+                            earlier agent (Section 4.2, "Start layer") */
+  int32_t n_suffix;      /* tokens after the segment, may be 0 */
+  const void* x_suffix;  /* [n_suffix][d] of T */
+  int32_t src_seq;       /* row of the source block table holding the earlier agent's sequence */
+  int32_t src_offset;    /* position of the segment's first token inside that sequence */
+  int32_t k_is_pre_rope; /* 1: source keys are stored before rotation (Figure "Overview", item 2);
+                            0: they carry the rotation of positions seg_old_start_pos + j */
+  int32_t seg_old_start_pos;
+  int32_t dst_seq;       /* row of the destination block table */
+  const float* s_inf;    /* reserved for influence scores (Eq. 6); must be NULL */
+} rc_request;
+
+typedef struct {
+  int32_t l_start, l_det, l_end; /* 0-based; 0 <= l_start < l_det <= l_end < n_layers.
+                                    h_start is the input of layer l_start; layers [l_start, l_det)
+                                    are recomputed for all S tokens, [l_det, l_end] for selected
+                                    tokens only (both ends included). */
+  const int32_t* k_per_req;      /* host [n_req]: recompute budget as a token count, 0 <= k <= S */
+  const int32_t* forced_idx;     /* device, optional: concatenated per request, k_per_req[b] ascending
+                                    segment indices that replace the top-k result (scores are still
+                                    computed).  NULL: select by score. */
+} rc_plan;
+
+/* Workspace size for rc_reuse with these requests (0 on invalid arguments). */
+RC_API size_t rc_reuse_workspace_bytes(const rc_model* m, const rc_request* reqs, int32_t n_req,
+                                const rc_plan* plan);
+
+/* The selective-recompute prefill (Section 4.2, paragraph after Eq. 4; Eq. 1; Figure "Overview", item 3).
+ *
+ *   src      the earlier agent's cache (read only).  May share pools with dst only if no
+ *            destination row overlaps a source row that is still to be read (not checked).
+ *   dst      in/out: on return rows 0..P+S+n_suffix-1 of every layer of sequence dst_seq hold
+ *            the corrected cache: new tokens' K/V, re-rotated reused K/V, recomputed rows.
+ *   logits   [n_req][vocab] float: logits of the last position of each request.
+ *   sel_idx  [sum k_per_req] int32, per request ascending: the k tokens with the largest
+ *            deviation at l_det, equal scores resolved to the lower index.
+ *   scores   optional [sum n_seg] float: Eq. (1) at l_det for every segment token of every
+ *            request with k > 0 (others untouched); NULL to skip.
+ *   With n_suffix == 0 the last segment token is recomputed from l_start to the last layer in
+ *   addition to the k selected ones (it yields the logits); it is not listed in sel_idx.
+ *   k == 0 for a request skips its dense layers too (pure reuse).
+ *
+ * Errors: RC_E_INVALID_ARG (nulls, triple, k out of range, n_seg == 0 with no new token),
+ * RC_E_CAPACITY (n_req > RC_MAX_REQ, sequence longer than max_blocks_per_seq * block_size,
+ * seq index out of range), RC_E_UNSUPPORTED (s_inf given, dtype/head_dim), RC_E_WORKSPACE. */
+RC_API rc_status rc_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req, const rc_plan* plan,
+                   const rc_paged_kv* src, const rc_paged_kv* dst, float* logits, int32_t* sel_idx,
+                   float* scores, void* workspace, size_t workspace_bytes, void* stream);
+
+/* FULL baseline (Appendix "Baseline Descriptions") and the earlier agent's side: a plain causal
+ * prefill of n_req sequences of new tokens, written into dst.  Optionally records what the cache
+ * manager keeps for later reuse (Figure "Overview", item 2): keys before rotation and the hidden
+ * states entering layer `capture_layer`.
+ *   x[b]        [n_tokens[b]][d] of T (host array of device pointers)
+ *   dst_seq     host [n_req] rows of dst's block table
+ *   k_pre_pool  optional host array [n_layers] of device pools with dst's geometry receiving
+ *               un-rotated keys; NULL to skip
+ *   h_capture   optional host array [n_req] of device [n_tokens[b]][d] of T receiving the hidden
+ *               states entering capture_layer; NULL to skip
+ *   logits      [n_req][vocab] float, last position of each sequence */
+RC_API size_t rc_prefill_workspace_bytes(const rc_model* m, const int32_t* n_tokens, int32_t n_req);
+RC_API rc_status rc_prefill(const rc_model* m, const void* const* x, const int32_t* n_tokens,
+                     const int32_t* dst_seq, int32_t n_req, const rc_paged_kv* dst,
+                     void* const* k_pre_pool, int32_t capture_layer, void* const* h_capture,
+                     float* logits, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------ stage calls
+ * One kernel (family) each, for unit tests and for profiling a stage in isolation. */
+
+/* Scratch the two stage calls below need (request table + rotary table), in bytes. */
+RC_API size_t rc_stage_workspace_bytes(int32_t n_positions, int32_t head_dim);
+
+/* Move n_tokens reused keys of one layer to their new positions and copy the values
+ * (Figure "Overview", item 3, "re-applies RoPE").  Source rows src_offset..; destination rows
+ * dst_offset.. (the new positions).  Pre-RoPE keys are rotated by the new position; rotated keys by
+ * (dst_offset - old_start_pos).  src and dst must have equal n_kv_heads, head_dim, dtype.
+ * workspace: device scratch of rc_stage_workspace_bytes(dst_offset + n_tokens, head_dim). */
+RC_API rc_status rc_rope_rerotate(const rc_kv_layer* src, int32_t src_seq, int32_t src_offset,
+                           const rc_kv_layer* dst, int32_t dst_seq, int32_t dst_offset,
+                           int32_t n_tokens, int32_t k_is_pre_rope, int32_t old_start_pos,
+                           float rope_base, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Eq. (1): score[j] = 1 - mean_h cos(cache V row (offset + j, h), v_fresh[j][h]); H = KV heads;
+ * cos = dot / max(|a||b|, 1e-12).  Accumulated in float; above the floor 1 - cos is evaluated in the
+ * equivalent cancellation-free form 0.5 |a/|a| - b/|b||^2.  v_fresh [n_tokens][Hkv][dh] of T.
+ * workspace: device scratch of rc_stage_workspace_bytes(0, head_dim). */
+RC_API rc_status rc_vdev_score(const void* v_fresh, const rc_kv_layer* cache, int32_t seq, int32_t offset,
+                        int32_t n_tokens, float* score, void* workspace, size_t workspace_bytes,
+                        void* stream);
+
+/* Budget selection: indices of the k largest of score[0..n), equal scores to the lower index,
+ * written ascending to idx_out[k].  n <= 2^20.  NaN scores order above +inf. */
+RC_API rc_status rc_topk(const float* score, int32_t n, int32_t k, int32_t* idx_out, void* stream);
+
+/* Threshold selection (Eq. 5 / Eq. 7): idx_out receives, ascending, every j with
+ * score[j] >= tau * mean(score); *count_out (device int32) their number.  idx_out holds n entries. */
+RC_API rc_status rc_threshold_select(const float* score, int32_t n, float tau, int32_t* idx_out,
+                              int32_t* count_out, void* stream);
+
+/* Causal grouped-query attention of n arbitrary query rows over one layer of a cache
+ * (sparse rectification, Section 4.2): row i (already rotated, at position q_pos[i], ascending)
+ * attends over cache rows 0..q_pos[i] of `seq`.  q, out: [n][Hq][dh] of T. */
+RC_API rc_status rc_sparse_attention(const void* q, const int32_t* q_pos, int32_t n, int32_t n_q_heads,
+                              const rc_kv_layer* cache, int32_t seq, void* out, void* stream);
+
+/* C[M][N] (float) = A[M][K] (T) * W[N][K]^T (T): the gathered-row projection GEMM. */
+RC_API rc_status rc_gemm_rows(int32_t dtype, const void* a, const void* w, float* c, int32_t m, int32_t n,
+                       int32_t k, void* stream);
+
+/* Write n recomputed rows into one layer of a paged cache: k_rows/v_rows [n][Hkv][dh] of T go to
+ * positions pos[i] of `seq` (keys as given, i.e. already rotated). */
+RC_API rc_status rc_scatter_paged(const void* k_rows, const void* v_rows, const int32_t* pos, int32_t n,
+                           const rc_kv_layer* dst, int32_t seq, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RELAYCACHE_H */

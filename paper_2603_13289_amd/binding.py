@@ -1,0 +1,368 @@
+"""ctypes binding of librelaycache.so: argument marshalling only.
+
+Function names match the C ABI in include/relaycache.h.  PyTorch is used for
+device memory and streams; every step of the method runs inside the library's
+HIP kernels.  There is no CPU fallback: if the shared library is missing the
+import of this module fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "librelaycache.so")
+
+RC_OK, RC_E_INVALID_ARG, RC_E_UNSUPPORTED, RC_E_WORKSPACE, RC_E_HIP, RC_E_CAPACITY = 0, -1, -2, -3, -4, -5
+RC_F32, RC_BF16 = 0, 1
+RC_MAX_REQ = 32
+
+EXPORTS = [
+    "rc_status_str", "rc_build_info", "rc_model_create", "rc_model_destroy", "rc_reuse_workspace_bytes",
+    "rc_reuse", "rc_prefill_workspace_bytes", "rc_prefill", "rc_stage_workspace_bytes", "rc_rope_rerotate",
+    "rc_vdev_score", "rc_topk", "rc_threshold_select", "rc_sparse_attention", "rc_gemm_rows",
+    "rc_scatter_paged",
+]
+
+
+class RcError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_str(status)} ({status})")
+
+
+# ------------------------------------------------------------------ C structs
+class rc_model_desc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + \
+               [("rope_base", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32)]
+
+
+class rc_layer_w(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "g_attn", "g_ffn")]
+
+
+class rc_paged_kv(C.Structure):
+    _fields_ = [("k_pool", C.POINTER(C.c_void_p)), ("v_pool", C.POINTER(C.c_void_p)), ("n_blocks", C.c_int32),
+                ("block_size", C.c_int32), ("block_table", C.c_void_p), ("n_seq", C.c_int32),
+                ("max_blocks_per_seq", C.c_int32)]
+
+
+class rc_kv_layer(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("n_blocks", C.c_int32), ("block_size", C.c_int32),
+                ("block_table", C.c_void_p), ("n_seq", C.c_int32), ("max_blocks_per_seq", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("dtype", C.c_int32)]
+
+
+class rc_request(C.Structure):
+    _fields_ = [("n_prefix", C.c_int32), ("x_prefix", C.c_void_p), ("n_seg", C.c_int32), ("h_start", C.c_void_p),
+                ("n_suffix", C.c_int32), ("x_suffix", C.c_void_p), ("src_seq", C.c_int32), ("src_offset", C.c_int32),
+                ("k_is_pre_rope", C.c_int32), ("seg_old_start_pos", C.c_int32), ("dst_seq", C.c_int32),
+                ("s_inf", C.c_void_p)]
+
+
+class rc_plan(C.Structure):
+    _fields_ = [("l_start", C.c_int32), ("l_det", C.c_int32), ("l_end", C.c_int32),
+                ("k_per_req", C.POINTER(C.c_int32)), ("forced_idx", C.c_void_p)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2603_13289_amd.build` "
+                          "(there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    lib.rc_status_str.restype = C.c_char_p
+    lib.rc_status_str.argtypes = [C.c_int]
+    lib.rc_build_info.restype = C.c_char_p
+    lib.rc_build_info.argtypes = []
+    lib.rc_model_create.restype = C.c_int
+    lib.rc_model_create.argtypes = [C.POINTER(rc_model_desc), C.POINTER(rc_layer_w), vp, vp, C.POINTER(vp)]
+    lib.rc_model_destroy.restype = C.c_int
+    lib.rc_model_destroy.argtypes = [vp]
+    lib.rc_reuse_workspace_bytes.restype = sz
+    lib.rc_reuse_workspace_bytes.argtypes = [vp, C.POINTER(rc_request), i32, C.POINTER(rc_plan)]
+    lib.rc_reuse.restype = C.c_int
+    lib.rc_reuse.argtypes = [vp, C.POINTER(rc_request), i32, C.POINTER(rc_plan), C.POINTER(rc_paged_kv),
+                             C.POINTER(rc_paged_kv), vp, vp, vp, vp, sz, vp]
+    lib.rc_prefill_workspace_bytes.restype = sz
+    lib.rc_prefill_workspace_bytes.argtypes = [vp, C.POINTER(i32), i32]
+    lib.rc_prefill.restype = C.c_int
+    lib.rc_prefill.argtypes = [vp, C.POINTER(vp), C.POINTER(i32), C.POINTER(i32), i32, C.POINTER(rc_paged_kv),
+                               C.POINTER(vp), i32, C.POINTER(vp), vp, vp, sz, vp]
+    lib.rc_stage_workspace_bytes.restype = sz
+    lib.rc_stage_workspace_bytes.argtypes = [i32, i32]
+    lib.rc_rope_rerotate.restype = C.c_int
+    lib.rc_rope_rerotate.argtypes = [C.POINTER(rc_kv_layer), i32, i32, C.POINTER(rc_kv_layer), i32, i32, i32, i32,
+                                     i32, C.c_float, vp, sz, vp]
+    lib.rc_vdev_score.restype = C.c_int
+    lib.rc_vdev_score.argtypes = [vp, C.POINTER(rc_kv_layer), i32, i32, i32, vp, vp, sz, vp]
+    lib.rc_topk.restype = C.c_int
+    lib.rc_topk.argtypes = [vp, i32, i32, vp, vp]
+    lib.rc_threshold_select.restype = C.c_int
+    lib.rc_threshold_select.argtypes = [vp, i32, C.c_float, vp, vp, vp]
+    lib.rc_sparse_attention.restype = C.c_int
+    lib.rc_sparse_attention.argtypes = [vp, vp, i32, i32, C.POINTER(rc_kv_layer), i32, vp, vp]
+    lib.rc_gemm_rows.restype = C.c_int
+    lib.rc_gemm_rows.argtypes = [i32, vp, vp, vp, i32, i32, i32, vp]
+    lib.rc_scatter_paged.restype = C.c_int
+    lib.rc_scatter_paged.argtypes = [vp, vp, vp, i32, C.POINTER(rc_kv_layer), i32, vp]
+    return lib
+
+
+lib = _load()
+
+
+def status_str(status: int) -> str:
+    return lib.rc_status_str(status).decode()
+
+
+def build_info() -> str:
+    return lib.rc_build_info().decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != RC_OK:
+        raise RcError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_contiguous(), "tensors handed to the library must be contiguous"
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        if not torch.cuda.is_available():
+            return None          # host-side argument checks need no stream
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def torch_dtype(dtype: int) -> torch.dtype:
+    return torch.bfloat16 if dtype == RC_BF16 else torch.float32
+
+
+def rc_dtype_of(name: str) -> int:
+    return RC_BF16 if name in ("bf16", "bfloat16") else RC_F32
+
+
+# ------------------------------------------------------------------ model
+class Model:
+    """rc_model handle plus the tensors it points into (kept alive here)."""
+
+    def __init__(self, shape, layers: Sequence[dict], g_final: torch.Tensor, w_lm: torch.Tensor):
+        self.shape = shape
+        self.dtype = rc_dtype_of(shape.dtype)
+        self._keep = (layers, g_final, w_lm)
+        desc = rc_model_desc(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                             shape.d_ffn, shape.vocab, float(shape.rope_base), float(shape.rms_eps), self.dtype)
+        arr = (rc_layer_w * len(layers))()
+        for i, lw in enumerate(layers):
+            for name, _ in rc_layer_w._fields_:
+                setattr(arr[i], name, _ptr(lw[name]))
+        handle = C.c_void_p()
+        _check(lib.rc_model_create(C.byref(desc), arr, _ptr(g_final), _ptr(w_lm), C.byref(handle)), "rc_model_create")
+        self.handle = handle
+
+    def close(self) -> None:
+        if self.handle:
+            lib.rc_model_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def rc_model_create(shape, weights: dict, device="cuda") -> Model:
+    """weights: {"layers": [...], "g_final", "w_lm"} of numpy float32 or torch tensors ([out][in])."""
+    td = torch_dtype(rc_dtype_of(shape.dtype))
+
+    def dev(x):
+        t = x if isinstance(x, torch.Tensor) else torch.from_numpy(x)
+        return t.to(device=device, dtype=td).contiguous()
+
+    layers = [{k: dev(v) for k, v in lw.items()} for lw in weights["layers"]]
+    return Model(shape, layers, dev(weights["g_final"]), dev(weights["w_lm"]))
+
+
+# ------------------------------------------------------------------ paged cache
+class PagedKV:
+    """Per-layer K/V pools [n_blocks][Hkv][block_size][dh] plus a block table, on the device."""
+
+    def __init__(self, n_layers: int, n_blocks: int, block_size: int, n_kv_heads: int, head_dim: int, dtype: int,
+                 block_table, device="cuda", fill: Optional[float] = None):
+        td = torch_dtype(dtype)
+        self.n_layers, self.n_blocks, self.block_size = n_layers, n_blocks, block_size
+        self.n_kv_heads, self.head_dim, self.dtype = n_kv_heads, head_dim, dtype
+        shape = (n_blocks, n_kv_heads, block_size, head_dim)
+        mk = (lambda: torch.zeros(shape, dtype=td, device=device)) if fill is None else \
+             (lambda: torch.full(shape, fill, dtype=td, device=device))
+        self.k = [mk() for _ in range(n_layers)]
+        self.v = [mk() for _ in range(n_layers)]
+        self.block_table = torch.as_tensor(block_table, dtype=torch.int32).to(device).contiguous()
+        assert self.block_table.dim() == 2
+        self.n_seq, self.max_blocks = self.block_table.shape
+        self._kp = (C.c_void_p * n_layers)(*[t.data_ptr() for t in self.k])
+        self._vp = (C.c_void_p * n_layers)(*[t.data_ptr() for t in self.v])
+        self.c = rc_paged_kv(C.cast(self._kp, C.POINTER(C.c_void_p)), C.cast(self._vp, C.POINTER(C.c_void_p)),
+                             n_blocks, block_size, self.block_table.data_ptr(), self.n_seq, self.max_blocks)
+
+    @staticmethod
+    def contiguous(n_layers, n_seq, max_len, n_kv_heads, head_dim, dtype, device="cuda", fill=None) -> "PagedKV":
+        table = [[s] for s in range(n_seq)]
+        return PagedKV(n_layers, n_seq, max_len, n_kv_heads, head_dim, dtype, table, device, fill)
+
+    def layer(self, l: int) -> rc_kv_layer:
+        return rc_kv_layer(self.k[l].data_ptr(), self.v[l].data_ptr(), self.n_blocks, self.block_size,
+                           self.block_table.data_ptr(), self.n_seq, self.max_blocks, self.n_kv_heads,
+                           self.head_dim, self.dtype)
+
+    def _index(self, seq: int, n: int, start: int = 0):
+        pos = torch.arange(start, start + n, device=self.block_table.device)
+        blk = self.block_table[seq][pos // self.block_size].long()
+        return blk, pos % self.block_size
+
+    def read(self, which: str, l: int, seq: int, n: int, start: int = 0) -> torch.Tensor:
+        """Rows start..start+n-1 of a sequence as [n][Hkv][dh] (a gather done by torch, for tests)."""
+        pool = (self.k if which == "k" else self.v)[l]
+        blk, slot = self._index(seq, n, start)
+        return pool[blk, :, slot, :]
+
+    def write(self, which: str, l: int, seq: int, rows: torch.Tensor, start: int = 0) -> None:
+        pool = (self.k if which == "k" else self.v)[l]
+        blk, slot = self._index(seq, rows.shape[0], start)
+        pool[blk, :, slot, :] = rows.to(pool.dtype)
+
+
+# ------------------------------------------------------------------ the hot path
+@dataclass
+class Request:
+    x_prefix: Optional[torch.Tensor]          # [P][d]
+    h_start: Optional[torch.Tensor]           # [S][d]
+    x_suffix: Optional[torch.Tensor] = None   # [n_suffix][d]
+    src_seq: int = 0
+    src_offset: int = 0
+    k_is_pre_rope: bool = True
+    seg_old_start_pos: int = 0
+    dst_seq: int = 0
+
+    def c(self) -> rc_request:
+        n = lambda t: 0 if t is None else int(t.shape[0])
+        return rc_request(n(self.x_prefix), _ptr(self.x_prefix), n(self.h_start), _ptr(self.h_start),
+                          n(self.x_suffix), _ptr(self.x_suffix), self.src_seq, self.src_offset,
+                          1 if self.k_is_pre_rope else 0, self.seg_old_start_pos, self.dst_seq, None)
+
+
+@dataclass
+class Plan:
+    l_start: int
+    l_det: int
+    l_end: int
+    k_per_req: List[int]
+    forced_idx: Optional[torch.Tensor] = None     # int32 device, concatenated
+
+    def c(self):
+        ks = (C.c_int32 * len(self.k_per_req))(*self.k_per_req)
+        return rc_plan(self.l_start, self.l_det, self.l_end, C.cast(ks, C.POINTER(C.c_int32)),
+                       _ptr(self.forced_idx)), ks
+
+
+def _req_array(reqs: Sequence[Request]):
+    arr = (rc_request * len(reqs))()
+    for i, r in enumerate(reqs):
+        arr[i] = r.c()
+    return arr
+
+
+def rc_reuse_workspace_bytes(model: Model, reqs: Sequence[Request], plan: Plan) -> int:
+    cplan, _keep = plan.c()
+    return int(lib.rc_reuse_workspace_bytes(model.handle, _req_array(reqs), len(reqs), C.byref(cplan)))
+
+
+def rc_reuse(model: Model, reqs: Sequence[Request], plan: Plan, src: Optional[PagedKV], dst: PagedKV,
+             logits: torch.Tensor, sel_idx: Optional[torch.Tensor], scores: Optional[torch.Tensor],
+             workspace: torch.Tensor, stream=None) -> None:
+    cplan, _keep = plan.c()
+    st = lib.rc_reuse(model.handle, _req_array(reqs), len(reqs), C.byref(cplan),
+                      C.byref(src.c) if src is not None else None, C.byref(dst.c), _ptr(logits), _ptr(sel_idx),
+                      _ptr(scores), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "rc_reuse")
+
+
+def rc_prefill_workspace_bytes(model: Model, n_tokens: Sequence[int]) -> int:
+    arr = (C.c_int32 * len(n_tokens))(*n_tokens)
+    return int(lib.rc_prefill_workspace_bytes(model.handle, arr, len(n_tokens)))
+
+
+def rc_prefill(model: Model, x: Sequence[torch.Tensor], dst_seq: Sequence[int], dst: PagedKV,
+               logits: torch.Tensor, workspace: torch.Tensor, k_pre: Optional[PagedKV] = None,
+               capture_layer: int = -1, h_capture: Optional[Sequence[torch.Tensor]] = None, stream=None) -> None:
+    n = len(x)
+    xs = (C.c_void_p * n)(*[_ptr(t) for t in x])
+    nt = (C.c_int32 * n)(*[int(t.shape[0]) for t in x])
+    ds = (C.c_int32 * n)(*dst_seq)
+    hc = None if h_capture is None else (C.c_void_p * n)(*[_ptr(t) for t in h_capture])
+    st = lib.rc_prefill(model.handle, xs, nt, ds, n, C.byref(dst.c), k_pre.c.k_pool if k_pre is not None else None,
+                        capture_layer, hc, _ptr(logits), _ptr(workspace),
+                        workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "rc_prefill")
+
+
+def alloc_workspace(n_bytes: int, device="cuda") -> torch.Tensor:
+    """Device scratch of at least n_bytes, 256-byte aligned (torch's allocator aligns to 512)."""
+    return torch.empty(max(n_bytes, 256), dtype=torch.uint8, device=device)
+
+
+# ------------------------------------------------------------------ stage calls
+def rc_stage_workspace_bytes(n_positions: int, head_dim: int) -> int:
+    return int(lib.rc_stage_workspace_bytes(n_positions, head_dim))
+
+
+def rc_rope_rerotate(src: rc_kv_layer, src_seq: int, src_offset: int, dst: rc_kv_layer, dst_seq: int,
+                     dst_offset: int, n_tokens: int, k_is_pre_rope: bool, old_start_pos: int, rope_base: float,
+                     workspace: torch.Tensor, stream=None) -> None:
+    _check(lib.rc_rope_rerotate(C.byref(src), src_seq, src_offset, C.byref(dst), dst_seq, dst_offset, n_tokens,
+                                1 if k_is_pre_rope else 0, old_start_pos, rope_base, _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), _stream(stream)), "rc_rope_rerotate")
+
+
+def rc_vdev_score(v_fresh: torch.Tensor, cache: rc_kv_layer, seq: int, offset: int, n_tokens: int,
+                  score: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    _check(lib.rc_vdev_score(_ptr(v_fresh), C.byref(cache), seq, offset, n_tokens, _ptr(score), _ptr(workspace),
+                             workspace.numel() * workspace.element_size(), _stream(stream)), "rc_vdev_score")
+
+
+def rc_topk(score: torch.Tensor, n: int, k: int, idx_out: torch.Tensor, stream=None) -> None:
+    _check(lib.rc_topk(_ptr(score), n, k, _ptr(idx_out), _stream(stream)), "rc_topk")
+
+
+def rc_threshold_select(score: torch.Tensor, n: int, tau: float, idx_out: torch.Tensor, count_out: torch.Tensor,
+                        stream=None) -> None:
+    _check(lib.rc_threshold_select(_ptr(score), n, tau, _ptr(idx_out), _ptr(count_out), _stream(stream)),
+           "rc_threshold_select")
+
+
+def rc_sparse_attention(q: torch.Tensor, q_pos: torch.Tensor, n: int, n_q_heads: int, cache: rc_kv_layer, seq: int,
+                        out: torch.Tensor, stream=None) -> None:
+    _check(lib.rc_sparse_attention(_ptr(q), _ptr(q_pos), n, n_q_heads, C.byref(cache), seq, _ptr(out),
+                                   _stream(stream)), "rc_sparse_attention")
+
+
+def rc_gemm_rows(dtype: int, a: torch.Tensor, w: torch.Tensor, c: torch.Tensor, m: int, n: int, k: int,
+                 stream=None) -> None:
+    _check(lib.rc_gemm_rows(dtype, _ptr(a), _ptr(w), _ptr(c), m, n, k, _stream(stream)), "rc_gemm_rows")
+
+
+def rc_scatter_paged(k_rows: torch.Tensor, v_rows: torch.Tensor, pos: torch.Tensor, n: int, dst: rc_kv_layer,
+                     seq: int, stream=None) -> None:
+    _check(lib.rc_scatter_paged(_ptr(k_rows), _ptr(v_rows), _ptr(pos), n, C.byref(dst), seq, _stream(stream)),
+           "rc_scatter_paged")

@@ -1,0 +1,686 @@
+// C ABI of the selective-recompute prefill: argument checking, workspace carving and the per-layer
+// launch sequence.  All device work is done by the kernels in the sibling files; this file only
+// decides which rows are active in which layer and enqueues launches.
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+using namespace rc;
+
+struct rc_model {
+  rc_model_desc d;
+  std::vector<rc_layer_w> layers;
+  const void* g_final;
+  const void* w_lm;
+};
+
+namespace {
+
+#define RC_HIP(expr)                         \
+  do {                                       \
+    if ((expr) != hipSuccess) return RC_E_HIP; \
+  } while (0)
+#define RC_TRY(expr)               \
+  do {                             \
+    rc_status _s = (expr);         \
+    if (_s != RC_OK) return _s;    \
+  } while (0)
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+inline size_t elem_size(int dtype) { return dtype == RC_BF16 ? 2 : 4; }
+
+rc_status check_desc(const rc_model_desc& d) {
+  if (d.n_layers < 1 || d.d_model < 1 || d.n_q_heads < 1 || d.n_kv_heads < 1 || d.head_dim < 1 ||
+      d.d_ffn < 1 || d.vocab < 1 || !(d.rope_base > 0.f) || !(d.rms_eps >= 0.f))
+    return RC_E_INVALID_ARG;
+  if (d.dtype != RC_F32 && d.dtype != RC_BF16) return RC_E_INVALID_ARG;
+  if (d.n_q_heads % d.n_kv_heads != 0) return RC_E_INVALID_ARG;
+  if (d.n_layers > RC_MAX_LAYERS) return RC_E_CAPACITY;
+  if (d.dtype == RC_BF16 && d.head_dim != 128) return RC_E_UNSUPPORTED;
+  if (d.dtype == RC_F32 && d.head_dim != 64 && d.head_dim != 128) return RC_E_UNSUPPORTED;
+  if (d.d_model % 8 || d.d_ffn % 8) return RC_E_UNSUPPORTED;
+  return RC_OK;
+}
+
+KvGeom geom_of(const rc_paged_kv& kv, const rc_model_desc& d) {
+  KvGeom g;
+  g.n_blocks = kv.n_blocks;
+  g.block_size = kv.block_size;
+  g.block_table = kv.block_table;
+  g.max_blocks = kv.max_blocks_per_seq;
+  g.n_kv_heads = d.n_kv_heads;
+  g.head_dim = d.head_dim;
+  return g;
+}
+
+KvGeom geom_of(const rc_kv_layer& kv) {
+  KvGeom g;
+  g.n_blocks = kv.n_blocks;
+  g.block_size = kv.block_size;
+  g.block_table = kv.block_table;
+  g.max_blocks = kv.max_blocks_per_seq;
+  g.n_kv_heads = kv.n_kv_heads;
+  g.head_dim = kv.head_dim;
+  return g;
+}
+
+rc_status check_paged(const rc_paged_kv* kv, int n_layers) {
+  if (!kv || !kv->k_pool || !kv->v_pool || !kv->block_table) return RC_E_INVALID_ARG;
+  if (kv->n_blocks < 1 || kv->block_size < 1 || kv->n_seq < 1 || kv->max_blocks_per_seq < 1)
+    return RC_E_INVALID_ARG;
+  for (int l = 0; l < n_layers; ++l)
+    if (!kv->k_pool[l] || !kv->v_pool[l]) return RC_E_INVALID_ARG;
+  return RC_OK;
+}
+
+rc_status check_kv_layer(const rc_kv_layer* kv) {
+  if (!kv || !kv->k || !kv->v || !kv->block_table) return RC_E_INVALID_ARG;
+  if (kv->n_blocks < 1 || kv->block_size < 1 || kv->n_seq < 1 || kv->max_blocks_per_seq < 1 ||
+      kv->n_kv_heads < 1)
+    return RC_E_INVALID_ARG;
+  if (kv->dtype != RC_F32 && kv->dtype != RC_BF16) return RC_E_INVALID_ARG;
+  if (kv->dtype == RC_BF16 && kv->head_dim != 128) return RC_E_UNSUPPORTED;
+  if (kv->dtype == RC_F32 && kv->head_dim != 64 && kv->head_dim != 128) return RC_E_UNSUPPORTED;
+  return RC_OK;
+}
+
+// ---------------------------------------------------------------- phases
+// A: layers before l_start; B: dense detect layers; C: sparse rectification; D: after l_end.
+enum Phase : int { PH_A = 0, PH_B = 1, PH_C = 2, PH_D = 3, PH_COUNT = 4 };
+
+struct ReqHost {
+  int P, S, nsuf, k;
+  bool carries_logits;  // no suffix: the last segment token stands in for one
+};
+
+void seg_rows_in(const ReqHost& r, Phase ph, int* mode, int* n) {
+  const int last = (r.carries_logits && r.S > 0) ? 1 : 0;
+  switch (ph) {
+    case PH_A: *mode = SEG_NONE; *n = 0; break;
+    case PH_B:
+      if (r.k > 0) { *mode = SEG_ALL; *n = r.S; }
+      else { *mode = last ? SEG_LAST : SEG_NONE; *n = last; }
+      break;
+    case PH_C:
+      if (r.k > 0) { *mode = SEG_SEL; *n = r.k + last; }
+      else { *mode = last ? SEG_LAST : SEG_NONE; *n = last; }
+      break;
+    default: *mode = last ? SEG_LAST : SEG_NONE; *n = last; break;
+  }
+}
+
+Phase phase_of_layer(int l, int l_start, int l_det, int l_end) {
+  if (l < l_start) return PH_A;
+  if (l < l_det) return PH_B;
+  if (l <= l_end) return PH_C;
+  return PH_D;
+}
+
+int total_rows_in(const std::vector<ReqHost>& rq, Phase ph) {
+  long t = 0;
+  for (const ReqHost& r : rq) {
+    int mode, n;
+    seg_rows_in(r, ph, &mode, &n);
+    t += r.P + n + r.nsuf;
+  }
+  return (int)t;
+}
+
+// fills the phase-dependent fields; `prev` is the table of the phase being left (nullptr at the start)
+void fill_phase(ReqTable* t, const std::vector<ReqHost>& rq, Phase ph, const ReqTable* prev, int tile_rows) {
+  int row = 0, tile = 0;
+  for (size_t b = 0; b < rq.size(); ++b) {
+    ReqDev& r = t->r[b];
+    int mode, n;
+    seg_rows_in(rq[b], ph, &mode, &n);
+    r.seg_mode = mode;
+    r.n_seg_rows = n;
+    r.n_rows = rq[b].P + n + rq[b].nsuf;
+    r.row_base = row;
+    r.tile_base = tile;
+    row += r.n_rows;
+    tile += (r.n_rows + tile_rows - 1) / tile_rows;
+    if (prev) {
+      r.has_old = 1;
+      r.old_row_base = prev->r[b].row_base;
+      r.old_n_seg_rows = prev->r[b].n_seg_rows;
+      r.old_seg_mode = prev->r[b].seg_mode;
+    } else {
+      r.has_old = 0;
+      r.old_row_base = 0;
+      r.old_n_seg_rows = 0;
+      r.old_seg_mode = SEG_NONE;
+    }
+  }
+  t->total_rows = row;
+  t->total_tiles = tile;
+}
+
+// ---------------------------------------------------------------- workspace
+struct Workspace {
+  ReqTable* tables;  // PH_COUNT slots
+  float2* rope_tab;
+  float2* delta_tab;
+  int* row_pos;
+  int* row_req;
+  float* h[2];
+  void* a;       // normalised activations [R][d] of T
+  float* qkv;    // [R][Hq*dh + 2*Hkv*dh]
+  void* q;       // rotated queries [R][Hq*dh] of T
+  void* o;       // attention output [R][Hq*dh] of T
+  void* act;     // SwiGLU output [R][F] of T
+  void* vfresh;  // [R][Hkv*dh] of T
+  float* scores;
+  float* h_last;
+  void* a_last;
+  size_t bytes;
+};
+
+Workspace carve(void* base, const rc_model_desc& d, int max_rows, int max_pos, int n_req, int sum_seg) {
+  Workspace w;
+  size_t off = 0;
+  char* p = reinterpret_cast<char*>(base);
+  auto take = [&](size_t bytes) {
+    void* r = p ? p + off : nullptr;
+    off += align_up(bytes);
+    return r;
+  };
+  const size_t es = elem_size(d.dtype);
+  const size_t R = (size_t)(max_rows > 0 ? max_rows : 1);
+  const size_t nq = (size_t)d.n_q_heads * d.head_dim, nkv = (size_t)d.n_kv_heads * d.head_dim;
+  w.tables = (ReqTable*)take(sizeof(ReqTable) * PH_COUNT);
+  w.rope_tab = (float2*)take(sizeof(float2) * (size_t)(max_pos > 0 ? max_pos : 1) * (d.head_dim / 2));
+  w.delta_tab = (float2*)take(sizeof(float2) * (size_t)n_req * (d.head_dim / 2));
+  w.row_pos = (int*)take(sizeof(int) * R);
+  w.row_req = (int*)take(sizeof(int) * R);
+  w.h[0] = (float*)take(sizeof(float) * R * d.d_model);
+  w.h[1] = (float*)take(sizeof(float) * R * d.d_model);
+  w.a = take(es * R * d.d_model);
+  w.qkv = (float*)take(sizeof(float) * R * (nq + 2 * nkv));
+  w.q = take(es * R * nq);
+  w.o = take(es * R * nq);
+  w.act = take(es * R * d.d_ffn);
+  w.vfresh = take(es * R * nkv);
+  w.scores = (float*)take(sizeof(float) * (size_t)(sum_seg > 0 ? sum_seg : 1));
+  w.h_last = (float*)take(sizeof(float) * (size_t)n_req * d.d_model);
+  w.a_last = take(es * (size_t)n_req * d.d_model);
+  w.bytes = off;
+  return w;
+}
+
+// ---------------------------------------------------------------- the layer engine
+struct Job {
+  const rc_model* m;
+  std::vector<ReqHost> rq;
+  ReqTable base;                  // static per-request fields
+  int l_start, l_det, l_end;      // l_start >= n_layers: plain prefill
+  const rc_paged_kv* src;
+  const rc_paged_kv* dst;
+  void* const* k_pre_pool;
+  int capture_layer;              // -1: none
+  const int32_t* forced_idx;
+  float* logits;
+  int32_t* sel_idx;
+  float* scores_out;
+  int max_pos, sum_seg, max_seg;
+};
+
+template <typename T>
+hipError_t attention_dispatch(const T* q, const int* row_pos, const int* row_req, const ReqTable* table,
+                              int fixed_seq, int total_rows, int total_tiles, const T* k_pool, const T* v_pool,
+                              KvGeom g, int n_q_heads, T* out, hipStream_t st) {
+  return launch_attention<T>(q, row_pos, row_req, table, fixed_seq, total_rows, total_tiles, k_pool, v_pool, g,
+                             n_q_heads, out, st);
+}
+
+template <typename T>
+rc_status run_job(const Job& job, Workspace& w, hipStream_t st) {
+  const rc_model_desc& d = job.m->d;
+  const int n_req = (int)job.rq.size();
+  const int D = d.d_model, nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim, F = d.d_ffn;
+  const int nqkv = nq + 2 * nkv;
+  const int tile_rows = attention_tile_rows(d.dtype, d.n_q_heads, d.n_kv_heads);
+  const KvGeom gd = geom_of(*job.dst, d);
+  const bool has_seg = job.max_seg > 0;
+
+  ReqTable tabs[PH_COUNT];
+  bool uploaded[PH_COUNT] = {false, false, false, false};
+  for (int p = 0; p < PH_COUNT; ++p) tabs[p] = job.base;
+
+  RC_HIP(launch_rope_table(w.rope_tab, job.max_pos, d.head_dim / 2, (double)d.rope_base, st));
+
+  int cur = -1;   // phase whose rows are live in w.h[hbuf]
+  int hbuf = 0;
+  auto enter_phase = [&](Phase ph) -> rc_status {
+    fill_phase(&tabs[ph], job.rq, ph, cur >= 0 ? &tabs[cur] : nullptr, tile_rows);
+    RC_HIP(launch_upload_table(tabs[ph], w.tables + ph, st));
+    uploaded[ph] = true;
+    const int nb = cur >= 0 ? 1 - hbuf : hbuf;
+    RC_HIP(launch_build_rows<T>(w.tables + ph, tabs[ph].total_rows, w.h[hbuf], w.h[nb], w.row_pos, w.row_req,
+                                job.sel_idx, D, st));
+    hbuf = nb;
+    cur = ph;
+    return RC_OK;
+  };
+
+  bool delta_done = false;
+  for (int l = 0; l < d.n_layers; ++l) {
+    const rc_layer_w& lw = job.m->layers[l];
+    const Phase ph = phase_of_layer(l, job.l_start, job.l_det, job.l_end);
+    if (cur < 0 || (ph != cur && ph != PH_C)) RC_TRY(enter_phase(ph));
+
+    // K1: take over the reused rows of this layer (keys to their new positions, values copied)
+    if (has_seg) {
+      const KvGeom gs = geom_of(*job.src, d);
+      if (!delta_done) {
+        RC_HIP(launch_delta_table(w.delta_tab, w.tables + cur, n_req, d.head_dim / 2, (double)d.rope_base, st));
+        delta_done = true;
+      }
+      RC_HIP(launch_rerotate<T>((const T*)job.src->k_pool[l], (const T*)job.src->v_pool[l], gs,
+                                (T*)job.dst->k_pool[l], (T*)job.dst->v_pool[l], gd, w.tables + cur, n_req,
+                                job.max_seg, w.rope_tab, w.delta_tab, st));
+    }
+
+    // detection layer: fresh values of every segment token -> Eq. (1) -> selection
+    if (ph == PH_C && cur != PH_C) {
+      bool any = false;
+      for (const ReqHost& r : job.rq) any = any || r.k > 0;
+      if (any) {
+        const int rows_b = tabs[cur].total_rows;
+        RC_HIP(launch_rmsnorm<T>(w.h[hbuf], (const T*)lw.g_attn, (T*)w.a, rows_b, D, d.rms_eps, st));
+        RC_HIP(launch_gemm<T>((const T*)w.a, (const T*)lw.wv, nullptr, w.vfresh, rows_b, nkv, D, nkv, EPI_STORE_T, st));
+        float* sc = job.scores_out ? job.scores_out : w.scores;
+        RC_HIP(launch_vdev_score<T>((const T*)w.vfresh, nkv, (const T*)job.dst->v_pool[l], gd, w.tables + cur,
+                                    n_req, job.max_seg, sc, st));
+        for (int b = 0; b < n_req; ++b) {
+          const ReqHost& r = job.rq[b];
+          if (r.k <= 0) continue;
+          const int sb = job.base.r[b].sel_base;
+          if (job.forced_idx) RC_HIP(launch_copy_i32(job.forced_idx + sb, job.sel_idx + sb, r.k, st));
+          else RC_HIP(launch_topk(sc + job.base.r[b].score_base, r.S, r.k, job.sel_idx + sb, st));
+        }
+      }
+      RC_TRY(enter_phase(PH_C));
+    }
+
+    const int rows = tabs[cur].total_rows;
+    if (rows == 0) continue;
+    if (l == job.capture_layer) RC_HIP(launch_capture_rows<T>(w.tables + cur, rows, w.h[hbuf], w.row_req, D, st));
+
+    float* h = w.h[hbuf];
+    RC_HIP(launch_rmsnorm<T>(h, (const T*)lw.g_attn, (T*)w.a, rows, D, d.rms_eps, st));
+    RC_HIP(launch_gemm<T>((const T*)w.a, (const T*)lw.wq, nullptr, w.qkv, rows, nq, D, nqkv, EPI_STORE_F32, st));
+    RC_HIP(launch_gemm<T>((const T*)w.a, (const T*)lw.wk, nullptr, w.qkv + nq, rows, nkv, D, nqkv, EPI_STORE_F32, st));
+    RC_HIP(launch_gemm<T>((const T*)w.a, (const T*)lw.wv, nullptr, w.qkv + nq + nkv, rows, nkv, D, nqkv, EPI_STORE_F32, st));
+    // rotary on q/k at the rows' absolute positions; fresh K/V written into the cache before anyone attends
+    RC_HIP(launch_rope_scatter<T>(w.qkv, rows, w.row_pos, w.row_req, w.tables + cur, w.rope_tab, (T*)w.q,
+                                  (T*)job.dst->k_pool[l], (T*)job.dst->v_pool[l],
+                                  job.k_pre_pool ? (T*)job.k_pre_pool[l] : nullptr, gd, d.n_q_heads, st));
+    RC_HIP(attention_dispatch<T>((const T*)w.q, w.row_pos, w.row_req, w.tables + cur, 0, rows,
+                                 tabs[cur].total_tiles, (const T*)job.dst->k_pool[l],
+                                 (const T*)job.dst->v_pool[l], gd, d.n_q_heads, (T*)w.o, st));
+    RC_HIP(launch_gemm<T>((const T*)w.o, (const T*)lw.wo, nullptr, h, rows, D, nq, D, EPI_ADD_F32, st));
+    RC_HIP(launch_rmsnorm<T>(h, (const T*)lw.g_ffn, (T*)w.a, rows, D, d.rms_eps, st));
+    RC_HIP(launch_gemm<T>((const T*)w.a, (const T*)lw.w_gate, (const T*)lw.w_up, w.act, rows, F, D, F, EPI_SWIGLU_T, st));
+    RC_HIP(launch_gemm<T>((const T*)w.act, (const T*)lw.w_down, nullptr, h, rows, D, F, D, EPI_ADD_F32, st));
+  }
+
+  // first-token logits from the last position of each request
+  RC_HIP(launch_gather_last(w.tables + cur, n_req, w.h[hbuf], w.h_last, D, st));
+  RC_HIP(launch_rmsnorm<T>(w.h_last, (const T*)job.m->g_final, (T*)w.a_last, n_req, D, d.rms_eps, st));
+  RC_HIP(launch_gemm<T>((const T*)w.a_last, (const T*)job.m->w_lm, nullptr, job.logits, n_req, d.vocab, D, d.vocab,
+                        EPI_STORE_F32, st));
+  (void)uploaded;
+  return RC_OK;
+}
+
+rc_status check_seq_fits(const rc_paged_kv* kv, int seq, int len) {
+  if (seq < 0 || seq >= kv->n_seq) return RC_E_CAPACITY;
+  if ((long)len > (long)kv->max_blocks_per_seq * kv->block_size) return RC_E_CAPACITY;
+  return RC_OK;
+}
+
+// shared validation of rc_reuse / rc_reuse_workspace_bytes; fills the job's host-side tables
+rc_status prepare_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req, const rc_plan* plan, Job* job) {
+  if (!m || !reqs || !plan) return RC_E_INVALID_ARG;
+  if (n_req < 1) return RC_E_INVALID_ARG;
+  if (n_req > RC_MAX_REQ) return RC_E_CAPACITY;
+  const rc_model_desc& d = m->d;
+  if (!(0 <= plan->l_start && plan->l_start < plan->l_det && plan->l_det <= plan->l_end &&
+        plan->l_end < d.n_layers))
+    return RC_E_INVALID_ARG;
+  if (!plan->k_per_req) return RC_E_INVALID_ARG;
+  job->m = m;
+  job->l_start = plan->l_start;
+  job->l_det = plan->l_det;
+  job->l_end = plan->l_end;
+  job->forced_idx = plan->forced_idx;
+  job->k_pre_pool = nullptr;
+  job->capture_layer = -1;
+  job->rq.clear();
+  job->base = ReqTable();
+  job->base.n_req = n_req;
+  int sel = 0, seg = 0, max_pos = 0, max_seg = 0;
+  for (int b = 0; b < n_req; ++b) {
+    const rc_request& q = reqs[b];
+    const int k = plan->k_per_req[b];
+    if (q.n_prefix < 0 || q.n_seg < 0 || q.n_suffix < 0) return RC_E_INVALID_ARG;
+    if (q.n_prefix + q.n_seg + q.n_suffix < 1) return RC_E_INVALID_ARG;
+    if (q.n_prefix > 0 && !q.x_prefix) return RC_E_INVALID_ARG;
+    if (q.n_seg > 0 && !q.h_start) return RC_E_INVALID_ARG;
+    if (q.n_suffix > 0 && !q.x_suffix) return RC_E_INVALID_ARG;
+    if (k < 0 || k > q.n_seg) return RC_E_INVALID_ARG;
+    if (q.s_inf) return RC_E_UNSUPPORTED;
+    if (q.src_offset < 0 || q.seg_old_start_pos < 0) return RC_E_INVALID_ARG;
+    ReqHost h;
+    h.P = q.n_prefix; h.S = q.n_seg; h.nsuf = q.n_suffix; h.k = k;
+    h.carries_logits = q.n_suffix == 0;
+    job->rq.push_back(h);
+    ReqDev& r = job->base.r[b];
+    r.P = h.P; r.S = h.S; r.nsuf = h.nsuf; r.k = k;
+    r.dst_seq = q.dst_seq; r.src_seq = q.src_seq; r.src_offset = q.src_offset;
+    r.k_is_pre_rope = q.k_is_pre_rope ? 1 : 0;
+    r.rot_delta = q.n_prefix - q.seg_old_start_pos;
+    r.sel_base = sel; r.score_base = seg;
+    r.x_prefix = q.x_prefix; r.h_start = q.h_start; r.x_suffix = q.x_suffix; r.h_capture = nullptr;
+    sel += k; seg += q.n_seg;
+    max_pos = std::max(max_pos, q.n_prefix + q.n_seg + q.n_suffix);
+    max_seg = std::max(max_seg, q.n_seg);
+  }
+  job->max_pos = max_pos;
+  job->sum_seg = seg;
+  job->max_seg = max_seg;
+  return RC_OK;
+}
+
+int max_rows_of(const Job& job) {
+  int r = 0;
+  for (int p = 0; p < PH_COUNT; ++p) r = std::max(r, total_rows_in(job.rq, (Phase)p));
+  return r;
+}
+
+}  // namespace
+
+// =================================================================== exported functions
+extern "C" {
+
+const char* rc_status_str(rc_status s) {
+  switch (s) {
+    case RC_OK: return "ok";
+    case RC_E_INVALID_ARG: return "invalid argument";
+    case RC_E_UNSUPPORTED: return "unsupported configuration";
+    case RC_E_WORKSPACE: return "workspace missing, misaligned or too small";
+    case RC_E_HIP: return "HIP runtime error";
+    case RC_E_CAPACITY: return "capacity exceeded";
+    default: return "unknown status";
+  }
+}
+
+const char* rc_build_info(void) { return "relaycache 0.1 (gfx950, wave64)"; }
+
+rc_status rc_model_create(const rc_model_desc* desc, const rc_layer_w* layers, const void* g_final,
+                          const void* w_lm_head, rc_model** out) {
+  if (!desc || !layers || !g_final || !w_lm_head || !out) return RC_E_INVALID_ARG;
+  RC_TRY(check_desc(*desc));
+  for (int l = 0; l < desc->n_layers; ++l) {
+    const rc_layer_w& w = layers[l];
+    if (!w.wq || !w.wk || !w.wv || !w.wo || !w.w_gate || !w.w_up || !w.w_down || !w.g_attn || !w.g_ffn)
+      return RC_E_INVALID_ARG;
+  }
+  rc_model* m = new (std::nothrow) rc_model();
+  if (!m) return RC_E_CAPACITY;
+  m->d = *desc;
+  m->layers.assign(layers, layers + desc->n_layers);
+  m->g_final = g_final;
+  m->w_lm = w_lm_head;
+  *out = m;
+  return RC_OK;
+}
+
+rc_status rc_model_destroy(rc_model* m) {
+  delete m;
+  return RC_OK;
+}
+
+size_t rc_reuse_workspace_bytes(const rc_model* m, const rc_request* reqs, int32_t n_req, const rc_plan* plan) {
+  Job job;
+  if (prepare_reuse(m, reqs, n_req, plan, &job) != RC_OK) return 0;
+  return carve(nullptr, m->d, max_rows_of(job), job.max_pos, n_req, job.sum_seg).bytes;
+}
+
+rc_status rc_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req, const rc_plan* plan,
+                   const rc_paged_kv* src, const rc_paged_kv* dst, float* logits, int32_t* sel_idx, float* scores,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+  Job job;
+  RC_TRY(prepare_reuse(m, reqs, n_req, plan, &job));
+  RC_TRY(check_paged(dst, m->d.n_layers));
+  if (!logits) return RC_E_INVALID_ARG;
+  int sum_k = 0;
+  for (const ReqHost& r : job.rq) sum_k += r.k;
+  if (sum_k > 0 && !sel_idx) return RC_E_INVALID_ARG;
+  if (job.max_seg > 0) RC_TRY(check_paged(src, m->d.n_layers));
+  for (int b = 0; b < n_req; ++b) {
+    RC_TRY(check_seq_fits(dst, reqs[b].dst_seq, reqs[b].n_prefix + reqs[b].n_seg + reqs[b].n_suffix));
+    if (reqs[b].n_seg > 0) RC_TRY(check_seq_fits(src, reqs[b].src_seq, reqs[b].src_offset + reqs[b].n_seg));
+  }
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RC_E_WORKSPACE;
+  Workspace w = carve(workspace, m->d, max_rows_of(job), job.max_pos, n_req, job.sum_seg);
+  if (w.bytes > workspace_bytes) return RC_E_WORKSPACE;
+  job.src = src;
+  job.dst = dst;
+  job.logits = logits;
+  job.sel_idx = sel_idx;
+  job.scores_out = scores;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  return m->d.dtype == RC_BF16 ? run_job<bf16>(job, w, st) : run_job<float>(job, w, st);
+}
+
+static rc_status prepare_prefill(const rc_model* m, const void* const* x, const int32_t* n_tokens,
+                                 const int32_t* dst_seq, int32_t n_req, void* const* h_capture, Job* job) {
+  if (!m || !n_tokens) return RC_E_INVALID_ARG;
+  if (n_req < 1) return RC_E_INVALID_ARG;
+  if (n_req > RC_MAX_REQ) return RC_E_CAPACITY;
+  job->m = m;
+  job->l_start = job->l_det = job->l_end = m->d.n_layers;   // every layer is a "before l_start" layer
+  job->forced_idx = nullptr;
+  job->rq.clear();
+  job->base = ReqTable();
+  job->base.n_req = n_req;
+  int max_pos = 0;
+  for (int b = 0; b < n_req; ++b) {
+    if (n_tokens[b] < 1) return RC_E_INVALID_ARG;
+    if (x && !x[b]) return RC_E_INVALID_ARG;
+    ReqHost h;
+    h.P = n_tokens[b]; h.S = 0; h.nsuf = 0; h.k = 0; h.carries_logits = false;
+    job->rq.push_back(h);
+    ReqDev& r = job->base.r[b];
+    r.P = h.P;
+    r.dst_seq = dst_seq ? dst_seq[b] : 0;
+    r.x_prefix = x ? x[b] : nullptr;
+    r.h_capture = h_capture ? h_capture[b] : nullptr;
+    max_pos = std::max(max_pos, h.P);
+  }
+  job->max_pos = max_pos;
+  job->sum_seg = 0;
+  job->max_seg = 0;
+  return RC_OK;
+}
+
+size_t rc_prefill_workspace_bytes(const rc_model* m, const int32_t* n_tokens, int32_t n_req) {
+  Job job;
+  if (prepare_prefill(m, nullptr, n_tokens, nullptr, n_req, nullptr, &job) != RC_OK) return 0;
+  return carve(nullptr, m->d, max_rows_of(job), job.max_pos, n_req, 0).bytes;
+}
+
+rc_status rc_prefill(const rc_model* m, const void* const* x, const int32_t* n_tokens, const int32_t* dst_seq,
+                     int32_t n_req, const rc_paged_kv* dst, void* const* k_pre_pool, int32_t capture_layer,
+                     void* const* h_capture, float* logits, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!x || !dst_seq || !logits) return RC_E_INVALID_ARG;
+  Job job;
+  RC_TRY(prepare_prefill(m, x, n_tokens, dst_seq, n_req, h_capture, &job));
+  RC_TRY(check_paged(dst, m->d.n_layers));
+  if (h_capture && (capture_layer < 0 || capture_layer >= m->d.n_layers)) return RC_E_INVALID_ARG;
+  if (k_pre_pool)
+    for (int l = 0; l < m->d.n_layers; ++l)
+      if (!k_pre_pool[l]) return RC_E_INVALID_ARG;
+  for (int b = 0; b < n_req; ++b) RC_TRY(check_seq_fits(dst, dst_seq[b], n_tokens[b]));
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RC_E_WORKSPACE;
+  Workspace w = carve(workspace, m->d, max_rows_of(job), job.max_pos, n_req, 0);
+  if (w.bytes > workspace_bytes) return RC_E_WORKSPACE;
+  job.src = nullptr;
+  job.dst = dst;
+  job.k_pre_pool = k_pre_pool;
+  job.capture_layer = h_capture ? capture_layer : -1;
+  job.logits = logits;
+  job.sel_idx = nullptr;
+  job.scores_out = nullptr;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  return m->d.dtype == RC_BF16 ? run_job<bf16>(job, w, st) : run_job<float>(job, w, st);
+}
+
+// ------------------------------------------------------------------ stage calls
+size_t rc_stage_workspace_bytes(int32_t n_positions, int32_t head_dim) {
+  if (n_positions < 0 || head_dim < 2) return 0;
+  return align_up(sizeof(ReqTable)) + align_up(sizeof(float2) * (size_t)(n_positions + 1) * (head_dim / 2)) +
+         align_up(sizeof(float2) * (size_t)(head_dim / 2));
+}
+
+rc_status rc_rope_rerotate(const rc_kv_layer* src, int32_t src_seq, int32_t src_offset, const rc_kv_layer* dst,
+                           int32_t dst_seq, int32_t dst_offset, int32_t n_tokens, int32_t k_is_pre_rope,
+                           int32_t old_start_pos, float rope_base, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+  RC_TRY(check_kv_layer(src));
+  RC_TRY(check_kv_layer(dst));
+  if (src->n_kv_heads != dst->n_kv_heads || src->head_dim != dst->head_dim || src->dtype != dst->dtype)
+    return RC_E_INVALID_ARG;
+  if (n_tokens < 0 || src_offset < 0 || dst_offset < 0 || old_start_pos < 0 || !(rope_base > 0.f))
+    return RC_E_INVALID_ARG;
+  if (src_seq < 0 || src_seq >= src->n_seq || dst_seq < 0 || dst_seq >= dst->n_seq) return RC_E_CAPACITY;
+  if ((long)src_offset + n_tokens > (long)src->max_blocks_per_seq * src->block_size ||
+      (long)dst_offset + n_tokens > (long)dst->max_blocks_per_seq * dst->block_size)
+    return RC_E_CAPACITY;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RC_E_WORKSPACE;
+  const int n_pos = dst_offset + n_tokens;
+  if (rc_stage_workspace_bytes(n_pos, src->head_dim) > workspace_bytes) return RC_E_WORKSPACE;
+  if (n_tokens == 0) return RC_OK;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  char* p = reinterpret_cast<char*>(workspace);
+  ReqTable* dt = reinterpret_cast<ReqTable*>(p);
+  float2* rope_tab = reinterpret_cast<float2*>(p + align_up(sizeof(ReqTable)));
+  float2* delta_tab = reinterpret_cast<float2*>(p + align_up(sizeof(ReqTable)) +
+                                                align_up(sizeof(float2) * (size_t)(n_pos + 1) * (src->head_dim / 2)));
+  ReqTable t = ReqTable();
+  t.n_req = 1;
+  ReqDev& r = t.r[0];
+  r.P = dst_offset; r.S = n_tokens; r.src_seq = src_seq; r.src_offset = src_offset; r.dst_seq = dst_seq;
+  r.k_is_pre_rope = k_is_pre_rope ? 1 : 0;
+  r.rot_delta = dst_offset - old_start_pos;
+  RC_HIP(launch_upload_table(t, dt, st));
+  const int half = src->head_dim / 2;
+  if (k_is_pre_rope) RC_HIP(launch_rope_table(rope_tab, n_pos, half, (double)rope_base, st));
+  else RC_HIP(launch_delta_table(delta_tab, dt, 1, half, (double)rope_base, st));
+  if (src->dtype == RC_BF16)
+    RC_HIP(launch_rerotate<bf16>((const bf16*)src->k, (const bf16*)src->v, geom_of(*src), (bf16*)dst->k,
+                                 (bf16*)dst->v, geom_of(*dst), dt, 1, n_tokens, rope_tab, delta_tab, st));
+  else
+    RC_HIP(launch_rerotate<float>((const float*)src->k, (const float*)src->v, geom_of(*src), (float*)dst->k,
+                                  (float*)dst->v, geom_of(*dst), dt, 1, n_tokens, rope_tab, delta_tab, st));
+  return RC_OK;
+}
+
+rc_status rc_vdev_score(const void* v_fresh, const rc_kv_layer* cache, int32_t seq, int32_t offset,
+                        int32_t n_tokens, float* score, void* workspace, size_t workspace_bytes, void* stream) {
+  RC_TRY(check_kv_layer(cache));
+  if (!v_fresh || !score || n_tokens < 0 || offset < 0) return RC_E_INVALID_ARG;
+  if (seq < 0 || seq >= cache->n_seq) return RC_E_CAPACITY;
+  if ((long)offset + n_tokens > (long)cache->max_blocks_per_seq * cache->block_size) return RC_E_CAPACITY;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RC_E_WORKSPACE;
+  if (rc_stage_workspace_bytes(0, cache->head_dim) > workspace_bytes) return RC_E_WORKSPACE;
+  if (n_tokens == 0) return RC_OK;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  ReqTable* dt = reinterpret_cast<ReqTable*>(workspace);
+  ReqTable t = ReqTable();
+  t.n_req = 1;
+  ReqDev& r = t.r[0];
+  r.P = offset; r.S = n_tokens; r.dst_seq = seq; r.seg_mode = SEG_ALL;
+  r.row_base = -offset;   // fresh row of token j is j
+  r.score_base = 0;
+  RC_HIP(launch_upload_table(t, dt, st));
+  const int stride = cache->n_kv_heads * cache->head_dim;
+  if (cache->dtype == RC_BF16)
+    RC_HIP(launch_vdev_score<bf16>((const bf16*)v_fresh, stride, (const bf16*)cache->v, geom_of(*cache), dt, 1,
+                                   n_tokens, score, st));
+  else
+    RC_HIP(launch_vdev_score<float>((const float*)v_fresh, stride, (const float*)cache->v, geom_of(*cache), dt, 1,
+                                    n_tokens, score, st));
+  return RC_OK;
+}
+
+rc_status rc_topk(const float* score, int32_t n, int32_t k, int32_t* idx_out, void* stream) {
+  if (n < 0 || k < 0 || k > n) return RC_E_INVALID_ARG;
+  if (n > (1 << 20)) return RC_E_CAPACITY;
+  if (k == 0) return RC_OK;
+  if (!score || !idx_out) return RC_E_INVALID_ARG;
+  RC_HIP(launch_topk(score, n, k, idx_out, reinterpret_cast<hipStream_t>(stream)));
+  return RC_OK;
+}
+
+rc_status rc_threshold_select(const float* score, int32_t n, float tau, int32_t* idx_out, int32_t* count_out,
+                              void* stream) {
+  if (n < 1 || !score || !idx_out || !count_out) return RC_E_INVALID_ARG;
+  if (n > (1 << 20)) return RC_E_CAPACITY;
+  RC_HIP(launch_threshold_select(score, n, tau, idx_out, count_out, reinterpret_cast<hipStream_t>(stream)));
+  return RC_OK;
+}
+
+rc_status rc_sparse_attention(const void* q, const int32_t* q_pos, int32_t n, int32_t n_q_heads,
+                              const rc_kv_layer* cache, int32_t seq, void* out, void* stream) {
+  RC_TRY(check_kv_layer(cache));
+  if (!q || !q_pos || !out || n < 0 || n_q_heads < 1 || n_q_heads % cache->n_kv_heads) return RC_E_INVALID_ARG;
+  if (seq < 0 || seq >= cache->n_seq) return RC_E_CAPACITY;
+  if (n == 0) return RC_OK;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const int tile_rows = attention_tile_rows(cache->dtype, n_q_heads, cache->n_kv_heads);
+  const int tiles = (n + tile_rows - 1) / tile_rows;
+  if (cache->dtype == RC_BF16)
+    RC_HIP(launch_attention<bf16>((const bf16*)q, q_pos, nullptr, nullptr, seq, n, tiles, (const bf16*)cache->k,
+                                  (const bf16*)cache->v, geom_of(*cache), n_q_heads, (bf16*)out, st));
+  else
+    RC_HIP(launch_attention<float>((const float*)q, q_pos, nullptr, nullptr, seq, n, tiles, (const float*)cache->k,
+                                   (const float*)cache->v, geom_of(*cache), n_q_heads, (float*)out, st));
+  return RC_OK;
+}
+
+rc_status rc_gemm_rows(int32_t dtype, const void* a, const void* w, float* c, int32_t m, int32_t n, int32_t k,
+                       void* stream) {
+  if (dtype != RC_F32 && dtype != RC_BF16) return RC_E_INVALID_ARG;
+  if (!a || !w || !c || m < 0 || n < 1 || k < 1) return RC_E_INVALID_ARG;
+  if (k % 8) return RC_E_UNSUPPORTED;
+  if (m == 0) return RC_OK;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (dtype == RC_BF16)
+    RC_HIP(launch_gemm<bf16>((const bf16*)a, (const bf16*)w, nullptr, c, m, n, k, n, EPI_STORE_F32, st));
+  else
+    RC_HIP(launch_gemm<float>((const float*)a, (const float*)w, nullptr, c, m, n, k, n, EPI_STORE_F32, st));
+  return RC_OK;
+}
+
+rc_status rc_scatter_paged(const void* k_rows, const void* v_rows, const int32_t* pos, int32_t n,
+                           const rc_kv_layer* dst, int32_t seq, void* stream) {
+  RC_TRY(check_kv_layer(dst));
+  if (!k_rows || !v_rows || !pos || n < 0) return RC_E_INVALID_ARG;
+  if (seq < 0 || seq >= dst->n_seq) return RC_E_CAPACITY;
+  if (n == 0) return RC_OK;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (dst->dtype == RC_BF16)
+    RC_HIP(launch_scatter_rows<bf16>((const bf16*)k_rows, (const bf16*)v_rows, pos, n, (bf16*)dst->k, (bf16*)dst->v,
+                                     geom_of(*dst), seq, st));
+  else
+    RC_HIP(launch_scatter_rows<float>((const float*)k_rows, (const float*)v_rows, pos, n, (float*)dst->k,
+                                      (float*)dst->v, geom_of(*dst), seq, st));
+  return RC_OK;
+}
+
+}  // extern "C"

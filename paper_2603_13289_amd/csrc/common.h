@@ -1,0 +1,175 @@
+// Shared device/host declarations of the selective-recompute prefill library (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/relaycache.h"
+
+namespace rc {
+
+// ------------------------------------------------------------------ element types
+struct bf16 {
+  uint16_t v;
+};
+
+__host__ __device__ inline float bf16_to_f32(bf16 x) {
+  union { uint32_t u; float f; } c;
+  c.u = (uint32_t)x.v << 16;
+  return c.f;
+}
+// round to nearest, ties to even; NaN stays NaN
+__host__ __device__ inline bf16 f32_to_bf16(float f) {
+  union { uint32_t u; float f; } c;
+  c.f = f;
+  uint32_t u = c.u;
+  bf16 r;
+  if ((u & 0x7fffffffu) > 0x7f800000u) {
+    r.v = (uint16_t)((u >> 16) | 0x0040u);
+  } else {
+    r.v = (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+  }
+  return r;
+}
+
+__device__ inline float to_f32(float x) { return x; }
+__device__ inline float to_f32(bf16 x) { return bf16_to_f32(x); }
+template <typename T> __device__ inline T from_f32(float x);
+template <> __device__ inline float from_f32<float>(float x) { return x; }
+template <> __device__ inline bf16 from_f32<bf16>(float x) { return f32_to_bf16(x); }
+
+// 16-byte vector access: VEC elements of T
+template <typename T> struct Vec16;
+template <> struct Vec16<float> {
+  static constexpr int N = 4;
+  static __device__ inline void load(const float* p, float* out) {
+    const float4 v = *reinterpret_cast<const float4*>(p);
+    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+  }
+  static __device__ inline void store(float* p, const float* in) {
+    *reinterpret_cast<float4*>(p) = make_float4(in[0], in[1], in[2], in[3]);
+  }
+};
+template <> struct Vec16<bf16> {
+  static constexpr int N = 8;
+  static __device__ inline void load(const bf16* p, float* out) {
+    const uint4 v = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      out[2 * i] = __uint_as_float(w[i] << 16);
+      out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+  static __device__ inline void store(bf16* p, const float* in) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      w[i] = (uint32_t)f32_to_bf16(in[2 * i]).v | ((uint32_t)f32_to_bf16(in[2 * i + 1]).v << 16);
+    }
+    *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+
+// ------------------------------------------------------------------ paged cache geometry
+struct KvGeom {
+  int n_blocks, block_size;
+  const int32_t* block_table;  // device [n_seq][max_blocks]
+  int max_blocks;
+  int n_kv_heads, head_dim;
+};
+
+// element offset of (seq, pos, head, 0) inside one layer's pool; positions, table slots and block ids
+// are clamped to the geometry, so bad indices read or write a wrong row but never leave the pool
+__device__ inline size_t kv_row_offset(const KvGeom& g, int seq, int pos, int head) {
+  pos = max(pos, 0);
+  const int bi = min(pos / g.block_size, g.max_blocks - 1);
+  const int slot = min(pos - bi * g.block_size, g.block_size - 1);
+  int blk = g.block_table[(size_t)seq * g.max_blocks + bi];
+  blk = min(max(blk, 0), g.n_blocks - 1);
+  return (((size_t)blk * g.n_kv_heads + head) * g.block_size + slot) * (size_t)g.head_dim;
+}
+
+// ------------------------------------------------------------------ per-request phase table
+enum SegMode : int { SEG_NONE = 0, SEG_ALL = 1, SEG_SEL = 2, SEG_LAST = 3 };
+
+struct ReqDev {
+  int P, S, nsuf, k;
+  int row_base, n_seg_rows, n_rows, seg_mode;           // current phase
+  int old_row_base, old_n_seg_rows, old_seg_mode, has_old;  // phase being left (has_old = 0: inputs)
+  int dst_seq, src_seq, src_offset, rot_delta;           // rot_delta valid when keys are rotated
+  int sel_base, score_base, tile_base, k_is_pre_rope;
+  const void* x_prefix;
+  const void* h_start;
+  const void* x_suffix;
+  void* h_capture;
+};
+
+struct ReqTable {
+  int n_req, total_rows, total_tiles, pad;
+  ReqDev r[RC_MAX_REQ];
+};
+
+// ------------------------------------------------------------------ launchers (host)
+// Every launcher enqueues on `st` and returns hipGetLastError().
+hipError_t launch_upload_table(const ReqTable& host_table, ReqTable* dev_slot, hipStream_t st);
+hipError_t launch_rope_table(float2* tab, int n_pos, int half, double base, hipStream_t st);
+hipError_t launch_delta_table(float2* tab, const ReqTable* table, int n_req, int half, double base,
+                              hipStream_t st);
+
+template <typename T>
+hipError_t launch_rerotate(const T* k_src, const T* v_src, KvGeom gs, T* k_dst, T* v_dst, KvGeom gd,
+                           const ReqTable* table, int n_req, int max_seg, const float2* rope_tab,
+                           const float2* delta_tab, hipStream_t st);
+
+template <typename T>
+hipError_t launch_build_rows(const ReqTable* table, int total_rows, const float* h_old, float* h_new,
+                             int* row_pos, int* row_req, const int* sel_idx, int d, hipStream_t st);
+template <typename T>
+hipError_t launch_capture_rows(const ReqTable* table, int total_rows, const float* h, const int* row_req,
+                               int d, hipStream_t st);
+
+template <typename T>
+hipError_t launch_rmsnorm(const float* h, const T* gain, T* out, int rows, int d, float eps, hipStream_t st);
+
+enum GemmEpilogue : int { EPI_STORE_F32 = 0, EPI_STORE_T = 1, EPI_ADD_F32 = 2, EPI_SWIGLU_T = 3 };
+// C[M][ldc] (op)= A[M][K] * W[N][K]^T ; W2 only for EPI_SWIGLU_T (gate = W, up = W2)
+template <typename T>
+hipError_t launch_gemm(const T* a, const T* w, const T* w2, void* c, int m, int n, int k, int ldc,
+                       GemmEpilogue epi, hipStream_t st);
+
+template <typename T>
+hipError_t launch_rope_scatter(const float* qkv, int n_rows, const int* row_pos, const int* row_req,
+                               const ReqTable* table, const float2* rope_tab, T* q_out, T* k_pool, T* v_pool,
+                               T* k_pre_pool, KvGeom g, int n_q_heads, hipStream_t st);
+
+// Attention of the active rows over one layer of the cache.  With a table, row r belongs to request
+// row_req[r] (sequence table->r[..].dst_seq) and tiles never straddle requests; with table == nullptr
+// all rows belong to sequence `fixed_seq`.
+template <typename T>
+hipError_t launch_attention(const T* q, const int* row_pos, const int* row_req, const ReqTable* table,
+                            int fixed_seq, int total_rows, int total_tiles, const T* k_pool, const T* v_pool,
+                            KvGeom g, int n_q_heads, T* out, hipStream_t st);
+template <typename T>
+hipError_t launch_attention_simt(const T* q, const int* row_pos, const int* row_req, const ReqTable* table,
+                                 int fixed_seq, int total_rows, const T* k_pool, const T* v_pool, KvGeom g,
+                                 int n_q_heads, T* out, hipStream_t st);
+int attention_tile_rows(int dtype, int n_q_heads, int n_kv_heads);  // query rows per attention tile
+
+template <typename T>
+hipError_t launch_vdev_score(const T* v_fresh, int fresh_row_stride, const T* v_pool, KvGeom g,
+                             const ReqTable* table, int n_req, int max_seg, float* scores, hipStream_t st);
+
+hipError_t launch_topk(const float* score, int n, int k, int* idx_out, hipStream_t st);
+hipError_t launch_threshold_select(const float* score, int n, float tau, int* idx_out, int* count_out,
+                                   hipStream_t st);
+hipError_t launch_copy_i32(const int* src, int* dst, int n, hipStream_t st);
+
+template <typename T>
+hipError_t launch_scatter_rows(const T* k_rows, const T* v_rows, const int* pos, int n, T* k_pool,
+                               T* v_pool, KvGeom g, int seq, hipStream_t st);
+
+hipError_t launch_gather_last(const ReqTable* table, int n_req, const float* h, float* out, int d,
+                              hipStream_t st);
+
+}  // namespace rc

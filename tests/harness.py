@@ -1,0 +1,192 @@
+"""Shared helpers of the GPU parity tests: build a seeded case, run the oracle, run the HIP path.
+
+The oracle side and the HIP side only share the seeded inputs (synth/) and the
+earlier agent's segment record, which the oracle produces and which is rounded
+to the workload's storage type once before either side consumes it.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from oracle import relay_oracle as R
+from synth import (WORKLOADS, Workload, budget_to_k, make_block_table, make_hidden, make_weights, ragged_lengths,
+                   round_to_bf16)
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}      # max |x - y| / max |y| per tensor
+
+
+def rel_err(got, want) -> float:
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    return float(np.max(np.abs(got - want)) / max(np.max(np.abs(want)), 1e-30))
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy()
+
+
+def round_store(x: np.ndarray, dtype: str) -> np.ndarray:
+    x = np.asarray(x, np.float32)
+    return round_to_bf16(x) if dtype == "bf16" else x
+
+
+@dataclass
+class ReqCase:
+    P: int
+    S: int
+    A: int
+    xp: np.ndarray
+    xa: np.ndarray
+    xs: np.ndarray
+    xsuf: Optional[np.ndarray]
+    seg: R.SegmentRecord            # record after storage rounding
+    k: int
+
+
+@dataclass
+class Case:
+    w: Workload
+    weights: dict
+    om: R.OracleModel
+    reqs: List[ReqCase]
+
+
+def build_case(name: str, k_override: Optional[int] = None, pre_rope: bool = True, n_suffix: int = 0,
+               l_triple=None, max_req: Optional[int] = None) -> Case:
+    w = WORKLOADS[name]
+    if l_triple is not None:
+        from dataclasses import replace
+        w = replace(w, l_start=l_triple[0], l_det=l_triple[1], l_end=l_triple[2])
+    weights = make_weights(w)
+    om = R.OracleModel.from_shape(w.shape, weights)
+    reqs = []
+    lens = ragged_lengths(w)
+    if max_req is not None:
+        lens = lens[:max_req]
+    for b, (P, S, A) in enumerate(lens):
+        xp = make_hidden(w, "x_prefix", P, b)
+        xa = make_hidden(w, "x_alt", A, b)
+        xs = make_hidden(w, "x_seg", S, b)
+        xsuf = make_hidden(w, "x_suffix", n_suffix, b) if n_suffix else None
+        seg = R.decode_record(om, xa, xs, w.l_start, k_is_pre_rope=pre_rope)
+        dt = w.shape.dtype
+        seg = R.SegmentRecord(round_store(seg.k, dt).astype(np.float64), round_store(seg.v, dt).astype(np.float64),
+                              round_store(seg.h_start, dt).astype(np.float64), pre_rope, A)
+        k = budget_to_k(S, w.budget_pct) if k_override is None else min(k_override, S)
+        reqs.append(ReqCase(P, S, A, xp, xa, xs, xsuf, seg, k))
+    return Case(w, weights, om, reqs)
+
+
+def oracle_relay(case: Case, b: int = 0, forced_idx=None) -> R.RelayResult:
+    rq = case.reqs[b]
+    w = case.w
+    return R.relay_prefill(case.om, rq.xp, rq.seg, w.l_start, w.l_det, w.l_end, rq.k, x_suffix=rq.xsuf,
+                           forced_idx=forced_idx)
+
+
+def selection_margin(score: np.ndarray, k: int) -> float:
+    """Relative gap between the k-th and (k+1)-th largest score (inf when k is 0 or all)."""
+    if k <= 0 or k >= score.shape[0]:
+        return float("inf")
+    s = np.sort(score)[::-1]
+    return float((s[k - 1] - s[k]) / max(abs(s[k - 1]), 1e-300))
+
+
+# ------------------------------------------------------------------ HIP side
+@dataclass
+class HipRun:
+    k_cache: List[List[np.ndarray]]      # [req][layer] -> [T][Hkv][dh]
+    v_cache: List[List[np.ndarray]]
+    logits: np.ndarray                   # [n_req][vocab]
+    sel: List[np.ndarray]
+    scores: List[np.ndarray]
+
+
+def hip_relay(case: Case, forced: Optional[List[np.ndarray]] = None, paged_src: bool = True) -> HipRun:
+    from paper_2603_13289_amd import binding as rc
+    w, sh = case.w, case.w.shape
+    dt = rc.rc_dtype_of(sh.dtype)
+    td = rc.torch_dtype(dt)
+    dev = "cuda"
+    model = rc.rc_model_create(sh, case.weights)
+    n_req = len(case.reqs)
+
+    def up(x):
+        return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(dev).to(td).contiguous()
+
+    # the earlier agents' caches: sequence b holds [alt_b ; seg_b]; only the segment rows are filled
+    src_lens = [r.A + r.S for r in case.reqs]
+    dst_lens = [r.P + r.S + (0 if r.xsuf is None else r.xsuf.shape[0]) for r in case.reqs]
+    if w.block_size > 0:
+        st, sn = make_block_table(src_lens, w.block_size, seed=1)
+        dtab, dn = make_block_table(dst_lens, w.block_size, seed=2)
+        src = rc.PagedKV(sh.n_layers, sn, w.block_size, sh.n_kv_heads, sh.head_dim, dt, st)
+        dst = rc.PagedKV(sh.n_layers, dn, w.block_size, sh.n_kv_heads, sh.head_dim, dt, dtab, fill=7.0)
+    else:
+        src = rc.PagedKV.contiguous(sh.n_layers, n_req, max(src_lens), sh.n_kv_heads, sh.head_dim, dt)
+        dst = rc.PagedKV.contiguous(sh.n_layers, n_req, max(dst_lens), sh.n_kv_heads, sh.head_dim, dt, fill=7.0)
+    reqs = []
+    for b, r in enumerate(case.reqs):
+        for l in range(sh.n_layers):
+            src.write("k", l, b, up(r.seg.k[l]), start=r.A)
+            src.write("v", l, b, up(r.seg.v[l]), start=r.A)
+        reqs.append(rc.Request(up(r.xp) if r.P else None, up(r.seg.h_start), None if r.xsuf is None else up(r.xsuf),
+                               src_seq=b, src_offset=r.A, k_is_pre_rope=r.seg.k_is_pre_rope,
+                               seg_old_start_pos=r.seg.old_start_pos, dst_seq=b))
+    ks = [r.k for r in case.reqs]
+    fidx = None
+    if forced is not None:
+        fidx = torch.from_numpy(np.concatenate([np.asarray(f, np.int32) for f in forced])).to(dev)
+    plan = rc.Plan(w.l_start, w.l_det, w.l_end, ks, fidx)
+    ws = rc.alloc_workspace(rc.rc_reuse_workspace_bytes(model, reqs, plan))
+    logits = torch.zeros((n_req, sh.vocab), dtype=torch.float32, device=dev)
+    sel = torch.full((max(sum(ks), 1),), -1, dtype=torch.int32, device=dev)
+    scores = torch.full((sum(r.S for r in case.reqs),), -5.0, dtype=torch.float32, device=dev)
+    rc.rc_reuse(model, reqs, plan, src, dst, logits, sel, scores, ws)
+    torch.cuda.synchronize()
+    out_k, out_v, out_sel, out_sc = [], [], [], []
+    so = ko = 0
+    for b, r in enumerate(case.reqs):
+        out_k.append([to_np(dst.read("k", l, b, dst_lens[b])) for l in range(sh.n_layers)])
+        out_v.append([to_np(dst.read("v", l, b, dst_lens[b])) for l in range(sh.n_layers)])
+        out_sel.append(sel[ko:ko + r.k].cpu().numpy())
+        out_sc.append(scores[so:so + r.S].cpu().numpy())
+        ko += r.k
+        so += r.S
+    res = HipRun(out_k, out_v, to_np(logits), out_sel, out_sc)
+    model.close()
+    return res
+
+
+def hip_full_prefill(case: Case, b: int = 0, capture_layer: int = 0):
+    """rc_prefill of [prefix ; segment] of request b; returns (k, v, k_pre, h_capture, logits)."""
+    from paper_2603_13289_amd import binding as rc
+    sh = case.w.shape
+    dt = rc.rc_dtype_of(sh.dtype)
+    td = rc.torch_dtype(dt)
+    model = rc.rc_model_create(sh, case.weights)
+    r = case.reqs[b]
+    x = torch.from_numpy(np.concatenate([r.xp, r.xs]).astype(np.float32)).to("cuda").to(td).contiguous()
+    T = x.shape[0]
+    bs = case.w.block_size
+    if bs > 0:
+        tab, nb = make_block_table([T], bs, seed=3)
+        dst = rc.PagedKV(sh.n_layers, nb, bs, sh.n_kv_heads, sh.head_dim, dt, tab)
+        kpre = rc.PagedKV(sh.n_layers, nb, bs, sh.n_kv_heads, sh.head_dim, dt, tab)
+    else:
+        dst = rc.PagedKV.contiguous(sh.n_layers, 1, T, sh.n_kv_heads, sh.head_dim, dt)
+        kpre = rc.PagedKV.contiguous(sh.n_layers, 1, T, sh.n_kv_heads, sh.head_dim, dt)
+    hcap = torch.zeros((T, sh.d_model), dtype=td, device="cuda")
+    logits = torch.zeros((1, sh.vocab), dtype=torch.float32, device="cuda")
+    ws = rc.alloc_workspace(rc.rc_prefill_workspace_bytes(model, [T]))
+    rc.rc_prefill(model, [x], [0], dst, logits, ws, k_pre=kpre, capture_layer=capture_layer, h_capture=[hcap])
+    torch.cuda.synchronize()
+    k = [to_np(dst.read("k", l, 0, T)) for l in range(sh.n_layers)]
+    v = [to_np(dst.read("v", l, 0, T)) for l in range(sh.n_layers)]
+    kp = [to_np(kpre.read("k", l, 0, T)) for l in range(sh.n_layers)]
+    model.close()
+    return k, v, kp, to_np(hcap), to_np(logits)[0]

@@ -1,0 +1,144 @@
+"""End-to-end parity of the selective-recompute prefill (rc_reuse / rc_prefill) against the CPU oracle."""
+import numpy as np
+import pytest
+
+from oracle import relay_oracle as R
+from tests.harness import (TOL, build_case, hip_full_prefill, hip_relay, oracle_relay, rel_err, selection_margin)
+
+pytestmark = pytest.mark.gpu
+
+# Index parity is asserted bit-exactly when the oracle's k-th and (k+1)-th scores are further apart
+# (relatively) than float arithmetic can move them: the float path carries ~3e-4 relative error on a
+# deviation of 1e-5 (hidden states and fresh values are float products of ~256 terms).
+MARGIN = 2e-3
+
+
+def _check_against_oracle(case, run, want_list, tol, check_sel=True):
+    L = case.w.shape.n_layers
+    for b, want in enumerate(want_list):
+        T = want.k_cache.shape[1]
+        if check_sel:
+            assert np.array_equal(run.sel[b], want.sel_idx), f"req {b}: selected indices differ"
+        for l in range(L):
+            ek = rel_err(run.k_cache[b][l][:T], want.k_cache[l])
+            ev = rel_err(run.v_cache[b][l][:T], want.v_cache[l])
+            assert ek <= tol and ev <= tol, f"req {b} layer {l}: K err {ek:.2e} V err {ev:.2e} (tol {tol})"
+        el = rel_err(run.logits[b], want.logits)
+        assert el <= tol, f"req {b}: logits err {el:.2e}"
+
+
+# ------------------------------------------------------------------ float configuration (config 1)
+def test_tiny_f32_matches_oracle_exact_indices():
+    case = build_case("tiny_f32")
+    want = oracle_relay(case)
+    assert len(want.sel_idx) == 51
+    # the guard that makes bit-exact index parity meaningful across precisions
+    assert selection_margin(want.score, case.reqs[0].k) > MARGIN
+    run = hip_relay(case)
+    assert np.max(np.abs(run.scores[0] - want.score)) <= 1e-6
+    _check_against_oracle(case, run, [want], TOL["f32"])
+    # and the result is close to, but not the same as, a full prefill (the method is an approximation)
+    full = R.full_prefill(case.om, np.concatenate([case.reqs[0].xp, case.reqs[0].xs]))
+    assert rel_err(run.logits[0], full.logits) < 0.2
+
+
+@pytest.mark.parametrize("k", [0, 1, 203])
+def test_tiny_f32_paged_budgets(k):
+    case = build_case("tiny_f32_paged", k_override=k)
+    want = oracle_relay(case)
+    run = hip_relay(case)
+    _check_against_oracle(case, run, [want], TOL["f32"], check_sel=(k in (0, 203)) or
+                          selection_margin(want.score, k) > MARGIN)
+
+
+@pytest.mark.parametrize("pre_rope", [True, False])
+def test_tiny_f32_suffix_and_rotated_keys(pre_rope):
+    case = build_case("tiny_f32_paged", pre_rope=pre_rope, n_suffix=5)
+    want = oracle_relay(case)
+    run = hip_relay(case)
+    ok = selection_margin(want.score, case.reqs[0].k) > MARGIN
+    _check_against_oracle(case, run, [want], TOL["f32"], check_sel=ok)
+
+
+def test_zero_budget_is_pure_reuse_bit_exact():
+    """ZERO baseline on the GPU: with a suffix and k = 0 every segment row equals the re-rotated record."""
+    case = build_case("tiny_f32_paged", k_override=0, n_suffix=2)
+    want = oracle_relay(case)
+    run = hip_relay(case)
+    rq = case.reqs[0]
+    for l in range(case.w.shape.n_layers):
+        assert np.array_equal(run.v_cache[0][l][rq.P:rq.P + rq.S], rq.seg.v[l].astype(np.float32))
+        assert rel_err(run.k_cache[0][l][rq.P:rq.P + rq.S], want.k_cache[l][rq.P:rq.P + rq.S]) <= 1e-6
+    _check_against_oracle(case, run, [want], TOL["f32"])
+
+
+def test_full_budget_equals_full_prefill_on_gpu():
+    """FULL baseline: k = S from layer 0 with the token inputs as h_start reproduces rc_prefill."""
+    case = build_case("tiny_f32", k_override=256, l_triple=(0, 1, 1))
+    rq = case.reqs[0]
+    rq.seg.h_start = rq.xs.astype(np.float64)
+    run = hip_relay(case)
+    k, v, kp, hcap, logits = hip_full_prefill(case)
+    for l in range(case.w.shape.n_layers):
+        assert rel_err(run.k_cache[0][l], k[l]) <= 1e-5
+        assert rel_err(run.v_cache[0][l], v[l]) <= 1e-5
+    assert rel_err(run.logits[0], logits) <= 1e-5
+    assert run.sel[0].tolist() == list(range(256))
+
+
+def test_prefill_matches_oracle_full_prefill_f32():
+    case = build_case("tiny_f32_paged")
+    rq = case.reqs[0]
+    full = R.full_prefill(case.om, np.concatenate([rq.xp, rq.xs]))
+    k, v, kp, hcap, logits = hip_full_prefill(case, capture_layer=1)
+    for l in range(case.w.shape.n_layers):
+        assert rel_err(k[l], full.k_cache[l]) <= TOL["f32"]
+        assert rel_err(v[l], full.v_cache[l]) <= TOL["f32"]
+        assert rel_err(kp[l], full.k_pre_rope[l]) <= TOL["f32"]
+    assert rel_err(hcap, full.h_in[1]) <= TOL["f32"]
+    assert rel_err(logits, full.logits) <= TOL["f32"]
+
+
+# ------------------------------------------------------------------ bf16 configurations
+@pytest.mark.parametrize("name", ["small_bf16", "qwen32b_trunc", "mistral7b_trunc"])
+def test_bf16_matches_oracle_with_forced_indices(name):
+    """bf16 against the float64 oracle: tolerances are measured on the same rows (the oracle's
+    selection is forced), and the library's own selection must overlap it almost everywhere."""
+    case = build_case(name)
+    want = oracle_relay(case)
+    free = hip_relay(case)
+    k = case.reqs[0].k
+    overlap = len(set(free.sel[0].tolist()) & set(want.sel_idx.tolist())) / max(k, 1)
+    assert overlap >= 0.9, f"selection overlap {overlap:.3f}"
+    assert np.max(np.abs(free.scores[0] - want.score)) <= 5e-3 * max(np.max(want.score), 1e-3) + 1e-4
+    forced = hip_relay(case, forced=[want.sel_idx])
+    assert np.array_equal(forced.sel[0], want.sel_idx)
+    _check_against_oracle(case, forced, [want], TOL["bf16"])
+
+
+def test_bf16_ragged_batch_equals_single_requests():
+    case = build_case("small_bf16_ragged")
+    wants = [oracle_relay(case, b) for b in range(len(case.reqs))]
+    batch = hip_relay(case, forced=[w.sel_idx for w in wants])
+    _check_against_oracle(case, batch, wants, TOL["bf16"])
+    # one request at a time gives bit-identical results to the batched launch sequence
+    from dataclasses import replace
+    for b in range(len(case.reqs)):
+        single = replace(case, reqs=[case.reqs[b]])
+        one = hip_relay(single, forced=[wants[b].sel_idx])
+        T = wants[b].k_cache.shape[1]
+        for l in range(case.w.shape.n_layers):
+            assert np.array_equal(one.k_cache[0][l][:T], batch.k_cache[b][l][:T])
+            assert np.array_equal(one.v_cache[0][l][:T], batch.v_cache[b][l][:T])
+        assert np.array_equal(one.logits[0], batch.logits[b])
+        assert np.array_equal(one.scores[0], batch.scores[b])
+
+
+def test_determinism_same_inputs_twice():
+    case = build_case("small_bf16")
+    a = hip_relay(case)
+    b = hip_relay(case)
+    assert np.array_equal(a.sel[0], b.sel[0])
+    assert np.array_equal(a.logits, b.logits)
+    for l in range(case.w.shape.n_layers):
+        assert np.array_equal(a.k_cache[0][l], b.k_cache[0][l])

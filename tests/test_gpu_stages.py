@@ -1,0 +1,212 @@
+"""Stage-level parity: each kernel family through the C ABI against the CPU oracle's stage function."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import relay_oracle as R
+from synth import make_block_table, round_to_bf16, stream_rng
+from tests.harness import TOL, rel_err, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def _rc():
+    from paper_2603_13289_amd import binding as rc
+    return rc
+
+
+def _td(dtype):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+def _rand(shape, dtype, name, scale=1.0):
+    x = stream_rng("stage", name).standard_normal(shape, dtype=np.float32) * np.float32(scale)
+    return round_to_bf16(x) if dtype == "bf16" else x
+
+
+def _up(x, dtype):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda().to(_td(dtype)).contiguous()
+
+
+def _cache(dtype, hkv, dh, lens, block_size, name, fill_random=True):
+    """A one-layer cache with random content; returns (PagedKV, [seq] -> K rows, V rows as numpy)."""
+    rc = _rc()
+    dt = rc.rc_dtype_of(dtype)
+    if block_size:
+        tab, nb = make_block_table(lens, block_size, seed=11)
+        kv = rc.PagedKV(1, nb, block_size, hkv, dh, dt, tab)
+    else:
+        kv = rc.PagedKV.contiguous(1, len(lens), max(lens), hkv, dh, dt)
+    ks, vs = [], []
+    for s, n in enumerate(lens):
+        k = _rand((n, hkv, dh), dtype, f"{name}k{s}")
+        v = _rand((n, hkv, dh), dtype, f"{name}v{s}")
+        if fill_random:
+            kv.write("k", 0, s, _up(k, dtype))
+            kv.write("v", 0, s, _up(v, dtype))
+        ks.append(k)
+        vs.append(v)
+    return kv, ks, vs
+
+
+# ------------------------------------------------------------------ K1
+@pytest.mark.parametrize("dtype,hkv,dh", [("f32", 2, 64), ("bf16", 8, 128), ("f32", 3, 128)])
+@pytest.mark.parametrize("block_size", [0, 16])
+@pytest.mark.parametrize("pre_rope", [True, False])
+def test_rope_rerotate(dtype, hkv, dh, block_size, pre_rope):
+    rc = _rc()
+    n, src_off, dst_off, old = 203, 37, 129, 37
+    base = 10000.0 if dtype == "f32" else 1.0e6
+    src, ks, vs = _cache(dtype, hkv, dh, [src_off + n + 5, 50], block_size, "rr_src")
+    dst, _, _ = _cache(dtype, hkv, dh, [30, dst_off + n], block_size, "rr_dst", fill_random=False)
+    ws = rc.alloc_workspace(rc.rc_stage_workspace_bytes(dst_off + n, dh))
+    rc.rc_rope_rerotate(src.layer(0), 0, src_off, dst.layer(0), 1, dst_off, n, pre_rope, old, base, ws)
+    torch.cuda.synchronize()
+    k_src, v_src = ks[0][src_off:src_off + n], vs[0][src_off:src_off + n]
+    ang = dst_off + np.arange(n) if pre_rope else np.full(n, dst_off - old)
+    want_k = R.rope_rotate(k_src, ang, base)
+    got_k = to_np(dst.read("k", 0, 1, n, start=dst_off))
+    got_v = to_np(dst.read("v", 0, 1, n, start=dst_off))
+    assert rel_err(got_k, want_k) <= (1e-6 if dtype == "f32" else 4e-3)
+    assert np.array_equal(got_v, v_src)                       # values are copied bit for bit
+    # rows outside the destination range are untouched (zeros)
+    assert float(dst.read("k", 0, 1, dst_off, start=0).abs().max()) == 0.0
+    assert float(dst.read("k", 0, 0, 30, start=0).abs().max()) == 0.0
+
+
+def test_rope_rerotate_large_positions_keep_float_accuracy():
+    rc = _rc()
+    n, dst_off, dh = 64, 36800, 128
+    src, ks, _ = _cache("f32", 1, dh, [n], 0, "rr_big")
+    dst, _, _ = _cache("f32", 1, dh, [dst_off + n], 0, "rr_big_dst", fill_random=False)
+    ws = rc.alloc_workspace(rc.rc_stage_workspace_bytes(dst_off + n, dh))
+    rc.rc_rope_rerotate(src.layer(0), 0, 0, dst.layer(0), 0, dst_off, n, True, 0, 1.0e6, ws)
+    torch.cuda.synchronize()
+    want = R.rope_rotate(ks[0], dst_off + np.arange(n), 1.0e6)
+    assert rel_err(to_np(dst.read("k", 0, 0, n, start=dst_off)), want) <= 1e-6
+
+
+# ------------------------------------------------------------------ K4
+@pytest.mark.parametrize("dtype,hkv,dh", [("f32", 2, 64), ("bf16", 8, 128), ("f32", 5, 128), ("bf16", 3, 128)])
+@pytest.mark.parametrize("block_size", [0, 16])
+def test_vdev_score(dtype, hkv, dh, block_size):
+    rc = _rc()
+    n, off = 301, 77
+    cache, _, vs = _cache(dtype, hkv, dh, [40, off + n], block_size, "sc")
+    v_reuse = vs[1][off:off + n]
+    fresh = v_reuse + _rand((n, hkv, dh), dtype, "sc_noise", 0.3)
+    fresh[5] = v_reuse[5] * 2.0            # scaled copy -> 0
+    fresh[6] = -v_reuse[6]                 # negation -> 2
+    fresh[7] = 0.0                         # zero vector -> cos := 0 -> score 1
+    if dtype == "bf16":
+        fresh = round_to_bf16(fresh)
+    score = torch.full((n,), -9.0, device="cuda")
+    ws = rc.alloc_workspace(rc.rc_stage_workspace_bytes(0, dh))
+    rc.rc_vdev_score(_up(fresh, dtype), cache.layer(0), 1, off, n, score, ws)
+    torch.cuda.synchronize()
+    want = R.vdev_score(v_reuse, fresh)
+    got = score.cpu().numpy()
+    assert np.max(np.abs(got - want)) <= 2e-6        # float accumulation of <= 128-term dot products
+    assert abs(got[5]) <= 1e-6 and abs(got[6] - 2.0) <= 1e-6 and got[7] == 1.0
+
+
+# ------------------------------------------------------------------ K5
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 1000, 4096, 16384, 32768, 40001])
+def test_topk_matches_oracle_bit_exactly(n):
+    rc = _rc()
+    g = stream_rng("stage", f"topk{n}")
+    score = g.random(n, dtype=np.float32)
+    score[g.integers(0, n, size=max(1, n // 7))] = score[0]          # many exact ties
+    if n > 10:
+        score[3] = -0.0; score[4] = 0.0; score[9] = -1.5e-7
+    dev = torch.from_numpy(score).cuda()
+    for k in sorted({0, 1, n // 7, (n * 15) // 100, n // 2, n - 1, n}):
+        if k < 0 or k > n:
+            continue
+        out = torch.full((max(k, 1),), -1, dtype=torch.int32, device="cuda")
+        rc.rc_topk(dev, n, k, out)
+        torch.cuda.synchronize()
+        want = R.topk_select(score, k)
+        assert np.array_equal(out.cpu().numpy()[:k], want), (n, k)
+
+
+def test_topk_all_equal_and_descending_inputs():
+    rc = _rc()
+    n = 5000
+    for arr in (np.full(n, 0.25, np.float32), np.linspace(1, 0, n, dtype=np.float32),
+                np.linspace(0, 1, n, dtype=np.float32)):
+        out = torch.zeros(777, dtype=torch.int32, device="cuda")
+        rc.rc_topk(torch.from_numpy(arr).cuda(), n, 777, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), R.topk_select(arr, 777))
+
+
+@pytest.mark.parametrize("n", [10, 1000, 33333])
+def test_threshold_select(n):
+    rc = _rc()
+    g = stream_rng("stage", f"thr{n}")
+    score = (g.random(n, dtype=np.float32) ** 4).astype(np.float32)       # sparse large values
+    for tau in (1.5, 1.45, 0.0, 50.0):
+        idx = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+        cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+        rc.rc_threshold_select(torch.from_numpy(score).cuda(), n, tau, idx, cnt)
+        torch.cuda.synchronize()
+        want = R.threshold_select(score.astype(np.float64), float(np.float32(tau)))
+        c = int(cnt.item())
+        assert c == len(want)
+        assert np.array_equal(idx.cpu().numpy()[:c], want)
+
+
+# ------------------------------------------------------------------ K6
+@pytest.mark.parametrize("dtype,hq,hkv,dh", [("f32", 4, 2, 64), ("bf16", 8, 2, 128), ("bf16", 10, 2, 128),
+                                              ("bf16", 4, 4, 128), ("f32", 2, 1, 128)])
+@pytest.mark.parametrize("block_size", [0, 16])
+def test_sparse_attention(dtype, hq, hkv, dh, block_size):
+    rc = _rc()
+    T = 333
+    cache, ks, vs = _cache(dtype, hkv, dh, [20, T], block_size, "att")
+    g = stream_rng("stage", "att_pos")
+    pos = np.sort(np.concatenate([np.arange(0, 70), g.choice(np.arange(70, T), size=57, replace=False), [T - 1, T - 1]]))
+    n = len(pos)
+    q = _rand((n, hq, dh), dtype, "att_q", 0.5)
+    out = torch.zeros((n, hq, dh), dtype=_td(dtype), device="cuda")
+    rc.rc_sparse_attention(_up(q, dtype), torch.from_numpy(pos.astype(np.int32)).cuda(), n, hq, cache.layer(0), 1, out)
+    torch.cuda.synchronize()
+    want = R.causal_gqa_attention(q.astype(np.float64), pos, ks[1].astype(np.float64), vs[1].astype(np.float64))
+    assert rel_err(to_np(out), want) <= (2e-5 if dtype == "f32" else 1e-2)
+    # the first query sees a single key: its output is that value row
+    assert rel_err(to_np(out)[0, 0], vs[1][0, 0]) <= (1e-6 if dtype == "f32" else 4e-3)
+
+
+# ------------------------------------------------------------------ K3
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("m,n,k", [(1, 64, 64), (51, 192, 256), (129, 1000, 688), (300, 257, 1408), (1639, 512, 1024)])
+def test_gemm_rows(dtype, m, n, k):
+    rc = _rc()
+    a = _rand((m, k), dtype, f"ga{m}{k}")
+    w = _rand((n, k), dtype, f"gw{n}{k}", 0.05)
+    c = torch.zeros((m, n), dtype=torch.float32, device="cuda")
+    rc.rc_gemm_rows(rc.rc_dtype_of(dtype), _up(a, dtype), _up(w, dtype), c, m, n, k)
+    torch.cuda.synchronize()
+    want = a.astype(np.float64) @ w.astype(np.float64).T
+    assert rel_err(to_np(c), want) <= 2e-6 * np.sqrt(k)
+
+
+# ------------------------------------------------------------------ K7
+@pytest.mark.parametrize("dtype,hkv,dh", [("f32", 2, 64), ("bf16", 8, 128)])
+@pytest.mark.parametrize("block_size", [0, 16])
+def test_scatter_paged(dtype, hkv, dh, block_size):
+    rc = _rc()
+    T = 500
+    cache, ks, vs = _cache(dtype, hkv, dh, [T, 33], block_size, "scat")
+    g = stream_rng("stage", "scat_pos")
+    pos = np.sort(g.choice(T, size=75, replace=False)).astype(np.int32)
+    kr = _rand((75, hkv, dh), dtype, "scat_k")
+    vr = _rand((75, hkv, dh), dtype, "scat_v")
+    rc.rc_scatter_paged(_up(kr, dtype), _up(vr, dtype), torch.from_numpy(pos).cuda(), 75, cache.layer(0), 0)
+    torch.cuda.synchronize()
+    want_k, want_v = ks[0].copy(), vs[0].copy()
+    want_k[pos], want_v[pos] = kr, vr
+    assert np.array_equal(to_np(cache.read("k", 0, 0, T)), want_k)
+    assert np.array_equal(to_np(cache.read("v", 0, 0, T)), want_v)
+    assert np.array_equal(to_np(cache.read("k", 0, 1, 33)), ks[1])     # other sequences untouched
