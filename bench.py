@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the selective-recompute prefill on one MI355X.
+
+One "step" is one pass of the whole hot path -- rc_reuse: re-rotation of the reused keys in every
+layer, prefill of the new prefix, dense recompute of [l_start, l_det), Eq. (1) scoring, budget
+top-k, sparse rectification of [l_det, l_end], tail layers and first-token logits -- over one
+synthetic request of the headline workload (Mistral-7B shape, 1024 new + 4096 reused tokens,
+15 % budget in layers 8-24).  All inputs (weights, hidden states, the earlier agent's KV) are
+resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is context tokens per second = (P + S) / TTFT.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "TTFT ms + context tokens/s, selective-recompute prefill, 4k reuse @15%"
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def gemm_flops(w, P, S, k):
+    """Algorithmic GEMM FLOPs of one step: 2 * W_l per active row and layer, the fresh values of the S
+    segment tokens at l_det, and the LM head on one row."""
+    sh = w.shape
+    rows = 0
+    last = 1
+    for l in range(sh.n_layers):
+        if l < w.l_start:
+            rows += P
+        elif l < w.l_det:
+            rows += P + S
+        elif l <= w.l_end:
+            rows += P + k + last
+        else:
+            rows += P + last
+    fl = 2.0 * sh.gemm_params_per_layer * rows
+    fl += 2.0 * S * sh.d_model * sh.n_kv_heads * sh.head_dim
+    fl += 2.0 * sh.d_model * sh.vocab
+    return fl, rows
+
+
+def device_model(rc, torch, w, seed):
+    sh = w.shape
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    td = rc.torch_dtype(rc.rc_dtype_of(sh.dtype))
+    d, hq, hkv, dh, f = sh.d_model, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.d_ffn
+
+    def draw(rows, cols):
+        return (torch.randn((rows, cols), generator=g, device="cuda", dtype=torch.float32) * 0.02).to(td)
+
+    layers = []
+    for _ in range(sh.n_layers):
+        layers.append(dict(wq=draw(hq * dh, d), wk=draw(hkv * dh, d), wv=draw(hkv * dh, d), wo=draw(d, hq * dh),
+                           w_gate=draw(f, d), w_up=draw(f, d), w_down=draw(d, f),
+                           g_attn=torch.ones(d, device="cuda", dtype=td), g_ffn=torch.ones(d, device="cuda", dtype=td)))
+    model = rc.Model(sh, layers, torch.ones(d, device="cuda", dtype=td), draw(sh.vocab, d))
+    return model, g
+
+
+def cpu_baseline(w, budget_s=20.0):
+    """The CPU oracle timed on a bounded sample of the same workload: same widths and token counts,
+    3 layers with triple (0, 1, 2) (one dense detect layer, two sparse layers), random segment record.
+    Scaled to the full workload by row-layers."""
+    import numpy as np
+    from dataclasses import replace
+    from oracle import relay_oracle as R
+    from synth import make_hidden, make_weights, budget_to_k
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    sh = replace(w.shape, n_layers=3, vocab=1024)
+    ws = replace(w, name=w.name + "_cpu_sample", shape=sh, l_start=0, l_det=1, l_end=2)
+    P, S = w.n_prefix, w.n_seg
+    k = budget_to_k(S, w.budget_pct)
+    weights = make_weights(ws)
+    om = R.OracleModel.from_shape(sh, weights)
+    xp = make_hidden(ws, "x_prefix", P)
+    rng = np.random.default_rng(1)
+    kv_shape = (sh.n_layers, S, sh.n_kv_heads, sh.head_dim)
+    seg = R.SegmentRecord(rng.standard_normal(kv_shape), rng.standard_normal(kv_shape),
+                          make_hidden(ws, "h_start", S).astype(np.float64), True, w.n_alt)
+    t0 = time.perf_counter()
+    res = R.relay_prefill(om, xp, seg, 0, 1, 2, k)
+    dt = time.perf_counter() - t0
+    sample_rows = sum(res.active_rows)
+    _, full_rows = gemm_flops(w, P, S, k)
+    est_ttft = dt * full_rows / sample_rows
+    return {"value": (P + S) / est_ttft, "unit": "context tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"oracle relay_prefill (numpy float64) on a 3-layer instance of the workload's widths, "
+                      f"P={P}, S={S}, k={k}, triple (0,1,2): {sample_rows} row-layers in {dt:.1f} s, scaled to the "
+                      f"workload's {full_rows} row-layers (estimated TTFT {est_ttft:.0f} s)"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="mistral7b_4k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-full-prefill", action="store_true")
+    ap.add_argument("--seed", type=int, default=20260313)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2603_13289_amd import binding as rc
+    from synth import WORKLOADS, budget_to_k
+
+    w = WORKLOADS[args.workload]
+    sh = w.shape
+    P, S, A = w.n_prefix, w.n_seg, w.n_alt
+    k = budget_to_k(S, w.budget_pct)
+    dt = rc.rc_dtype_of(sh.dtype)
+    td = rc.torch_dtype(dt)
+    torch.cuda.set_device(0)
+    model, g = device_model(rc, torch, w, args.seed)
+
+    def hidden(n):
+        return torch.randn((n, sh.d_model), generator=g, device="cuda", dtype=torch.float32).to(td)
+
+    x_alt, x_seg, x_prefix = hidden(A), hidden(S), hidden(P)
+
+    # the earlier agent: prefill of [alt ; segment] keeps pre-RoPE keys, values and h entering l_start
+    old = rc.PagedKV.contiguous(sh.n_layers, 1, A + S, sh.n_kv_heads, sh.head_dim, dt)
+    old_pre = rc.PagedKV.contiguous(sh.n_layers, 1, A + S, sh.n_kv_heads, sh.head_dim, dt)
+    h_cap = torch.zeros((A + S, sh.d_model), dtype=td, device="cuda")
+    lg = torch.zeros((1, sh.vocab), dtype=torch.float32, device="cuda")
+    ws_p = rc.alloc_workspace(rc.rc_prefill_workspace_bytes(model, [max(A + S, P + S)]))
+    rc.rc_prefill(model, [torch.cat([x_alt, x_seg]).contiguous()], [0], old, lg, ws_p, k_pre=old_pre,
+                  capture_layer=w.l_start, h_capture=[h_cap])
+    torch.cuda.synchronize()
+    record = rc.PagedKV.from_pools(old_pre.k, old.v, old.block_table, dt)   # pre-RoPE keys + values
+    h_start = h_cap[A:].contiguous()
+
+    dst = rc.PagedKV.contiguous(sh.n_layers, 1, P + S, sh.n_kv_heads, sh.head_dim, dt)
+    req = rc.Request(x_prefix, h_start, None, src_seq=0, src_offset=A, k_is_pre_rope=True, seg_old_start_pos=A,
+                     dst_seq=0)
+    plan = rc.Plan(w.l_start, w.l_det, w.l_end, [k])
+    ws = rc.alloc_workspace(rc.rc_reuse_workspace_bytes(model, [req], plan))
+    logits = torch.zeros((1, sh.vocab), dtype=torch.float32, device="cuda")
+    sel = torch.zeros(max(k, 1), dtype=torch.int32, device="cuda")
+
+    def step():
+        rc.rc_reuse(model, [req], plan, record, dst, logits, sel, None, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_per_step = ev0.elapsed_time(ev1) / args.steps
+
+    # per-stage split of the same steps, with HIP events around every launch on the same stream
+    rc.rc_profile_enable(True)
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_per_step_profiled = ev0.elapsed_time(ev1) / args.steps
+    prof = rc.rc_profile_read()
+    rc.rc_profile_enable(False)
+    stages = {name: {"ms_per_step": ms / args.steps, "launches_per_step": n // args.steps}
+              for name, (ms, n) in prof.items() if n}
+    gemm_ms = sum(v["ms_per_step"] for n, v in stages.items() if n.startswith("gemm"))
+    gemm_launches = sum(v["launches_per_step"] for n, v in stages.items() if n.startswith("gemm"))
+    fl, rows = gemm_flops(w, P, S, k)
+    achieved = fl / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+
+    full_ms = None
+    if not args.no_full_prefill:
+        full_dst = rc.PagedKV.contiguous(sh.n_layers, 1, P + S, sh.n_kv_heads, sh.head_dim, dt)
+        x_full = torch.cat([x_prefix, x_seg]).contiguous()
+        rc.rc_prefill(model, [x_full], [0], full_dst, lg, ws_p)
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(2):
+            rc.rc_prefill(model, [x_full], [0], full_dst, lg, ws_p)
+        ev1.record()
+        torch.cuda.synchronize()
+        full_ms = ev0.elapsed_time(ev1) / 2
+
+    out = {
+        "metric": METRIC,
+        "value": (P + S) / (ms_per_step * 1e-3),
+        "unit": "context tokens/s",
+        "ttft_ms": ms_per_step,
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": sh.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "n_prefix": P, "n_seg": S, "n_alt": A, "k": k,
+                   "layers": [w.l_start, w.l_det, w.l_end], "n_layers": sh.n_layers, "d_model": sh.d_model,
+                   "kv_layout": "contiguous", "batch": 1},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "projection GEMMs (all launches of one step)",
+                     "algorithmic_gflop_per_step": fl / 1e9, "gemm_ms_per_step": gemm_ms,
+                     "gemm_launches_per_step": gemm_launches, "row_layers": rows},
+        "stages_ms": {n: round(v["ms_per_step"], 4) for n, v in stages.items()},
+        "ms_per_step_with_stage_events": ms_per_step_profiled,
+        "full_prefill_ms": full_ms,
+        "speedup_vs_full_prefill": (full_ms / ms_per_step) if full_ms else None,
+        "reuse_rate": 1.0 - ((w.l_det - w.l_start) * S + (w.l_end - w.l_det + 1) * k) / float(sh.n_layers * S),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

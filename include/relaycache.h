@@ -182,6 +182,22 @@ RC_API rc_status rc_prefill(const rc_model* m, const void* const* x, const int32
                      void* const* k_pre_pool, int32_t capture_layer, void* const* h_capture,
                      float* logits, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------- timing
+ * Optional per-stage GPU timing of rc_reuse / rc_prefill (the per-stage latency split the paper
+ * reports in its Table "Per-agent TTFT breakdown").  While enabled, every kernel launch of those two
+ * calls is bracketed by a pair of HIP events on the call's stream.  rc_profile_read waits for the
+ * recorded events, adds up milliseconds and launch counts per stage class into ms / launches (host
+ * arrays of rc_profile_class_count() entries) and forgets them.  Process-global, not thread-safe. */
+RC_API rc_status rc_profile_enable(int32_t on);
+RC_API int32_t rc_profile_class_count(void);
+RC_API const char* rc_profile_class_name(int32_t cls);
+RC_API rc_status rc_profile_read(float* ms, int32_t* launches);
+
+/* Tuning knobs (process-global).  RC_TUNE_GEMM_TILE: workgroup tile of the bf16 projection GEMM,
+ * 0 = chosen per shape (default), 1 = 128x256, 2 = 256x256, 3 = 128x128. */
+#define RC_TUNE_GEMM_TILE 1
+RC_API rc_status rc_tune_set(int32_t key, int32_t value);
+
 /* ------------------------------------------------------------ stage calls
  * One kernel (family) each, for unit tests and for profiling a stage in isolation. */
 

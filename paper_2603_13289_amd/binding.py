@@ -25,7 +25,8 @@ EXPORTS = [
     "rc_status_str", "rc_build_info", "rc_model_create", "rc_model_destroy", "rc_reuse_workspace_bytes",
     "rc_reuse", "rc_prefill_workspace_bytes", "rc_prefill", "rc_stage_workspace_bytes", "rc_rope_rerotate",
     "rc_vdev_score", "rc_topk", "rc_threshold_select", "rc_sparse_attention", "rc_gemm_rows",
-    "rc_scatter_paged",
+    "rc_scatter_paged", "rc_profile_enable", "rc_profile_class_count", "rc_profile_class_name", "rc_profile_read",
+    "rc_tune_set",
 ]
 
 
@@ -110,6 +111,16 @@ def _load() -> C.CDLL:
     lib.rc_gemm_rows.argtypes = [i32, vp, vp, vp, i32, i32, i32, vp]
     lib.rc_scatter_paged.restype = C.c_int
     lib.rc_scatter_paged.argtypes = [vp, vp, vp, i32, C.POINTER(rc_kv_layer), i32, vp]
+    lib.rc_tune_set.restype = C.c_int
+    lib.rc_tune_set.argtypes = [i32, i32]
+    lib.rc_profile_enable.restype = C.c_int
+    lib.rc_profile_enable.argtypes = [i32]
+    lib.rc_profile_class_count.restype = i32
+    lib.rc_profile_class_count.argtypes = []
+    lib.rc_profile_class_name.restype = C.c_char_p
+    lib.rc_profile_class_name.argtypes = [i32]
+    lib.rc_profile_read.restype = C.c_int
+    lib.rc_profile_read.argtypes = [C.POINTER(C.c_float), C.POINTER(i32)]
     return lib
 
 
@@ -220,6 +231,20 @@ class PagedKV:
     def contiguous(n_layers, n_seq, max_len, n_kv_heads, head_dim, dtype, device="cuda", fill=None) -> "PagedKV":
         table = [[s] for s in range(n_seq)]
         return PagedKV(n_layers, n_seq, max_len, n_kv_heads, head_dim, dtype, table, device, fill)
+
+    @staticmethod
+    def from_pools(k: List[torch.Tensor], v: List[torch.Tensor], block_table: torch.Tensor, dtype: int) -> "PagedKV":
+        """A cache made of existing per-layer pools (e.g. one run's pre-RoPE keys with its values)."""
+        self = PagedKV.__new__(PagedKV)
+        self.n_layers = len(k)
+        self.n_blocks, self.n_kv_heads, self.block_size, self.head_dim = k[0].shape
+        self.dtype, self.k, self.v, self.block_table = dtype, list(k), list(v), block_table
+        self.n_seq, self.max_blocks = block_table.shape
+        self._kp = (C.c_void_p * self.n_layers)(*[t.data_ptr() for t in self.k])
+        self._vp = (C.c_void_p * self.n_layers)(*[t.data_ptr() for t in self.v])
+        self.c = rc_paged_kv(C.cast(self._kp, C.POINTER(C.c_void_p)), C.cast(self._vp, C.POINTER(C.c_void_p)),
+                             self.n_blocks, self.block_size, block_table.data_ptr(), self.n_seq, self.max_blocks)
+        return self
 
     def layer(self, l: int) -> rc_kv_layer:
         return rc_kv_layer(self.k[l].data_ptr(), self.v[l].data_ptr(), self.n_blocks, self.block_size,
@@ -366,3 +391,24 @@ def rc_scatter_paged(k_rows: torch.Tensor, v_rows: torch.Tensor, pos: torch.Tens
                      seq: int, stream=None) -> None:
     _check(lib.rc_scatter_paged(_ptr(k_rows), _ptr(v_rows), _ptr(pos), n, C.byref(dst), seq, _stream(stream)),
            "rc_scatter_paged")
+
+
+# ------------------------------------------------------------------ per-stage timing
+def rc_profile_enable(on: bool) -> None:
+    _check(lib.rc_profile_enable(1 if on else 0), "rc_profile_enable")
+
+
+def rc_profile_read() -> dict:
+    """{stage class: (milliseconds, launches)} accumulated since the last read."""
+    n = lib.rc_profile_class_count()
+    ms = (C.c_float * n)()
+    cnt = (C.c_int32 * n)()
+    _check(lib.rc_profile_read(ms, cnt), "rc_profile_read")
+    return {lib.rc_profile_class_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(n)}
+
+
+RC_TUNE_GEMM_TILE = 1
+
+
+def rc_tune_set(key: int, value: int) -> None:
+    _check(lib.rc_tune_set(key, value), "rc_tune_set")

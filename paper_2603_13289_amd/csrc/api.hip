@@ -28,6 +28,46 @@ namespace {
     if (_s != RC_OK) return _s;    \
   } while (0)
 
+// ---------------------------------------------------------------- optional per-class GPU timing
+enum ProfClass : int {
+  PC_REROTATE = 0, PC_ROWS, PC_RMSNORM, PC_GEMM_QKV, PC_GEMM_O, PC_GEMM_GATE_UP, PC_GEMM_DOWN, PC_GEMM_VFRESH,
+  PC_GEMM_LM_HEAD, PC_ROPE_SCATTER, PC_ATTENTION, PC_SCORE, PC_SELECT, PC_TABLES, PC_COUNT
+};
+const char* const kProfNames[PC_COUNT] = {"rope_rerotate", "row_bookkeeping", "rmsnorm", "gemm_qkv", "gemm_o",
+                                          "gemm_gate_up", "gemm_down", "gemm_vfresh", "gemm_lm_head",
+                                          "rope_scatter", "attention", "vdev_score", "select", "tables"};
+struct ProfRec { int cls; hipEvent_t a, b; };
+struct Profiler {
+  bool on = false;
+  std::vector<ProfRec> recs;
+  std::vector<hipEvent_t> pool;
+  hipEvent_t get() {
+    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+} g_prof;
+
+struct ProfScope {
+  hipStream_t st;
+  hipEvent_t b = nullptr;
+  ProfScope(int cls, hipStream_t s) : st(s) {
+    if (!g_prof.on) return;
+    hipEvent_t a = g_prof.get();
+    b = g_prof.get();
+    if (!a || !b) { b = nullptr; return; }
+    (void)hipEventRecord(a, st);
+    g_prof.recs.push_back({cls, a, b});
+  }
+  ~ProfScope() { if (b) (void)hipEventRecord(b, st); }
+};
+#define RC_LAUNCH(cls, expr)          \
+  do {                                \
+    ProfScope _ps((cls), st);         \
+    if ((expr) != hipSuccess) return RC_E_HIP; \
+  } while (0)
+
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 inline size_t elem_size(int dtype) { return dtype == RC_BF16 ? 2 : 4; }
 
@@ -249,16 +289,16 @@ rc_status run_job(const Job& job, Workspace& w, hipStream_t st) {
   bool uploaded[PH_COUNT] = {false, false, false, false};
   for (int p = 0; p < PH_COUNT; ++p) tabs[p] = job.base;
 
-  RC_HIP(launch_rope_table(w.rope_tab, job.max_pos, d.head_dim / 2, (double)d.rope_base, st));
+  RC_LAUNCH(PC_TABLES, launch_rope_table(w.rope_tab, job.max_pos, d.head_dim / 2, (double)d.rope_base, st));
 
   int cur = -1;   // phase whose rows are live in w.h[hbuf]
   int hbuf = 0;
   auto enter_phase = [&](Phase ph) -> rc_status {
     fill_phase(&tabs[ph], job.rq, ph, cur >= 0 ? &tabs[cur] : nullptr, tile_rows);
-    RC_HIP(launch_upload_table(tabs[ph], w.tables + ph, st));
+    RC_LAUNCH(PC_TABLES, launch_upload_table(tabs[ph], w.tables + ph, st));
     uploaded[ph] = true;
     const int nb = cur >= 0 ? 1 - hbuf : hbuf;
-    RC_HIP(launch_build_rows<T>(w.tables + ph, tabs[ph].total_rows, w.h[hbuf], w.h[nb], w.row_pos, w.row_req,
+    RC_LAUNCH(PC_ROWS, launch_build_rows<T>(w.tables + ph, tabs[ph].total_rows, w.h[hbuf], w.h[nb], w.row_pos, w.row_req,
                                 job.sel_idx, D, st));
     hbuf = nb;
     cur = ph;
@@ -275,10 +315,10 @@ rc_status run_job(const Job& job, Workspace& w, hipStream_t st) {
     if (has_seg) {
       const KvGeom gs = geom_of(*job.src, d);
       if (!delta_done) {
-        RC_HIP(launch_delta_table(w.delta_tab, w.tables + cur, n_req, d.head_dim / 2, (double)d.rope_base, st));
+        RC_LAUNCH(PC_TABLES, launch_delta_table(w.delta_tab, w.tables + cur, n_req, d.head_dim / 2, (double)d.rope_base, st));
         delta_done = true;
       }
-      RC_HIP(launch_rerotate<T>((const T*)job.src->k_pool[l], (const T*)job.src->v_pool[l], gs,
+      RC_LAUNCH(PC_REROTATE, launch_rerotate<T>((const T*)job.src->k_pool[l], (const T*)job.src->v_pool[l], gs,
                                 (T*)job.dst->k_pool[l], (T*)job.dst->v_pool[l], gd, w.tables + cur, n_req,
                                 job.max_seg, w.rope_tab, w.delta_tab, st));
     }
@@ -289,17 +329,17 @@ rc_status run_job(const Job& job, Workspace& w, hipStream_t st) {
       for (const ReqHost& r : job.rq) any = any || r.k > 0;
       if (any) {
         const int rows_b = tabs[cur].total_rows;
-        RC_HIP(launch_rmsnorm<T>(w.h[hbuf], (const T*)lw.g_attn, (T*)w.a, rows_b, D, d.rms_eps, st));
-        RC_HIP(launch_gemm<T>((const T*)w.a, (const T*)lw.wv, nullptr, w.vfresh, rows_b, nkv, D, nkv, EPI_STORE_T, st));
+        RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(w.h[hbuf], (const T*)lw.g_attn, (T*)w.a, rows_b, D, d.rms_eps, st));
+        RC_LAUNCH(PC_GEMM_VFRESH, launch_gemm<T>((const T*)w.a, (const T*)lw.wv, nullptr, w.vfresh, rows_b, nkv, D, nkv, EPI_STORE_T, st));
         float* sc = job.scores_out ? job.scores_out : w.scores;
-        RC_HIP(launch_vdev_score<T>((const T*)w.vfresh, nkv, (const T*)job.dst->v_pool[l], gd, w.tables + cur,
+        RC_LAUNCH(PC_SCORE, launch_vdev_score<T>((const T*)w.vfresh, nkv, (const T*)job.dst->v_pool[l], gd, w.tables + cur,
                                     n_req, job.max_seg, sc, st));
         for (int b = 0; b < n_req; ++b) {
           const ReqHost& r = job.rq[b];
           if (r.k <= 0) continue;
           const int sb = job.base.r[b].sel_base;
-          if (job.forced_idx) RC_HIP(launch_copy_i32(job.forced_idx + sb, job.sel_idx + sb, r.k, st));
-          else RC_HIP(launch_topk(sc + job.base.r[b].score_base, r.S, r.k, job.sel_idx + sb, st));
+          if (job.forced_idx) RC_LAUNCH(PC_SELECT, launch_copy_i32(job.forced_idx + sb, job.sel_idx + sb, r.k, st));
+          else RC_LAUNCH(PC_SELECT, launch_topk(sc + job.base.r[b].score_base, r.S, r.k, job.sel_idx + sb, st));
         }
       }
       RC_TRY(enter_phase(PH_C));
@@ -307,30 +347,30 @@ rc_status run_job(const Job& job, Workspace& w, hipStream_t st) {
 
     const int rows = tabs[cur].total_rows;
     if (rows == 0) continue;
-    if (l == job.capture_layer) RC_HIP(launch_capture_rows<T>(w.tables + cur, rows, w.h[hbuf], w.row_req, D, st));
+    if (l == job.capture_layer) RC_LAUNCH(PC_ROWS, launch_capture_rows<T>(w.tables + cur, rows, w.h[hbuf], w.row_req, D, st));
 
     float* h = w.h[hbuf];
-    RC_HIP(launch_rmsnorm<T>(h, (const T*)lw.g_attn, (T*)w.a, rows, D, d.rms_eps, st));
-    RC_HIP(launch_gemm<T>((const T*)w.a, (const T*)lw.wq, nullptr, w.qkv, rows, nq, D, nqkv, EPI_STORE_F32, st));
-    RC_HIP(launch_gemm<T>((const T*)w.a, (const T*)lw.wk, nullptr, w.qkv + nq, rows, nkv, D, nqkv, EPI_STORE_F32, st));
-    RC_HIP(launch_gemm<T>((const T*)w.a, (const T*)lw.wv, nullptr, w.qkv + nq + nkv, rows, nkv, D, nqkv, EPI_STORE_F32, st));
+    RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(h, (const T*)lw.g_attn, (T*)w.a, rows, D, d.rms_eps, st));
+    RC_LAUNCH(PC_GEMM_QKV, launch_gemm<T>((const T*)w.a, (const T*)lw.wq, nullptr, w.qkv, rows, nq, D, nqkv, EPI_STORE_F32, st));
+    RC_LAUNCH(PC_GEMM_QKV, launch_gemm<T>((const T*)w.a, (const T*)lw.wk, nullptr, w.qkv + nq, rows, nkv, D, nqkv, EPI_STORE_F32, st));
+    RC_LAUNCH(PC_GEMM_QKV, launch_gemm<T>((const T*)w.a, (const T*)lw.wv, nullptr, w.qkv + nq + nkv, rows, nkv, D, nqkv, EPI_STORE_F32, st));
     // rotary on q/k at the rows' absolute positions; fresh K/V written into the cache before anyone attends
-    RC_HIP(launch_rope_scatter<T>(w.qkv, rows, w.row_pos, w.row_req, w.tables + cur, w.rope_tab, (T*)w.q,
+    RC_LAUNCH(PC_ROPE_SCATTER, launch_rope_scatter<T>(w.qkv, rows, w.row_pos, w.row_req, w.tables + cur, w.rope_tab, (T*)w.q,
                                   (T*)job.dst->k_pool[l], (T*)job.dst->v_pool[l],
                                   job.k_pre_pool ? (T*)job.k_pre_pool[l] : nullptr, gd, d.n_q_heads, st));
-    RC_HIP(attention_dispatch<T>((const T*)w.q, w.row_pos, w.row_req, w.tables + cur, 0, rows,
+    RC_LAUNCH(PC_ATTENTION, attention_dispatch<T>((const T*)w.q, w.row_pos, w.row_req, w.tables + cur, 0, rows,
                                  tabs[cur].total_tiles, (const T*)job.dst->k_pool[l],
                                  (const T*)job.dst->v_pool[l], gd, d.n_q_heads, (T*)w.o, st));
-    RC_HIP(launch_gemm<T>((const T*)w.o, (const T*)lw.wo, nullptr, h, rows, D, nq, D, EPI_ADD_F32, st));
-    RC_HIP(launch_rmsnorm<T>(h, (const T*)lw.g_ffn, (T*)w.a, rows, D, d.rms_eps, st));
-    RC_HIP(launch_gemm<T>((const T*)w.a, (const T*)lw.w_gate, (const T*)lw.w_up, w.act, rows, F, D, F, EPI_SWIGLU_T, st));
-    RC_HIP(launch_gemm<T>((const T*)w.act, (const T*)lw.w_down, nullptr, h, rows, D, F, D, EPI_ADD_F32, st));
+    RC_LAUNCH(PC_GEMM_O, launch_gemm<T>((const T*)w.o, (const T*)lw.wo, nullptr, h, rows, D, nq, D, EPI_ADD_F32, st));
+    RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(h, (const T*)lw.g_ffn, (T*)w.a, rows, D, d.rms_eps, st));
+    RC_LAUNCH(PC_GEMM_GATE_UP, launch_gemm<T>((const T*)w.a, (const T*)lw.w_gate, (const T*)lw.w_up, w.act, rows, F, D, F, EPI_SWIGLU_T, st));
+    RC_LAUNCH(PC_GEMM_DOWN, launch_gemm<T>((const T*)w.act, (const T*)lw.w_down, nullptr, h, rows, D, F, D, EPI_ADD_F32, st));
   }
 
   // first-token logits from the last position of each request
-  RC_HIP(launch_gather_last(w.tables + cur, n_req, w.h[hbuf], w.h_last, D, st));
-  RC_HIP(launch_rmsnorm<T>(w.h_last, (const T*)job.m->g_final, (T*)w.a_last, n_req, D, d.rms_eps, st));
-  RC_HIP(launch_gemm<T>((const T*)w.a_last, (const T*)job.m->w_lm, nullptr, job.logits, n_req, d.vocab, D, d.vocab,
+  RC_LAUNCH(PC_ROWS, launch_gather_last(w.tables + cur, n_req, w.h[hbuf], w.h_last, D, st));
+  RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(w.h_last, (const T*)job.m->g_final, (T*)w.a_last, n_req, D, d.rms_eps, st));
+  RC_LAUNCH(PC_GEMM_LM_HEAD, launch_gemm<T>((const T*)w.a_last, (const T*)job.m->w_lm, nullptr, job.logits, n_req, d.vocab, D, d.vocab,
                         EPI_STORE_F32, st));
   (void)uploaded;
   return RC_OK;
@@ -437,6 +477,41 @@ rc_status rc_model_create(const rc_model_desc* desc, const rc_layer_w* layers, c
   m->w_lm = w_lm_head;
   *out = m;
   return RC_OK;
+}
+
+rc_status rc_tune_set(int32_t key, int32_t value) {
+  if (key == RC_TUNE_GEMM_TILE && value >= 0 && value <= 3) {
+    set_gemm_tile(value);
+    return RC_OK;
+  }
+  return RC_E_INVALID_ARG;
+}
+
+rc_status rc_profile_enable(int32_t on) {
+  g_prof.on = on != 0;
+  return RC_OK;
+}
+
+int32_t rc_profile_class_count(void) { return PC_COUNT; }
+
+const char* rc_profile_class_name(int32_t cls) {
+  return (cls >= 0 && cls < PC_COUNT) ? kProfNames[cls] : "";
+}
+
+rc_status rc_profile_read(float* ms, int32_t* launches) {
+  if (!ms || !launches) return RC_E_INVALID_ARG;
+  for (int i = 0; i < PC_COUNT; ++i) { ms[i] = 0.f; launches[i] = 0; }
+  rc_status rs = RC_OK;
+  for (ProfRec& r : g_prof.recs) {
+    float t = 0.f;
+    if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&t, r.a, r.b) != hipSuccess) rs = RC_E_HIP;
+    ms[r.cls] += t;
+    launches[r.cls] += 1;
+    g_prof.pool.push_back(r.a);
+    g_prof.pool.push_back(r.b);
+  }
+  g_prof.recs.clear();
+  return rs;
 }
 
 rc_status rc_model_destroy(rc_model* m) {

@@ -91,16 +91,6 @@ hipError_t launch_attention<float>(const float* q, const int* row_pos, const int
                                       n_q_heads, out, st);
 }
 
-// interim: bf16 through the same vector-ALU kernel until the MFMA kernel lands
-template <>
-hipError_t launch_attention<bf16>(const bf16* q, const int* row_pos, const int* row_req, const ReqTable* table,
-                                  int fixed_seq, int total_rows, int total_tiles, const bf16* k_pool,
-                                  const bf16* v_pool, KvGeom g, int n_q_heads, bf16* out, hipStream_t st) {
-  (void)total_tiles;
-  return launch_attention_simt<bf16>(q, row_pos, row_req, table, fixed_seq, total_rows, k_pool, v_pool, g,
-                                     n_q_heads, out, st);
-}
-
 int attention_tile_rows(int dtype, int n_q_heads, int n_kv_heads) {
   (void)dtype; (void)n_q_heads; (void)n_kv_heads;
   return 32;

@@ -20,6 +20,11 @@ __host__ __device__ inline float bf16_to_f32(bf16 x) {
 }
 // round to nearest, ties to even; NaN stays NaN
 __host__ __device__ inline bf16 f32_to_bf16(float f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  bf16 h;
+  h.v = __builtin_bit_cast(uint16_t, (__bf16)f);   // hardware convert, same rounding
+  return h;
+#endif
   union { uint32_t u; float f; } c;
   c.f = f;
   uint32_t u = c.u;
@@ -137,6 +142,8 @@ enum GemmEpilogue : int { EPI_STORE_F32 = 0, EPI_STORE_T = 1, EPI_ADD_F32 = 2, E
 template <typename T>
 hipError_t launch_gemm(const T* a, const T* w, const T* w2, void* c, int m, int n, int k, int ldc,
                        GemmEpilogue epi, hipStream_t st);
+
+void set_gemm_tile(int t);  // 0: by shape, 1: 128x256, 2: 256x256, 3: 128x128 (bf16 MFMA GEMM)
 
 template <typename T>
 hipError_t launch_rope_scatter(const float* qkv, int n_rows, const int* row_pos, const int* row_req,

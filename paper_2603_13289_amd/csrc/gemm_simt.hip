@@ -97,11 +97,4 @@ hipError_t launch_gemm<float>(const float* a, const float* w, const float* w2, v
   return launch_gemm_simt<float>(a, w, w2, c, m, n, k, ldc, epi, st);
 }
 
-// interim: bf16 through the same vector-ALU kernel until the MFMA kernel lands
-template <>
-hipError_t launch_gemm<bf16>(const bf16* a, const bf16* w, const bf16* w2, void* c, int m, int n, int k, int ldc,
-                             GemmEpilogue epi, hipStream_t st) {
-  return launch_gemm_simt<bf16>(a, w, w2, c, m, n, k, ldc, epi, st);
-}
-
 }  // namespace rc
