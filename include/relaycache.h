@@ -196,6 +196,9 @@ RC_API rc_status rc_profile_read(float* ms, int32_t* launches);
 /* Tuning knobs (process-global).  RC_TUNE_GEMM_TILE: workgroup tile of the bf16 projection GEMM,
  * 0 = chosen per shape (default), 1 = 128x256, 2 = 256x256, 3 = 128x128. */
 #define RC_TUNE_GEMM_TILE 1
+/* RC_TUNE_ATTN_CHUNK_TILES: KV tiles (of 64 keys) per attention workgroup when a query tile's KV range is
+ * split; 0 = chosen per shape (default), a value beyond the context length disables the split. */
+#define RC_TUNE_ATTN_CHUNK_TILES 2
 RC_API rc_status rc_tune_set(int32_t key, int32_t value);
 
 /* ------------------------------------------------------------ stage calls
@@ -233,9 +236,14 @@ RC_API rc_status rc_threshold_select(const float* score, int32_t n, float tau, i
 
 /* Causal grouped-query attention of n arbitrary query rows over one layer of a cache
  * (sparse rectification, Section 4.2): row i (already rotated, at position q_pos[i], ascending)
- * attends over cache rows 0..q_pos[i] of `seq`.  q, out: [n][Hq][dh] of T. */
+ * attends over cache rows 0..q_pos[i] of `seq`.  q, out: [n][Hq][dh] of T.
+ * workspace (optional, device, 256-byte aligned, rc_sparse_attention_workspace_bytes): lets the bf16
+ * kernel cut long KV ranges into chunks when there are few query rows; NULL runs every query tile
+ * in one workgroup. */
+RC_API size_t rc_sparse_attention_workspace_bytes(int32_t n, int32_t n_q_heads, const rc_kv_layer* cache);
 RC_API rc_status rc_sparse_attention(const void* q, const int32_t* q_pos, int32_t n, int32_t n_q_heads,
-                              const rc_kv_layer* cache, int32_t seq, void* out, void* stream);
+                                     const rc_kv_layer* cache, int32_t seq, void* out, void* workspace,
+                                     size_t workspace_bytes, void* stream);
 
 /* C[M][N] (float) = A[M][K] (T) * W[N][K]^T (T): the gathered-row projection GEMM. */
 RC_API rc_status rc_gemm_rows(int32_t dtype, const void* a, const void* w, float* c, int32_t m, int32_t n,

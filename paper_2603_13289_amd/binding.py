@@ -26,7 +26,7 @@ EXPORTS = [
     "rc_reuse", "rc_prefill_workspace_bytes", "rc_prefill", "rc_stage_workspace_bytes", "rc_rope_rerotate",
     "rc_vdev_score", "rc_topk", "rc_threshold_select", "rc_sparse_attention", "rc_gemm_rows",
     "rc_scatter_paged", "rc_profile_enable", "rc_profile_class_count", "rc_profile_class_name", "rc_profile_read",
-    "rc_tune_set",
+    "rc_tune_set", "rc_sparse_attention_workspace_bytes",
 ]
 
 
@@ -106,7 +106,9 @@ def _load() -> C.CDLL:
     lib.rc_threshold_select.restype = C.c_int
     lib.rc_threshold_select.argtypes = [vp, i32, C.c_float, vp, vp, vp]
     lib.rc_sparse_attention.restype = C.c_int
-    lib.rc_sparse_attention.argtypes = [vp, vp, i32, i32, C.POINTER(rc_kv_layer), i32, vp, vp]
+    lib.rc_sparse_attention.argtypes = [vp, vp, i32, i32, C.POINTER(rc_kv_layer), i32, vp, vp, sz, vp]
+    lib.rc_sparse_attention_workspace_bytes.restype = sz
+    lib.rc_sparse_attention_workspace_bytes.argtypes = [i32, i32, C.POINTER(rc_kv_layer)]
     lib.rc_gemm_rows.restype = C.c_int
     lib.rc_gemm_rows.argtypes = [i32, vp, vp, vp, i32, i32, i32, vp]
     lib.rc_scatter_paged.restype = C.c_int
@@ -376,10 +378,15 @@ def rc_threshold_select(score: torch.Tensor, n: int, tau: float, idx_out: torch.
            "rc_threshold_select")
 
 
+def rc_sparse_attention_workspace_bytes(n: int, n_q_heads: int, cache: rc_kv_layer) -> int:
+    return int(lib.rc_sparse_attention_workspace_bytes(n, n_q_heads, C.byref(cache)))
+
+
 def rc_sparse_attention(q: torch.Tensor, q_pos: torch.Tensor, n: int, n_q_heads: int, cache: rc_kv_layer, seq: int,
-                        out: torch.Tensor, stream=None) -> None:
+                        out: torch.Tensor, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.rc_sparse_attention(_ptr(q), _ptr(q_pos), n, n_q_heads, C.byref(cache), seq, _ptr(out),
-                                   _stream(stream)), "rc_sparse_attention")
+                                   _ptr(workspace), nbytes, _stream(stream)), "rc_sparse_attention")
 
 
 def rc_gemm_rows(dtype: int, a: torch.Tensor, w: torch.Tensor, c: torch.Tensor, m: int, n: int, k: int,
@@ -408,6 +415,7 @@ def rc_profile_read() -> dict:
 
 
 RC_TUNE_GEMM_TILE = 1
+RC_TUNE_ATTN_CHUNK_TILES = 2
 
 
 def rc_tune_set(key: int, value: int) -> None:

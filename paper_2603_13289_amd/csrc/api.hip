@@ -92,6 +92,7 @@ KvGeom geom_of(const rc_paged_kv& kv, const rc_model_desc& d) {
   g.max_blocks = kv.max_blocks_per_seq;
   g.n_kv_heads = d.n_kv_heads;
   g.head_dim = d.head_dim;
+  g.bs_shift = log2_if_pow2(kv.block_size);
   return g;
 }
 
@@ -103,6 +104,7 @@ KvGeom geom_of(const rc_kv_layer& kv) {
   g.max_blocks = kv.max_blocks_per_seq;
   g.n_kv_heads = kv.n_kv_heads;
   g.head_dim = kv.head_dim;
+  g.bs_shift = log2_if_pow2(kv.block_size);
   return g;
 }
 
@@ -198,6 +200,81 @@ void fill_phase(ReqTable* t, const std::vector<ReqHost>& rq, Phase ph, const Req
   t->total_tiles = tile;
 }
 
+// ---------------------------------------------------------------- attention KV-split plan of one phase
+// Query tiles whose KV range is long are cut into chunks when the phase has too few tiles to keep the
+// chip busy otherwise (sparse rectification: few rows, long context).  Row positions are known on the
+// host except for the selected rows, which are taken as evenly spread over the segment.
+constexpr int kLongKvTiles = 24;   // a query tile with more KV tiles (of 64 keys) than this may be split
+constexpr int kKvTile = 64;
+
+int est_row_pos(const ReqDev& r, int i) {
+  if (i < r.P) return i;
+  if (i < r.P + r.n_seg_rows) {
+    const int si = i - r.P;
+    if (r.seg_mode == SEG_ALL) return r.P + si;
+    if (r.seg_mode == SEG_SEL) return r.P + (int)std::min<long>((long)(si + 1) * r.S / std::max(r.n_seg_rows, 1), r.S) - 1;
+    return r.P + r.S - 1;
+  }
+  return r.P + r.S + (i - r.P - r.n_seg_rows);
+}
+
+AttnSplit plan_phase_split(ReqTable* t, int n_req, int n_kv_heads, int tile_rows, int max_pos) {
+  for (int b = 0; b < n_req; ++b) {
+    t->r[b].long_tile_start = 1 << 30;
+    t->r[b].part_base = 0;
+  }
+  long work = 0;
+  int longest = 0;
+  for (int b = 0; b < n_req; ++b) {
+    const ReqDev& r = t->r[b];
+    for (int i0 = 0; i0 < r.n_rows; i0 += tile_rows) {
+      const int n = est_row_pos(r, std::min(i0 + tile_rows, r.n_rows) - 1) / kKvTile + 1;
+      work += n;
+      longest = std::max(longest, n);
+    }
+  }
+  int chunk_tiles, thr;
+  const int forced = attention_forced_chunk_tiles();
+  if (forced > 0) {
+    chunk_tiles = thr = forced;
+  } else {
+    const long balanced = work * n_kv_heads / 512;      // KV tiles per workgroup slot if perfectly spread
+    if (longest <= kLongKvTiles || longest <= 2 * balanced) return attention_no_split();
+    thr = kLongKvTiles;
+    for (chunk_tiles = 16; chunk_tiles > 4; chunk_tiles /= 2) {
+      long wgs = 0;
+      for (int b = 0; b < n_req; ++b) {
+        const ReqDev& r = t->r[b];
+        for (int i0 = 0; i0 < r.n_rows; i0 += tile_rows) {
+          const int n = est_row_pos(r, std::min(i0 + tile_rows, r.n_rows) - 1) / kKvTile + 1;
+          if (n > thr) wgs += (long)((n + chunk_tiles - 1) / chunk_tiles) * n_kv_heads;
+        }
+      }
+      if (wgs >= 512) break;
+    }
+  }
+  const int max_tiles = (max_pos + kKvTile - 1) / kKvTile;
+  const int n_chunks = (max_tiles + chunk_tiles - 1) / chunk_tiles;
+  if (n_chunks <= 1) return attention_no_split();
+  int base = 0;
+  for (int b = 0; b < n_req; ++b) {
+    ReqDev& r = t->r[b];
+    const int tiles = (r.n_rows + tile_rows - 1) / tile_rows;
+    int start = tiles;
+    for (int j = 0; j < tiles; ++j) {
+      const int i_last = std::min((j + 1) * tile_rows, r.n_rows) - 1;
+      // a tile of prefix rows only has exactly known positions; any other tile may reach far
+      if (i_last >= r.P || i_last / kKvTile + 1 > thr) { start = j; break; }
+    }
+    r.long_tile_start = start;
+    r.part_base = base;
+    base += (tiles - start) * n_chunks;
+  }
+  if (base == 0) return attention_no_split();
+  AttnSplit sp = {n_chunks, chunk_tiles, thr, base};
+  return sp;
+}
+
 // ---------------------------------------------------------------- workspace
 struct Workspace {
   ReqTable* tables;  // PH_COUNT slots
@@ -215,10 +292,12 @@ struct Workspace {
   float* scores;
   float* h_last;
   void* a_last;
+  float* attn_part;   // partial attention results when a layer's KV range is split into chunks
   size_t bytes;
 };
 
-Workspace carve(void* base, const rc_model_desc& d, int max_rows, int max_pos, int n_req, int sum_seg) {
+Workspace carve(void* base, const rc_model_desc& d, int max_rows, int max_pos, int n_req, int sum_seg,
+                size_t attn_part_floats) {
   Workspace w;
   size_t off = 0;
   char* p = reinterpret_cast<char*>(base);
@@ -246,6 +325,7 @@ Workspace carve(void* base, const rc_model_desc& d, int max_rows, int max_pos, i
   w.scores = (float*)take(sizeof(float) * (size_t)(sum_seg > 0 ? sum_seg : 1));
   w.h_last = (float*)take(sizeof(float) * (size_t)n_req * d.d_model);
   w.a_last = take(es * (size_t)n_req * d.d_model);
+  w.attn_part = (float*)take(sizeof(float) * (attn_part_floats > 0 ? attn_part_floats : 1));
   w.bytes = off;
   return w;
 }
@@ -269,10 +349,21 @@ struct Job {
 
 template <typename T>
 hipError_t attention_dispatch(const T* q, const int* row_pos, const int* row_req, const ReqTable* table,
-                              int fixed_seq, int total_rows, int total_tiles, const T* k_pool, const T* v_pool,
-                              KvGeom g, int n_q_heads, T* out, hipStream_t st) {
-  return launch_attention<T>(q, row_pos, row_req, table, fixed_seq, total_rows, total_tiles, k_pool, v_pool, g,
-                             n_q_heads, out, st);
+                              int total_rows, int total_tiles, const T* k_pool, const T* v_pool, KvGeom g,
+                              int n_q_heads, T* out, AttnSplit sp, float* part, hipStream_t st);
+template <>
+hipError_t attention_dispatch<float>(const float* q, const int* row_pos, const int* row_req, const ReqTable* table,
+                                     int total_rows, int total_tiles, const float* k_pool, const float* v_pool,
+                                     KvGeom g, int n_q_heads, float* out, AttnSplit, float*, hipStream_t st) {
+  return launch_attention<float>(q, row_pos, row_req, table, 0, total_rows, total_tiles, k_pool, v_pool, g,
+                                 n_q_heads, out, st);
+}
+template <>
+hipError_t attention_dispatch<bf16>(const bf16* q, const int* row_pos, const int* row_req, const ReqTable* table,
+                                    int total_rows, int total_tiles, const bf16* k_pool, const bf16* v_pool,
+                                    KvGeom g, int n_q_heads, bf16* out, AttnSplit sp, float* part, hipStream_t st) {
+  return launch_attention_bf16(q, row_pos, row_req, table, 0, total_rows, total_tiles, k_pool, v_pool, g, n_q_heads,
+                               out, sp, part, st);
 }
 
 template <typename T>
@@ -280,12 +371,12 @@ rc_status run_job(const Job& job, Workspace& w, hipStream_t st) {
   const rc_model_desc& d = job.m->d;
   const int n_req = (int)job.rq.size();
   const int D = d.d_model, nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim, F = d.d_ffn;
-  const int nqkv = nq + 2 * nkv;
   const int tile_rows = attention_tile_rows(d.dtype, d.n_q_heads, d.n_kv_heads);
   const KvGeom gd = geom_of(*job.dst, d);
   const bool has_seg = job.max_seg > 0;
 
   ReqTable tabs[PH_COUNT];
+  AttnSplit splits[PH_COUNT];
   bool uploaded[PH_COUNT] = {false, false, false, false};
   for (int p = 0; p < PH_COUNT; ++p) tabs[p] = job.base;
 
@@ -295,6 +386,8 @@ rc_status run_job(const Job& job, Workspace& w, hipStream_t st) {
   int hbuf = 0;
   auto enter_phase = [&](Phase ph) -> rc_status {
     fill_phase(&tabs[ph], job.rq, ph, cur >= 0 ? &tabs[cur] : nullptr, tile_rows);
+    splits[ph] = d.dtype == RC_BF16 ? plan_phase_split(&tabs[ph], n_req, d.n_kv_heads, tile_rows, job.max_pos)
+                                    : attention_no_split();
     RC_LAUNCH(PC_TABLES, launch_upload_table(tabs[ph], w.tables + ph, st));
     uploaded[ph] = true;
     const int nb = cur >= 0 ? 1 - hbuf : hbuf;
@@ -351,16 +444,15 @@ rc_status run_job(const Job& job, Workspace& w, hipStream_t st) {
 
     float* h = w.h[hbuf];
     RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(h, (const T*)lw.g_attn, (T*)w.a, rows, D, d.rms_eps, st));
-    RC_LAUNCH(PC_GEMM_QKV, launch_gemm<T>((const T*)w.a, (const T*)lw.wq, nullptr, w.qkv, rows, nq, D, nqkv, EPI_STORE_F32, st));
-    RC_LAUNCH(PC_GEMM_QKV, launch_gemm<T>((const T*)w.a, (const T*)lw.wk, nullptr, w.qkv + nq, rows, nkv, D, nqkv, EPI_STORE_F32, st));
-    RC_LAUNCH(PC_GEMM_QKV, launch_gemm<T>((const T*)w.a, (const T*)lw.wv, nullptr, w.qkv + nq + nkv, rows, nkv, D, nqkv, EPI_STORE_F32, st));
+    RC_LAUNCH(PC_GEMM_QKV, launch_gemm_qkv<T>((const T*)w.a, (const T*)lw.wq, nq, (const T*)lw.wk, (const T*)lw.wv, nkv,
+                                              w.qkv, rows, D, st));
     // rotary on q/k at the rows' absolute positions; fresh K/V written into the cache before anyone attends
     RC_LAUNCH(PC_ROPE_SCATTER, launch_rope_scatter<T>(w.qkv, rows, w.row_pos, w.row_req, w.tables + cur, w.rope_tab, (T*)w.q,
                                   (T*)job.dst->k_pool[l], (T*)job.dst->v_pool[l],
                                   job.k_pre_pool ? (T*)job.k_pre_pool[l] : nullptr, gd, d.n_q_heads, st));
-    RC_LAUNCH(PC_ATTENTION, attention_dispatch<T>((const T*)w.q, w.row_pos, w.row_req, w.tables + cur, 0, rows,
+    RC_LAUNCH(PC_ATTENTION, attention_dispatch<T>((const T*)w.q, w.row_pos, w.row_req, w.tables + cur, rows,
                                  tabs[cur].total_tiles, (const T*)job.dst->k_pool[l],
-                                 (const T*)job.dst->v_pool[l], gd, d.n_q_heads, (T*)w.o, st));
+                                 (const T*)job.dst->v_pool[l], gd, d.n_q_heads, (T*)w.o, splits[cur], w.attn_part, st));
     RC_LAUNCH(PC_GEMM_O, launch_gemm<T>((const T*)w.o, (const T*)lw.wo, nullptr, h, rows, D, nq, D, EPI_ADD_F32, st));
     RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(h, (const T*)lw.g_ffn, (T*)w.a, rows, D, d.rms_eps, st));
     RC_LAUNCH(PC_GEMM_GATE_UP, launch_gemm<T>((const T*)w.a, (const T*)lw.w_gate, (const T*)lw.w_up, w.act, rows, F, D, F, EPI_SWIGLU_T, st));
@@ -435,6 +527,21 @@ rc_status prepare_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req
   return RC_OK;
 }
 
+// floats of partial-attention scratch the largest phase needs (bf16 path only)
+size_t attn_part_need(const Job& job) {
+  const rc_model_desc& d = job.m->d;
+  if (d.dtype != RC_BF16) return 0;
+  const int tile_rows = attention_tile_rows(d.dtype, d.n_q_heads, d.n_kv_heads);
+  size_t need = 0;
+  ReqTable t = job.base;
+  for (int p = 0; p < PH_COUNT; ++p) {
+    fill_phase(&t, job.rq, (Phase)p, nullptr, tile_rows);
+    const AttnSplit sp = plan_phase_split(&t, (int)job.rq.size(), d.n_kv_heads, tile_rows, job.max_pos);
+    need = std::max(need, attention_partial_floats(sp.total_slots, d.n_q_heads));
+  }
+  return need;
+}
+
 int max_rows_of(const Job& job) {
   int r = 0;
   for (int p = 0; p < PH_COUNT; ++p) r = std::max(r, total_rows_in(job.rq, (Phase)p));
@@ -484,6 +591,10 @@ rc_status rc_tune_set(int32_t key, int32_t value) {
     set_gemm_tile(value);
     return RC_OK;
   }
+  if (key == RC_TUNE_ATTN_CHUNK_TILES && value >= 0) {
+    set_attention_chunk_tiles(value);
+    return RC_OK;
+  }
   return RC_E_INVALID_ARG;
 }
 
@@ -522,7 +633,7 @@ rc_status rc_model_destroy(rc_model* m) {
 size_t rc_reuse_workspace_bytes(const rc_model* m, const rc_request* reqs, int32_t n_req, const rc_plan* plan) {
   Job job;
   if (prepare_reuse(m, reqs, n_req, plan, &job) != RC_OK) return 0;
-  return carve(nullptr, m->d, max_rows_of(job), job.max_pos, n_req, job.sum_seg).bytes;
+  return carve(nullptr, m->d, max_rows_of(job), job.max_pos, n_req, job.sum_seg, attn_part_need(job)).bytes;
 }
 
 rc_status rc_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req, const rc_plan* plan,
@@ -541,7 +652,7 @@ rc_status rc_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req, con
     if (reqs[b].n_seg > 0) RC_TRY(check_seq_fits(src, reqs[b].src_seq, reqs[b].src_offset + reqs[b].n_seg));
   }
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RC_E_WORKSPACE;
-  Workspace w = carve(workspace, m->d, max_rows_of(job), job.max_pos, n_req, job.sum_seg);
+  Workspace w = carve(workspace, m->d, max_rows_of(job), job.max_pos, n_req, job.sum_seg, attn_part_need(job));
   if (w.bytes > workspace_bytes) return RC_E_WORKSPACE;
   job.src = src;
   job.dst = dst;
@@ -586,7 +697,7 @@ static rc_status prepare_prefill(const rc_model* m, const void* const* x, const 
 size_t rc_prefill_workspace_bytes(const rc_model* m, const int32_t* n_tokens, int32_t n_req) {
   Job job;
   if (prepare_prefill(m, nullptr, n_tokens, nullptr, n_req, nullptr, &job) != RC_OK) return 0;
-  return carve(nullptr, m->d, max_rows_of(job), job.max_pos, n_req, 0).bytes;
+  return carve(nullptr, m->d, max_rows_of(job), job.max_pos, n_req, 0, attn_part_need(job)).bytes;
 }
 
 rc_status rc_prefill(const rc_model* m, const void* const* x, const int32_t* n_tokens, const int32_t* dst_seq,
@@ -602,7 +713,7 @@ rc_status rc_prefill(const rc_model* m, const void* const* x, const int32_t* n_t
       if (!k_pre_pool[l]) return RC_E_INVALID_ARG;
   for (int b = 0; b < n_req; ++b) RC_TRY(check_seq_fits(dst, dst_seq[b], n_tokens[b]));
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RC_E_WORKSPACE;
-  Workspace w = carve(workspace, m->d, max_rows_of(job), job.max_pos, n_req, 0);
+  Workspace w = carve(workspace, m->d, max_rows_of(job), job.max_pos, n_req, 0, attn_part_need(job));
   if (w.bytes > workspace_bytes) return RC_E_WORKSPACE;
   job.src = nullptr;
   job.dst = dst;
@@ -710,8 +821,34 @@ rc_status rc_threshold_select(const float* score, int32_t n, float tau, int32_t*
   return RC_OK;
 }
 
+// stage call: positions live on the device, so the plan only looks at the row count and the cache capacity
+static AttnSplit plan_stage_split(int tiles, int n_kv_heads, int capacity) {
+  int chunk_tiles, thr;
+  const int forced = attention_forced_chunk_tiles();
+  if (forced > 0) {
+    chunk_tiles = thr = forced;
+  } else {
+    if ((long)tiles * n_kv_heads >= 1024) return attention_no_split();
+    thr = kLongKvTiles;
+    chunk_tiles = (long)tiles * n_kv_heads >= 128 ? 16 : 4;
+  }
+  const int n_chunks = ((capacity + kKvTile - 1) / kKvTile + chunk_tiles - 1) / chunk_tiles;
+  if (n_chunks <= 1) return attention_no_split();
+  AttnSplit sp = {n_chunks, chunk_tiles, thr, tiles * n_chunks};
+  return sp;
+}
+
+size_t rc_sparse_attention_workspace_bytes(int32_t n, int32_t n_q_heads, const rc_kv_layer* cache) {
+  if (!cache || n < 1 || n_q_heads < 1 || cache->dtype != RC_BF16 || cache->n_kv_heads < 1) return 0;
+  const int tile_rows = attention_tile_rows(cache->dtype, n_q_heads, cache->n_kv_heads);
+  const int tiles = (n + tile_rows - 1) / tile_rows;
+  const AttnSplit sp = plan_stage_split(tiles, cache->n_kv_heads, cache->max_blocks_per_seq * cache->block_size);
+  return align_up(sizeof(float) * attention_partial_floats(sp.total_slots, n_q_heads));
+}
+
 rc_status rc_sparse_attention(const void* q, const int32_t* q_pos, int32_t n, int32_t n_q_heads,
-                              const rc_kv_layer* cache, int32_t seq, void* out, void* stream) {
+                              const rc_kv_layer* cache, int32_t seq, void* out, void* workspace,
+                              size_t workspace_bytes, void* stream) {
   RC_TRY(check_kv_layer(cache));
   if (!q || !q_pos || !out || n < 0 || n_q_heads < 1 || n_q_heads % cache->n_kv_heads) return RC_E_INVALID_ARG;
   if (seq < 0 || seq >= cache->n_seq) return RC_E_CAPACITY;
@@ -719,12 +856,21 @@ rc_status rc_sparse_attention(const void* q, const int32_t* q_pos, int32_t n, in
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const int tile_rows = attention_tile_rows(cache->dtype, n_q_heads, cache->n_kv_heads);
   const int tiles = (n + tile_rows - 1) / tile_rows;
-  if (cache->dtype == RC_BF16)
-    RC_HIP(launch_attention<bf16>((const bf16*)q, q_pos, nullptr, nullptr, seq, n, tiles, (const bf16*)cache->k,
-                                  (const bf16*)cache->v, geom_of(*cache), n_q_heads, (bf16*)out, st));
-  else
+  if (cache->dtype == RC_BF16) {
+    AttnSplit sp = attention_no_split();
+    float* part = nullptr;
+    if (workspace) {
+      if (reinterpret_cast<uintptr_t>(workspace) & 255u) return RC_E_WORKSPACE;
+      if (rc_sparse_attention_workspace_bytes(n, n_q_heads, cache) > workspace_bytes) return RC_E_WORKSPACE;
+      sp = plan_stage_split(tiles, cache->n_kv_heads, cache->max_blocks_per_seq * cache->block_size);
+      part = reinterpret_cast<float*>(workspace);
+    }
+    RC_HIP(launch_attention_bf16((const bf16*)q, q_pos, nullptr, nullptr, seq, n, tiles, (const bf16*)cache->k,
+                                 (const bf16*)cache->v, geom_of(*cache), n_q_heads, (bf16*)out, sp, part, st));
+  } else {
     RC_HIP(launch_attention<float>((const float*)q, q_pos, nullptr, nullptr, seq, n, tiles, (const float*)cache->k,
                                    (const float*)cache->v, geom_of(*cache), n_q_heads, (float*)out, st));
+  }
   return RC_OK;
 }
 

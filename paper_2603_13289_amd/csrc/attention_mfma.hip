@@ -13,8 +13,8 @@
 // each group of 16.  V is transposed while it is written to LDS, with that same permutation applied,
 // so each operand is one 16-byte LDS read.
 //
-// LDS rows are 8 (K: 16) chunks of 16 bytes; chunk c of row r sits at slot c ^ (r & 7): conflict-free
-// for the row-strided operand reads.  K/V rows come from the paged cache through the block table.
+// LDS rows are padded by 16 bytes (K: 272, V^T: 144 bytes apart) so that operand fetches are free of
+// bank conflicts and all LDS addresses are constants off a per-thread base.  K/V rows come from the paged cache through the block table.
 // KV tiles entirely above the tile's last query position are skipped; the causal mask is applied
 // only in tiles that reach above the tile's first query position.  Workgroups are issued longest
 // first.
@@ -29,20 +29,30 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 static constexpr int BQ = 32;    // query rows per workgroup
 static constexpr int BKV = 64;   // keys per tile
 static constexpr int DH = 128;
+static constexpr int KROW = DH * 2 + 16;   // bytes between K rows in LDS
+static constexpr int VROW = BKV * 2 + 16;  // bytes between V^T rows in LDS
 
 template <int G>
-__global__ void __launch_bounds__(64 * G)
+__global__ void __launch_bounds__(64 * G, (G <= 4 ? 2 : 1))
 attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, const ReqTable* __restrict__ table,
                  int fixed_seq, int total_rows, int total_tiles, const bf16* __restrict__ k_pool,
-                 const bf16* __restrict__ v_pool, KvGeom g, bf16* __restrict__ out) {
+                 const bf16* __restrict__ v_pool, KvGeom g, bf16* __restrict__ out, AttnSplit sp,
+                 float* __restrict__ part_o, float2* __restrict__ part_ml) {
   constexpr int NT = 64 * G;
-  __shared__ uint4 lds_k[BKV * 16];        // [64 keys][16 chunks]
-  __shared__ uint4 lds_vt[DH * 8];         // [128 d][8 chunks of 8 (permuted) keys]
+  // K rows are 256 + 16 bytes, V^T rows 128 + 16 bytes apart.  With 64 banks of 4 bytes, the 16 lanes
+  // that fetch the same 16-byte chunk of 16 consecutive rows then hit every bank exactly once, and every
+  // LDS address in the main loop is a per-thread base plus a compile-time constant.
+  __shared__ __attribute__((aligned(16))) unsigned char lds_k[BKV * KROW];
+  __shared__ __attribute__((aligned(16))) unsigned char lds_vt[DH * VROW];
 
-  const int tile = total_tiles - 1 - (int)blockIdx.x;   // late tiles see the most keys: start them first
+  // late tiles see the most keys: start them first.  With sp.n_chunks > 1 the KV range of a long query
+  // tile is cut into chunks of sp.chunk_tiles tiles, one workgroup each, whose partial results are merged
+  // by attn_merge_kernel; short tiles are done whole by their chunk-0 workgroup.
+  const int tile = total_tiles - 1 - (int)blockIdx.x / sp.n_chunks;
+  const int chunk = (int)blockIdx.x % sp.n_chunks;
   const int kvh = blockIdx.y;
   const int n_q_heads = g.n_kv_heads * G;
-  int r0, n_valid, seq;
+  int r0, n_valid, seq, split_tile = tile, part_base = 0;   // split_tile < 0: this tile is never split
   if (table) {
     int b = 0;
     while (b + 1 < table->n_req && tile >= table->r[b + 1].tile_base) ++b;
@@ -50,6 +60,8 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
     r0 = rq.row_base + (tile - rq.tile_base) * BQ;
     n_valid = min(BQ, rq.row_base + rq.n_rows - r0);
     seq = rq.dst_seq;
+    split_tile = tile - rq.tile_base - rq.long_tile_start;
+    part_base = rq.part_base;
   } else {
     r0 = tile * BQ;
     n_valid = min(BQ, total_rows - r0);
@@ -85,49 +97,92 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   float m_run = -INFINITY, l_run = 0.f;
   const float c_scale = 1.4426950408889634f / sqrtf((float)DH);   // log2(e) / sqrt(dh)
 
-  const int n_tiles = last_pos / BKV + 1;
-  for (int t = 0; t < n_tiles; ++t) {
-    const int kv0 = t * BKV;
-    __syncthreads();   // previous tile fully consumed
-    // K tile: 64 rows x 16 chunks
-    for (int idx = tid; idx < BKV * 16; idx += NT) {
-      const int row = idx >> 4, ch = idx & 15;
+  // K/V tile staging: every thread owns KPER 16-byte chunks of the K tile (rows krow0 + i*KSTEP, chunk
+  // tid%16) and VPER blocks of the V tile (4 consecutive keys x 8 d).  The next tile is fetched into
+  // registers while the current one is multiplied.
+  constexpr int KSTEP = NT / 16;
+  constexpr int KPER = (BKV + KSTEP - 1) / KSTEP;
+  constexpr int VPER = (16 + KSTEP - 1) / KSTEP;
+  const int krow0 = tid >> 4, kch = tid & 15;      // K: row, 16-byte chunk
+  const int vdch0 = tid >> 4, vquad = tid & 15;    // V: chunk of 8 d, quad of 4 keys
+  const bool contig = g.max_blocks == 1;           // one block per sequence: rows are a linear function of pos
+  const bf16 *kbase = nullptr, *vbase = nullptr;
+  if (contig) {
+    const size_t o = kv_row_offset(g, seq, 0, kvh);
+    kbase = k_pool + o + kch * 8;
+    vbase = v_pool + o;
+  }
+  uint4 rk[KPER], rv[VPER][4];
+  auto fetch = [&](int kv0) {
+    const bool full = kv0 + BKV - 1 <= last_pos;   // uniform: only a query tile's last KV tile can be ragged
+#pragma unroll
+    for (int i = 0; i < KPER; ++i) {
+      const int row = krow0 + i * KSTEP;
       const int pos = kv0 + row;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (pos <= last_pos) v = *reinterpret_cast<const uint4*>(k_pool + kv_row_offset(g, seq, pos, kvh) + ch * 8);
-      lds_k[row * 16 + (ch ^ (row & 7))] = v;
+      rk[i] = make_uint4(0, 0, 0, 0);
+      if (row < BKV && (full || pos <= last_pos)) {
+        const bf16* src = contig ? kbase + (size_t)pos * DH : k_pool + kv_row_offset(g, seq, pos, kvh) + kch * 8;
+        rk[i] = *reinterpret_cast<const uint4*>(src);
+      }
     }
-    // V tile, transposed: item = (quad of 4 consecutive keys, chunk of 8 d)
-    for (int idx = tid; idx < (BKV / 4) * 16; idx += NT) {
-      const int dch = idx >> 4, quad = idx & 15;   // 16 lanes = 16 quads = 16 distinct 8-byte LDS slots
-      uint32_t w[4][4];
+#pragma unroll
+    for (int i = 0; i < VPER; ++i) {
+      const int dch = vdch0 + i * KSTEP;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        const int pos = kv0 + quad * 4 + kk;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (pos <= last_pos) v = *reinterpret_cast<const uint4*>(v_pool + kv_row_offset(g, seq, pos, kvh) + dch * 8);
-        w[kk][0] = v.x; w[kk][1] = v.y; w[kk][2] = v.z; w[kk][3] = v.w;
-      }
-      // key = 16 grp + 8 a + 4 h + c  ->  column 16 grp + 8 h + 4 a + c ; a quad shares (grp, a, h)
-      const int key0 = quad * 4;
-      const int col = (key0 & ~15) + 8 * ((key0 >> 2) & 1) + 4 * ((key0 >> 3) & 1);
-      const int chunk = col >> 3, within = (col & 7) >> 2;   // 8-byte half of the 16-byte chunk
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int d = dch * 8 + e;
-        const int wi = e >> 1;
-        uint2 pk;
-        if (e & 1) {
-          pk.x = (w[0][wi] >> 16) | (w[1][wi] & 0xffff0000u);
-          pk.y = (w[2][wi] >> 16) | (w[3][wi] & 0xffff0000u);
-        } else {
-          pk.x = (w[0][wi] & 0xffffu) | (w[1][wi] << 16);
-          pk.y = (w[2][wi] & 0xffffu) | (w[3][wi] << 16);
+        const int pos = kv0 + vquad * 4 + kk;
+        rv[i][kk] = make_uint4(0, 0, 0, 0);
+        if (dch < 16 && (full || pos <= last_pos)) {
+          const bf16* src = contig ? vbase + (size_t)pos * DH + dch * 8 : v_pool + kv_row_offset(g, seq, pos, kvh) + dch * 8;
+          rv[i][kk] = *reinterpret_cast<const uint4*>(src);
         }
-        reinterpret_cast<uint2*>(&lds_vt[d * 8 + (chunk ^ (d & 7))])[within] = pk;
       }
     }
+  };
+  // V transposed: key = 16 grp + 8 a + 4 h + c goes to column 16 grp + 8 h + 4 a + c; a quad shares (grp, a, h)
+  const int vkey0 = vquad * 4;
+  const int vcol = (vkey0 & ~15) + 8 * ((vkey0 >> 2) & 1) + 4 * ((vkey0 >> 3) & 1);
+  unsigned char* const k_wr = lds_k + krow0 * KROW + kch * 16;
+  unsigned char* const v_wr = lds_vt + vdch0 * 8 * VROW + vcol * 2;
+  auto stage = [&]() {
+#pragma unroll
+    for (int i = 0; i < KPER; ++i)
+      if (krow0 + i * KSTEP < BKV) *reinterpret_cast<uint4*>(k_wr + i * KSTEP * KROW) = rk[i];
+#pragma unroll
+    for (int i = 0; i < VPER; ++i) {
+      if (vdch0 + i * KSTEP >= 16) continue;
+      const uint32_t w[4][4] = {{rv[i][0].x, rv[i][0].y, rv[i][0].z, rv[i][0].w},
+                                {rv[i][1].x, rv[i][1].y, rv[i][1].z, rv[i][1].w},
+                                {rv[i][2].x, rv[i][2].y, rv[i][2].z, rv[i][2].w},
+                                {rv[i][3].x, rv[i][3].y, rv[i][3].z, rv[i][3].w}};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int wi = e >> 1;
+        // byte select: even e packs the low halves of two words, odd e the high halves
+        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+        uint2 pk;
+        pk.x = __builtin_amdgcn_perm(w[1][wi], w[0][wi], sel);
+        pk.y = __builtin_amdgcn_perm(w[3][wi], w[2][wi], sel);
+        *reinterpret_cast<uint2*>(v_wr + (i * KSTEP * 8 + e) * VROW) = pk;
+      }
+    }
+  };
+  // operand fetch addresses: K block b, dh step s -> k_rd + b*32*KROW + s*32 ; V^T block db, key step tt
+  const unsigned char* const k_rd = lds_k + ql * KROW + half * 16;
+  const unsigned char* const v_rd = lds_vt + ql * VROW + half * 16;
+
+  const int n_kv_tiles = last_pos / BKV + 1;
+  const bool is_split = sp.n_chunks > 1 && split_tile >= 0 && n_kv_tiles > sp.long_thr;
+  const int t_begin = is_split ? chunk * sp.chunk_tiles : 0;
+  const int t_end = is_split ? min(n_kv_tiles, t_begin + sp.chunk_tiles) : n_kv_tiles;
+  if (t_begin >= t_end || (!is_split && chunk != 0)) return;   // nothing for this workgroup (uniform)
+  fetch(t_begin * BKV);
+  for (int t = t_begin; t < t_end; ++t) {
+    const int kv0 = t * BKV;
+    __syncthreads();   // previous tile fully consumed
+    stage();
     __syncthreads();
+    if (t + 1 < t_end) fetch(kv0 + BKV);
 
     // S^T = K Q^T : two blocks of 32 keys
     f32x16 acc_s[2];
@@ -135,32 +190,44 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
     for (int b = 0; b < 2; ++b) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc_s[b][e] = 0.f;
-      const int row = 32 * b + ql;
 #pragma unroll
       for (int s = 0; s < 8; ++s) {
-        const bf16x8 kf = __builtin_bit_cast(bf16x8, lds_k[row * 16 + ((2 * s + half) ^ (row & 7))]);
+        const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(k_rd + b * 32 * KROW + s * 32));
         acc_s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], acc_s[b], 0, 0, 0);
       }
     }
-    // scale, mask, running softmax.  Element e of block b is key kv0 + 32 b + 8 (e/4) + 4 half + e%4.
-    const bool need_mask = kv0 + BKV - 1 > first_pos;
-    float mx = -INFINITY;
+    // running softmax on raw scores; the 1/sqrt(dh) * log2(e) factor is folded into the exponent.
+    // Element e of block b is key kv0 + 32 b + 8 (e/4) + 4 half + e%4.  Only tiles that reach above the
+    // tile's first query position need the causal mask.
+    if (kv0 + BKV - 1 > first_pos) {
+      asm volatile("; causal mask tile" ::: "memory");   // keeps this a real (wave-uniform) branch
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int key = kv0 + 32 * b + 8 * (e >> 2) + 4 * half + (e & 3);
+          if (key > my_pos) acc_s[b][e] = -INFINITY;
+        }
+    }
+    float mx = acc_s[0][0];
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        float s = acc_s[b][e] * c_scale;
-        if (need_mask) {
-          const int key = kv0 + 32 * b + 8 * (e >> 2) + 4 * half + (e & 3);
-          if (key > my_pos) s = -INFINITY;
-        }
-        acc_s[b][e] = s;
-        mx = fmaxf(mx, s);
-      }
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, acc_s[b][e]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);      // finite: key 0 is visible to every row in tile 0
-    const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
+    // m_run is kept in the scaled (log2) domain.  A row that has not seen a visible key yet keeps
+    // m_run = -inf; m_use avoids inf - inf in that case (all its p are then 0).
+    const float m_new = fmaxf(m_run, mx * c_scale);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    if (__any(m_new > m_run)) {          // wave-uniform: rescale only when some row's maximum moved
+      const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
+      l_run *= corr;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc_o[i][e] *= corr;
+      m_run = m_new;
+    }
     float psum = 0.f;
     bf16x8 pf[4];
 #pragma unroll
@@ -170,29 +237,39 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
         f32x8 p;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          p[j] = __builtin_amdgcn_exp2f(acc_s[b][8 * u + j] - m_new);
+          p[j] = __builtin_amdgcn_exp2f(fmaf(acc_s[b][8 * u + j], c_scale, -m_use));
           psum += p[j];
         }
         pf[2 * b + u] = __builtin_convertvector(p, bf16x8);
       }
-    l_run = l_run * corr + psum;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc_o[i][e] *= corr;
+    l_run += psum;
     // O^T += V^T P
 #pragma unroll
     for (int db = 0; db < 4; ++db) {
-      const int d = 32 * db + ql;
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt) {
-        const bf16x8 vf = __builtin_bit_cast(bf16x8, lds_vt[d * 8 + ((2 * tt + half) ^ (d & 7))]);
+        const bf16x8 vf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(v_rd + db * 32 * VROW + tt * 32));
         acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[tt], acc_o[db], 0, 0, 0);
       }
     }
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (is_split) {
+    // partial result of this chunk: un-normalised O, running maximum (log2 domain) and sum
+    const size_t slot = ((size_t)(part_base + split_tile * sp.n_chunks + chunk) * n_q_heads + head) * BQ + ql;
+    if (half == 0) part_ml[slot] = make_float2(m_run, l_tot);
+    float* po = part_o + slot * DH;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {
+        const int d = 32 * db + 8 * e4 + 4 * half;
+        *reinterpret_cast<float4*>(po + d) = make_float4(acc_o[db][4 * e4 + 0], acc_o[db][4 * e4 + 1],
+                                                          acc_o[db][4 * e4 + 2], acc_o[db][4 * e4 + 3]);
+      }
+    return;
+  }
   if (q_ok) {
     const float inv = 1.0f / l_tot;
     bf16* orow = out + ((size_t)my_row * n_q_heads + head) * DH;
@@ -209,13 +286,95 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   }
 }
 
+// Merge of the KV chunks of one (row, head): one wavefront each, two head-dim elements per lane.
+// Only rows of split tiles take part; chunk c holds keys for a row iff its first key position is <=
+// the row's position.
+__global__ void __launch_bounds__(256)
+attn_merge_kernel(const int* __restrict__ row_pos, const int* __restrict__ row_req, const ReqTable* __restrict__ table,
+                  int total_rows, int n_q_heads, AttnSplit sp, const float* __restrict__ part_o,
+                  const float2* __restrict__ part_ml, bf16* __restrict__ out) {
+  const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (item >= total_rows * n_q_heads) return;
+  const int r = item / n_q_heads, head = item - r * n_q_heads;
+  int split_tile, ql, part_base = 0, tile_last_row;
+  if (table) {
+    const ReqDev& rq = table->r[row_req[r]];
+    const int lt = (r - rq.row_base) / BQ;
+    split_tile = lt - rq.long_tile_start;
+    ql = (r - rq.row_base) % BQ;
+    part_base = rq.part_base;
+    tile_last_row = min(rq.row_base + (lt + 1) * BQ, rq.row_base + rq.n_rows) - 1;
+  } else {
+    split_tile = r / BQ;
+    ql = r % BQ;
+    tile_last_row = min((split_tile + 1) * BQ, total_rows) - 1;
+  }
+  const int n_kv_tiles = row_pos[tile_last_row] / BKV + 1;
+  if (split_tile < 0 || n_kv_tiles <= sp.long_thr) return;   // this row's tile was done by one workgroup
+  const int nc = min(sp.n_chunks, row_pos[r] / (sp.chunk_tiles * BKV) + 1);
+  const size_t slot0 = ((size_t)(part_base + split_tile * sp.n_chunks) * n_q_heads + head) * BQ + ql;
+  const size_t cstride = (size_t)n_q_heads * BQ;
+  float m = -INFINITY;
+  for (int c = 0; c < nc; ++c) m = fmaxf(m, part_ml[slot0 + c * cstride].x);
+  float l = 0.f, o0 = 0.f, o1 = 0.f;
+  for (int c = 0; c < nc; ++c) {
+    const size_t slot = slot0 + c * cstride;
+    const float2 ml = part_ml[slot];
+    const float wgt = (ml.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml.x - m);
+    l += ml.y * wgt;
+    const float2 o = *reinterpret_cast<const float2*>(part_o + slot * DH + 2 * lane);
+    o0 += o.x * wgt;
+    o1 += o.y * wgt;
+  }
+  const float inv = 1.0f / l;
+  const uint32_t pk = (uint32_t)f32_to_bf16(o0 * inv).v | ((uint32_t)f32_to_bf16(o1 * inv).v << 16);
+  *reinterpret_cast<uint32_t*>(out + ((size_t)r * n_q_heads + head) * DH + 2 * lane) = pk;
+}
+
+static int g_force_chunk_tiles = 0;   // 0: by shape; > 0: this many KV tiles per chunk
+void set_attention_chunk_tiles(int t) { g_force_chunk_tiles = t; }
+int attention_forced_chunk_tiles() { return g_force_chunk_tiles; }
+
+size_t attention_partial_floats(int total_slots, int n_q_heads) {
+  return (size_t)total_slots * n_q_heads * BQ * (DH + 2);
+}
+
 template <int G>
 static hipError_t launch_g(const bf16* q, const int* row_pos, const ReqTable* table, int fixed_seq, int total_rows,
                            int total_tiles, const bf16* k_pool, const bf16* v_pool, KvGeom g, bf16* out,
-                           hipStream_t st) {
-  dim3 grid((unsigned)total_tiles, (unsigned)g.n_kv_heads);
+                           AttnSplit sp, float* part, hipStream_t st) {
+  dim3 grid((unsigned)(total_tiles * sp.n_chunks), (unsigned)g.n_kv_heads);
+  float* part_o = part;
+  float2* part_ml = reinterpret_cast<float2*>(part + (size_t)sp.total_slots * g.n_kv_heads * G * BQ * DH);
   attn_mfma_kernel<G><<<grid, 64 * G, 0, st>>>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool, v_pool,
-                                               g, out);
+                                               g, out, sp, part_o, part_ml);
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_bf16(const bf16* q, const int* row_pos, const int* row_req, const ReqTable* table,
+                                 int fixed_seq, int total_rows, int total_tiles, const bf16* k_pool,
+                                 const bf16* v_pool, KvGeom g, int n_q_heads, bf16* out, AttnSplit sp, float* part,
+                                 hipStream_t st) {
+  if (total_rows <= 0) return hipSuccess;
+  const int G = n_q_heads / g.n_kv_heads;
+  if (!part || sp.total_slots <= 0) sp = attention_no_split();
+  hipError_t e;
+  switch (G) {
+#define RC_ATTN_CASE(GG) \
+    case GG: e = launch_g<GG>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool, v_pool, g, out, sp, part, st); break;
+    RC_ATTN_CASE(1) RC_ATTN_CASE(2) RC_ATTN_CASE(3) RC_ATTN_CASE(4)
+    RC_ATTN_CASE(5) RC_ATTN_CASE(6) RC_ATTN_CASE(7) RC_ATTN_CASE(8)
+#undef RC_ATTN_CASE
+    default:  // wider groups: one wavefront per (row, head) on the vector ALUs
+      return launch_attention_simt<bf16>(q, row_pos, row_req, table, fixed_seq, total_rows, k_pool, v_pool, g,
+                                         n_q_heads, out, st);
+  }
+  if (e != hipSuccess || sp.n_chunks == 1) return e;
+  const float2* part_ml = reinterpret_cast<const float2*>(part + (size_t)sp.total_slots * n_q_heads * BQ * DH);
+  const int items = total_rows * n_q_heads;
+  attn_merge_kernel<<<(items + 3) / 4, 256, 0, st>>>(row_pos, row_req, table, total_rows, n_q_heads, sp, part, part_ml,
+                                                     out);
   return hipGetLastError();
 }
 
@@ -223,21 +382,9 @@ template <>
 hipError_t launch_attention<bf16>(const bf16* q, const int* row_pos, const int* row_req, const ReqTable* table,
                                   int fixed_seq, int total_rows, int total_tiles, const bf16* k_pool,
                                   const bf16* v_pool, KvGeom g, int n_q_heads, bf16* out, hipStream_t st) {
-  if (total_rows <= 0) return hipSuccess;
-  const int G = n_q_heads / g.n_kv_heads;
-  switch (G) {
-    case 1: return launch_g<1>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool, v_pool, g, out, st);
-    case 2: return launch_g<2>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool, v_pool, g, out, st);
-    case 3: return launch_g<3>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool, v_pool, g, out, st);
-    case 4: return launch_g<4>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool, v_pool, g, out, st);
-    case 5: return launch_g<5>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool, v_pool, g, out, st);
-    case 6: return launch_g<6>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool, v_pool, g, out, st);
-    case 7: return launch_g<7>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool, v_pool, g, out, st);
-    case 8: return launch_g<8>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool, v_pool, g, out, st);
-    default:  // wider groups: one wavefront per (row, head) on the vector ALUs
-      return launch_attention_simt<bf16>(q, row_pos, row_req, table, fixed_seq, total_rows, k_pool, v_pool, g,
-                                         n_q_heads, out, st);
-  }
+  const AttnSplit sp = attention_no_split();
+  return launch_attention_bf16(q, row_pos, row_req, table, fixed_seq, total_rows, total_tiles, k_pool, v_pool, g,
+                               n_q_heads, out, sp, nullptr, st);
 }
 
 }  // namespace rc

@@ -82,14 +82,31 @@ struct KvGeom {
   const int32_t* block_table;  // device [n_seq][max_blocks]
   int max_blocks;
   int n_kv_heads, head_dim;
+  int bs_shift;  // log2(block_size) when it is a power of two, else -1
 };
+
+inline int log2_if_pow2(int x) {
+  if (x <= 0 || (x & (x - 1))) return -1;
+  int s = 0;
+  while ((1 << s) < x) ++s;
+  return s;
+}
 
 // element offset of (seq, pos, head, 0) inside one layer's pool; positions, table slots and block ids
 // are clamped to the geometry, so bad indices read or write a wrong row but never leave the pool
 __device__ inline size_t kv_row_offset(const KvGeom& g, int seq, int pos, int head) {
   pos = max(pos, 0);
-  const int bi = min(pos / g.block_size, g.max_blocks - 1);
-  const int slot = min(pos - bi * g.block_size, g.block_size - 1);
+  int bi, slot;
+  if (g.max_blocks == 1) {            // contiguous cache: one block per sequence
+    bi = 0;
+    slot = min(pos, g.block_size - 1);
+  } else if (g.bs_shift >= 0) {       // power-of-two pages: no integer division
+    bi = min(pos >> g.bs_shift, g.max_blocks - 1);
+    slot = min(pos - (bi << g.bs_shift), g.block_size - 1);
+  } else {
+    bi = min(pos / g.block_size, g.max_blocks - 1);
+    slot = min(pos - bi * g.block_size, g.block_size - 1);
+  }
   int blk = g.block_table[(size_t)seq * g.max_blocks + bi];
   blk = min(max(blk, 0), g.n_blocks - 1);
   return (((size_t)blk * g.n_kv_heads + head) * g.block_size + slot) * (size_t)g.head_dim;
@@ -104,6 +121,7 @@ struct ReqDev {
   int old_row_base, old_n_seg_rows, old_seg_mode, has_old;  // phase being left (has_old = 0: inputs)
   int dst_seq, src_seq, src_offset, rot_delta;           // rot_delta valid when keys are rotated
   int sel_base, score_base, tile_base, k_is_pre_rope;
+  int long_tile_start, part_base;   // attention KV split: first local tile that may be split, its slot base
   const void* x_prefix;
   const void* h_start;
   const void* x_suffix;
@@ -143,6 +161,11 @@ template <typename T>
 hipError_t launch_gemm(const T* a, const T* w, const T* w2, void* c, int m, int n, int k, int ldc,
                        GemmEpilogue epi, hipStream_t st);
 
+// C[M][nq + 2 nkv] (float) = A * [wq; wk; wv]^T
+template <typename T>
+hipError_t launch_gemm_qkv(const T* a, const T* wq, int nq, const T* wk, const T* wv, int nkv, float* c, int m,
+                           int k, hipStream_t st);
+
 void set_gemm_tile(int t);  // 0: by shape, 1: 128x256, 2: 256x256, 3: 128x128 (bf16 MFMA GEMM)
 
 template <typename T>
@@ -162,6 +185,21 @@ hipError_t launch_attention_simt(const T* q, const int* row_pos, const int* row_
                                  int fixed_seq, int total_rows, const T* k_pool, const T* v_pool, KvGeom g,
                                  int n_q_heads, T* out, hipStream_t st);
 int attention_tile_rows(int dtype, int n_q_heads, int n_kv_heads);  // query rows per attention tile
+
+// bf16 attention with an optional split of every query tile's KV range into chunks (partial results
+// in `part`, merged by a second kernel).  part == nullptr: no split.
+// A query tile whose KV range spans more than long_thr tiles is cut into chunks of chunk_tiles tiles;
+// n_chunks is the grid's chunk dimension (1: no split at all), total_slots the (tile, chunk) slots of
+// partial results the plan may touch.
+struct AttnSplit { int n_chunks, chunk_tiles, long_thr, total_slots; };
+inline AttnSplit attention_no_split() { AttnSplit sp = {1, 1 << 24, 1 << 24, 0}; return sp; }
+int attention_forced_chunk_tiles();
+void set_attention_chunk_tiles(int t);  // 0: by shape; > 0: forced KV tiles per chunk
+size_t attention_partial_floats(int total_slots, int n_q_heads);
+hipError_t launch_attention_bf16(const bf16* q, const int* row_pos, const int* row_req, const ReqTable* table,
+                                 int fixed_seq, int total_rows, int total_tiles, const bf16* k_pool,
+                                 const bf16* v_pool, KvGeom g, int n_q_heads, bf16* out, AttnSplit sp, float* part,
+                                 hipStream_t st);
 
 template <typename T>
 hipError_t launch_vdev_score(const T* v_fresh, int fresh_row_stride, const T* v_pool, KvGeom g,

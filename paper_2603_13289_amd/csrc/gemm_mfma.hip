@@ -6,8 +6,10 @@
 // consecutive k per lane), so tiles go global -> LDS -> registers without any transpose.
 //
 // Workgroup tile BM x BN, K step 64.  LDS holds one A tile [BM][64] and one B tile [BN][64] as rows of
-// eight 16-byte chunks; chunk c of row r is stored at slot c ^ (r & 7), which makes both the
-// row-contiguous fill and the row-strided MFMA fragment reads bank-conflict free without padding.
+// eight 16-byte chunks; chunk c of row r is stored at slot c ^ ((r >> 1) & 7).  With 64 LDS banks of
+// 4 bytes a 128-byte row covers half the banks, so 16 lanes reading the same chunk of 16 consecutive
+// rows (one MFMA operand fetch) touch 16 different (row parity, slot) pairs = all 64 banks once, and
+// the row-contiguous fill is conflict free as well.  No padding is needed.
 // The next K step is fetched into registers while the current one is multiplied.
 // Each wavefront owns a (BM/WAVES_M) x (BN/WAVES_N) sub-tile built from 32x32x16 MFMA blocks.
 //
@@ -32,8 +34,8 @@ __device__ inline float silu_mf(float x) { return x / (1.0f + __expf(-x)); }
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool DUAL, int OCC>
 __global__ void __launch_bounds__(WAVES_M * WAVES_N * 64, OCC)
 gemm_mfma_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const bf16* __restrict__ w2,
-                 void* __restrict__ c, int m, int n, int k, int ldc, int epi, int tiles_m, int total_tiles,
-                 int per_xcd) {
+                 const bf16* __restrict__ w3, int ns1, int ns2, void* __restrict__ c, int m, int n, int k, int ldc,
+                 int epi, int tiles_m, int total_tiles, int per_xcd) {
   constexpr int NT = WAVES_M * WAVES_N * 64;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   constexpr int FM = WTM / 32, FN = WTN / 32;
@@ -70,7 +72,11 @@ gemm_mfma_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const b
       const int col = n0 + row - half * (BN / 2);
       pb[i] = (col < n) ? (half ? w2 : w) + (size_t)col * k + ch * 8 : nullptr;
     } else {
-      pb[i] = (n0 + row < n) ? w + (size_t)(n0 + row) * k + ch * 8 : nullptr;
+      // output columns [0, ns1) come from w, [ns1, ns2) from w2, [ns2, n) from w3 (fused q|k|v projection)
+      const int col = n0 + row;
+      const bf16* src = col < ns1 ? w + (size_t)col * k : (col < ns2 ? w2 + (size_t)(col - ns1) * k
+                                                                     : w3 + (size_t)(col - ns2) * k);
+      pb[i] = (col < n) ? src + ch * 8 : nullptr;
     }
   }
 
@@ -110,12 +116,12 @@ gemm_mfma_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const b
 #pragma unroll
     for (int i = 0; i < A_PER; ++i) {
       const int row = (tid + i * NT) >> 3;
-      lds_a[row * 8 + (ch ^ (row & 7))] = ra[i];
+      lds_a[row * 8 + (ch ^ ((row >> 1) & 7))] = ra[i];
     }
 #pragma unroll
     for (int i = 0; i < B_PER; ++i) {
       const int row = (tid + i * NT) >> 3;
-      lds_b[row * 8 + (ch ^ (row & 7))] = rb[i];
+      lds_b[row * 8 + (ch ^ ((row >> 1) & 7))] = rb[i];
     }
     __syncthreads();
     if (k0 + BK < k) fetch(k0 + BK);
@@ -125,10 +131,10 @@ gemm_mfma_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const b
       const int chunk = 2 * s + khalf;
 #pragma unroll
       for (int i = 0; i < FM; ++i)
-        fa[i] = __builtin_bit_cast(bf16x8, lds_a[arow[i] * 8 + (chunk ^ (arow[i] & 7))]);
+        fa[i] = __builtin_bit_cast(bf16x8, lds_a[arow[i] * 8 + (chunk ^ ((arow[i] >> 1) & 7))]);
 #pragma unroll
       for (int j = 0; j < FN; ++j)
-        fb[j] = __builtin_bit_cast(bf16x8, lds_b[brow[j] * 8 + (chunk ^ (brow[j] & 7))]);
+        fb[j] = __builtin_bit_cast(bf16x8, lds_b[brow[j] * 8 + (chunk ^ ((brow[j] >> 1) & 7))]);
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -170,8 +176,8 @@ static int g_gemm_tile = 0;   // 0: choose by shape; 1: 128x256; 2: 256x256; 3: 
 void set_gemm_tile(int t) { g_gemm_tile = t; }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int OCC>
-static hipError_t launch_cfg(const bf16* a, const bf16* w, const bf16* w2, void* c, int m, int n, int k, int ldc,
-                             GemmEpilogue epi, hipStream_t st) {
+static hipError_t launch_cfg(const bf16* a, const bf16* w, const bf16* w2, const bf16* w3, int ns1, int ns2, void* c,
+                             int m, int n, int k, int ldc, GemmEpilogue epi, hipStream_t st) {
   const bool dual = epi == EPI_SWIGLU_T;
   const int bn_out = dual ? BN / 2 : BN;
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + bn_out - 1) / bn_out;
@@ -180,29 +186,43 @@ static hipError_t launch_cfg(const bf16* a, const bf16* w, const bf16* w2, void*
   const dim3 grid((unsigned)(per_xcd * XCDS));
   constexpr int NT = WAVES_M * WAVES_N * 64;
   if (dual)
-    gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, true, OCC><<<grid, NT, 0, st>>>(a, w, w2, c, m, n, k, ldc, (int)epi,
-                                                                              tiles_m, total, per_xcd);
+    gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, true, OCC><<<grid, NT, 0, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc,
+                                                                              (int)epi, tiles_m, total, per_xcd);
   else
-    gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, false, OCC><<<grid, NT, 0, st>>>(a, w, w2, c, m, n, k, ldc, (int)epi,
-                                                                               tiles_m, total, per_xcd);
+    gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, false, OCC><<<grid, NT, 0, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc,
+                                                                               (int)epi, tiles_m, total, per_xcd);
   return hipGetLastError();
+}
+
+static hipError_t dispatch(const bf16* a, const bf16* w, const bf16* w2, const bf16* w3, int ns1, int ns2, void* c,
+                           int m, int n, int k, int ldc, GemmEpilogue epi, hipStream_t st) {
+  if (m <= 0 || n <= 0) return hipSuccess;
+  int tile = g_gemm_tile;
+  if (tile == 0) {
+    // enough 128x256 tiles to fill the chip twice over -> big tiles; otherwise smaller ones
+    const int bn_out = epi == EPI_SWIGLU_T ? 128 : 256;
+    const long t1 = (long)((m + 127) / 128) * ((n + bn_out - 1) / bn_out);
+    tile = t1 >= 400 ? 1 : 3;
+  }
+  switch (tile) {
+    case 2: return launch_cfg<256, 256, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);
+    case 3: return launch_cfg<128, 128, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);
+    default: return launch_cfg<128, 256, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);
+  }
 }
 
 template <>
 hipError_t launch_gemm<bf16>(const bf16* a, const bf16* w, const bf16* w2, void* c, int m, int n, int k, int ldc,
                              GemmEpilogue epi, hipStream_t st) {
-  if (m <= 0 || n <= 0) return hipSuccess;
-  int tile = g_gemm_tile;
-  if (tile == 0) {
-    // enough 128x256 tiles to fill the chip twice over -> big tiles; otherwise smaller ones
-    const long t1 = (long)((m + 127) / 128) * ((n + (epi == EPI_SWIGLU_T ? 127 : 255)) / (epi == EPI_SWIGLU_T ? 128 : 256));
-    tile = t1 >= 400 ? 1 : 3;
-  }
-  switch (tile) {
-    case 2: return launch_cfg<256, 256, 4, 2, 1>(a, w, w2, c, m, n, k, ldc, epi, st);
-    case 3: return launch_cfg<128, 128, 2, 2, 2>(a, w, w2, c, m, n, k, ldc, epi, st);
-    default: return launch_cfg<128, 256, 2, 2, 2>(a, w, w2, c, m, n, k, ldc, epi, st);
-  }
+  return dispatch(a, w, w2, nullptr, n, n, c, m, n, k, ldc, epi, st);
+}
+
+// q | k | v projections of the same rows as one GEMM over the concatenated output columns
+template <>
+hipError_t launch_gemm_qkv<bf16>(const bf16* a, const bf16* wq, int nq, const bf16* wk, const bf16* wv, int nkv,
+                                 float* c, int m, int k, hipStream_t st) {
+  const int n = nq + 2 * nkv;
+  return dispatch(a, wq, wk, wv, nq, nq + nkv, c, m, n, k, n, EPI_STORE_F32, st);
 }
 
 }  // namespace rc

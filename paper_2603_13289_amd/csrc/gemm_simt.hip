@@ -97,4 +97,15 @@ hipError_t launch_gemm<float>(const float* a, const float* w, const float* w2, v
   return launch_gemm_simt<float>(a, w, w2, c, m, n, k, ldc, epi, st);
 }
 
+template <>
+hipError_t launch_gemm_qkv<float>(const float* a, const float* wq, int nq, const float* wk, const float* wv, int nkv,
+                                  float* c, int m, int k, hipStream_t st) {
+  const int n = nq + 2 * nkv;
+  hipError_t e = launch_gemm_simt<float>(a, wq, nullptr, c, m, nq, k, n, EPI_STORE_F32, st);
+  if (e != hipSuccess) return e;
+  e = launch_gemm_simt<float>(a, wk, nullptr, c + nq, m, nkv, k, n, EPI_STORE_F32, st);
+  if (e != hipSuccess) return e;
+  return launch_gemm_simt<float>(a, wv, nullptr, c + nq + nkv, m, nkv, k, n, EPI_STORE_F32, st);
+}
+
 }  // namespace rc

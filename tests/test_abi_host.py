@@ -102,7 +102,7 @@ def test_stage_argument_errors():
     rc.rc_topk(s, 8, 0, idx)       # k = 0 is a no-op, no launch
     kv = rc.PagedKV.contiguous(1, 1, 16, 2, 64, rc.RC_F32, device="cpu")
     lay = kv.layer(0)
-    assert status(lambda: rc.rc_sparse_attention(s, idx, 1, 3, lay, 0, s)) == rc.RC_E_INVALID_ARG   # 3 % 2 heads
-    assert status(lambda: rc.rc_sparse_attention(s, idx, 1, 2, lay, 5, s)) == rc.RC_E_CAPACITY
+    assert status(lambda: rc.rc_sparse_attention(s, idx, 1, 3, lay, 0, s, None)) == rc.RC_E_INVALID_ARG   # 3 % 2 heads
+    assert status(lambda: rc.rc_sparse_attention(s, idx, 1, 2, lay, 5, s, None)) == rc.RC_E_CAPACITY
     assert status(lambda: rc.rc_gemm_rows(rc.RC_F32, s, s, s, 1, 1, 4)) == rc.RC_E_UNSUPPORTED      # k % 8
     assert rc.rc_stage_workspace_bytes(10, 64) > 0

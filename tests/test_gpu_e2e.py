@@ -134,6 +134,21 @@ def test_bf16_ragged_batch_equals_single_requests():
         assert np.array_equal(one.scores[0], batch.scores[b])
 
 
+@pytest.mark.parametrize("chunk_tiles", [1, 3])
+def test_bf16_forced_kv_split_matches_oracle(chunk_tiles):
+    """Attention with every query tile's KV range cut into chunks (as chosen automatically for long
+    contexts with few active rows) gives the same result within tolerance, batched and paged."""
+    from paper_2603_13289_amd import binding as rc
+    case = build_case("small_bf16_ragged")
+    wants = [oracle_relay(case, b) for b in range(len(case.reqs))]
+    rc.rc_tune_set(rc.RC_TUNE_ATTN_CHUNK_TILES, chunk_tiles)
+    try:
+        run = hip_relay(case, forced=[w.sel_idx for w in wants])
+    finally:
+        rc.rc_tune_set(rc.RC_TUNE_ATTN_CHUNK_TILES, 0)
+    _check_against_oracle(case, run, wants, TOL["bf16"])
+
+
 def test_determinism_same_inputs_twice():
     case = build_case("small_bf16")
     a = hip_relay(case)

@@ -161,7 +161,8 @@ def test_threshold_select(n):
 @pytest.mark.parametrize("dtype,hq,hkv,dh", [("f32", 4, 2, 64), ("bf16", 8, 2, 128), ("bf16", 10, 2, 128),
                                               ("bf16", 4, 4, 128), ("f32", 2, 1, 128)])
 @pytest.mark.parametrize("block_size", [0, 16])
-def test_sparse_attention(dtype, hq, hkv, dh, block_size):
+@pytest.mark.parametrize("split", [False, True])
+def test_sparse_attention(dtype, hq, hkv, dh, block_size, split):
     rc = _rc()
     T = 333
     cache, ks, vs = _cache(dtype, hkv, dh, [20, T], block_size, "att")
@@ -170,8 +171,19 @@ def test_sparse_attention(dtype, hq, hkv, dh, block_size):
     n = len(pos)
     q = _rand((n, hq, dh), dtype, "att_q", 0.5)
     out = torch.zeros((n, hq, dh), dtype=_td(dtype), device="cuda")
-    rc.rc_sparse_attention(_up(q, dtype), torch.from_numpy(pos.astype(np.int32)).cuda(), n, hq, cache.layer(0), 1, out)
-    torch.cuda.synchronize()
+    ws = None
+    if split:      # the bf16 kernel cuts long KV ranges into chunks and merges partial results
+        if dtype != "bf16":
+            pytest.skip("the float path has no KV split")
+        rc.rc_tune_set(rc.RC_TUNE_ATTN_CHUNK_TILES, 2)     # chunks of 128 keys, so that T = 333 is "long"
+        assert rc.rc_sparse_attention_workspace_bytes(n, hq, cache.layer(0)) > 0
+        ws = rc.alloc_workspace(rc.rc_sparse_attention_workspace_bytes(n, hq, cache.layer(0)))
+    try:
+        rc.rc_sparse_attention(_up(q, dtype), torch.from_numpy(pos.astype(np.int32)).cuda(), n, hq, cache.layer(0), 1,
+                               out, ws)
+        torch.cuda.synchronize()
+    finally:
+        rc.rc_tune_set(rc.RC_TUNE_ATTN_CHUNK_TILES, 0)
     want = R.causal_gqa_attention(q.astype(np.float64), pos, ks[1].astype(np.float64), vs[1].astype(np.float64))
     assert rel_err(to_np(out), want) <= (2e-5 if dtype == "f32" else 1e-2)
     # the first query sees a single key: its output is that value row
