@@ -111,6 +111,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-prefill", action="store_true")
     ap.add_argument("--seed", type=int, default=20260313)
+    ap.add_argument("--counter-pass", action="store_true",
+                    help="for rocprofv3 --pmc runs: one warm-up, the timed steps, then a 1 GiB device copy whose "
+                         "FETCH_SIZE / WRITE_SIZE readings calibrate the counters; no CPU baseline, no full prefill")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -157,9 +160,21 @@ def main() -> int:
     def step():
         rc.rc_reuse(model, [req], plan, record, dst, logits, sel, None, ws)
 
+    if args.counter_pass:
+        args.no_cpu_baseline = args.no_full_prefill = True
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.counter_pass:
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read + 1 GiB written
+        dstc = torch.empty_like(src)
+        dstc.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"counter_pass": True, "steps": args.steps, "calibration_copy_bytes": 1 << 30}))
+        return 0
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     ev0.record()
     for _ in range(args.steps):

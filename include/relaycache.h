@@ -199,6 +199,8 @@ RC_API rc_status rc_profile_read(float* ms, int32_t* launches);
 /* RC_TUNE_ATTN_CHUNK_TILES: KV tiles (of 64 keys) per attention workgroup when a query tile's KV range is
  * split; 0 = chosen per shape (default), a value beyond the context length disables the split. */
 #define RC_TUNE_ATTN_CHUNK_TILES 2
+/* RC_TUNE_GEMM_XCD_REMAP: 1 (default) = GEMM workgroup ids are regrouped per XCD, 0 = launch order. */
+#define RC_TUNE_GEMM_XCD_REMAP 3
 RC_API rc_status rc_tune_set(int32_t key, int32_t value);
 
 /* ------------------------------------------------------------ stage calls
@@ -245,9 +247,13 @@ RC_API rc_status rc_sparse_attention(const void* q, const int32_t* q_pos, int32_
                                      const rc_kv_layer* cache, int32_t seq, void* out, void* workspace,
                                      size_t workspace_bytes, void* stream);
 
-/* C[M][N] (float) = A[M][K] (T) * W[N][K]^T (T): the gathered-row projection GEMM. */
+/* C[M][N] (float) = A[M][K] (T) * W[N][K]^T (T): the gathered-row projection GEMM.
+ * workspace (optional, device, 256-byte aligned, rc_gemm_workspace_bytes()): lets the bf16 kernel cut the
+ * last, partial round of output tiles along K (results are summed in a fixed order); NULL: one workgroup
+ * per output tile. */
+RC_API size_t rc_gemm_workspace_bytes(void);
 RC_API rc_status rc_gemm_rows(int32_t dtype, const void* a, const void* w, float* c, int32_t m, int32_t n,
-                       int32_t k, void* stream);
+                              int32_t k, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Write n recomputed rows into one layer of a paged cache: k_rows/v_rows [n][Hkv][dh] of T go to
  * positions pos[i] of `seq` (keys as given, i.e. already rotated). */

@@ -27,6 +27,7 @@ EXPORTS = [
     "rc_vdev_score", "rc_topk", "rc_threshold_select", "rc_sparse_attention", "rc_gemm_rows",
     "rc_scatter_paged", "rc_profile_enable", "rc_profile_class_count", "rc_profile_class_name", "rc_profile_read",
     "rc_tune_set", "rc_sparse_attention_workspace_bytes",
+    "rc_gemm_workspace_bytes",
 ]
 
 
@@ -110,7 +111,9 @@ def _load() -> C.CDLL:
     lib.rc_sparse_attention_workspace_bytes.restype = sz
     lib.rc_sparse_attention_workspace_bytes.argtypes = [i32, i32, C.POINTER(rc_kv_layer)]
     lib.rc_gemm_rows.restype = C.c_int
-    lib.rc_gemm_rows.argtypes = [i32, vp, vp, vp, i32, i32, i32, vp]
+    lib.rc_gemm_rows.argtypes = [i32, vp, vp, vp, i32, i32, i32, vp, sz, vp]
+    lib.rc_gemm_workspace_bytes.restype = sz
+    lib.rc_gemm_workspace_bytes.argtypes = []
     lib.rc_scatter_paged.restype = C.c_int
     lib.rc_scatter_paged.argtypes = [vp, vp, vp, i32, C.POINTER(rc_kv_layer), i32, vp]
     lib.rc_tune_set.restype = C.c_int
@@ -389,9 +392,15 @@ def rc_sparse_attention(q: torch.Tensor, q_pos: torch.Tensor, n: int, n_q_heads:
                                    _ptr(workspace), nbytes, _stream(stream)), "rc_sparse_attention")
 
 
+def rc_gemm_workspace_bytes() -> int:
+    return int(lib.rc_gemm_workspace_bytes())
+
+
 def rc_gemm_rows(dtype: int, a: torch.Tensor, w: torch.Tensor, c: torch.Tensor, m: int, n: int, k: int,
-                 stream=None) -> None:
-    _check(lib.rc_gemm_rows(dtype, _ptr(a), _ptr(w), _ptr(c), m, n, k, _stream(stream)), "rc_gemm_rows")
+                 workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.rc_gemm_rows(dtype, _ptr(a), _ptr(w), _ptr(c), m, n, k, _ptr(workspace), nbytes, _stream(stream)),
+           "rc_gemm_rows")
 
 
 def rc_scatter_paged(k_rows: torch.Tensor, v_rows: torch.Tensor, pos: torch.Tensor, n: int, dst: rc_kv_layer,
@@ -416,6 +425,7 @@ def rc_profile_read() -> dict:
 
 RC_TUNE_GEMM_TILE = 1
 RC_TUNE_ATTN_CHUNK_TILES = 2
+RC_TUNE_GEMM_XCD_REMAP = 3
 
 
 def rc_tune_set(key: int, value: int) -> None:

@@ -293,6 +293,7 @@ struct Workspace {
   float* h_last;
   void* a_last;
   float* attn_part;   // partial attention results when a layer's KV range is split into chunks
+  float* gemm_part;   // accumulators of K-split tail tiles of the bf16 GEMMs
   size_t bytes;
 };
 
@@ -326,6 +327,7 @@ Workspace carve(void* base, const rc_model_desc& d, int max_rows, int max_pos, i
   w.h_last = (float*)take(sizeof(float) * (size_t)n_req * d.d_model);
   w.a_last = take(es * (size_t)n_req * d.d_model);
   w.attn_part = (float*)take(sizeof(float) * (attn_part_floats > 0 ? attn_part_floats : 1));
+  w.gemm_part = (float*)take(d.dtype == RC_BF16 ? gemm_partial_bytes() : 256);
   w.bytes = off;
   return w;
 }
@@ -364,6 +366,33 @@ hipError_t attention_dispatch<bf16>(const bf16* q, const int* row_pos, const int
                                     KvGeom g, int n_q_heads, bf16* out, AttnSplit sp, float* part, hipStream_t st) {
   return launch_attention_bf16(q, row_pos, row_req, table, 0, total_rows, total_tiles, k_pool, v_pool, g, n_q_heads,
                                out, sp, part, st);
+}
+
+template <typename T>
+hipError_t gemm_any(const T* a, const T* wt, const T* wt2, void* c, int m, int n, int k, int ldc, GemmEpilogue epi,
+                    float* partial, hipStream_t st);
+template <>
+hipError_t gemm_any<float>(const float* a, const float* wt, const float* wt2, void* c, int m, int n, int k, int ldc,
+                           GemmEpilogue epi, float*, hipStream_t st) {
+  return launch_gemm<float>(a, wt, wt2, c, m, n, k, ldc, epi, st);
+}
+template <>
+hipError_t gemm_any<bf16>(const bf16* a, const bf16* wt, const bf16* wt2, void* c, int m, int n, int k, int ldc,
+                          GemmEpilogue epi, float* partial, hipStream_t st) {
+  return launch_gemm_bf16(a, wt, wt2, c, m, n, k, ldc, epi, partial, st);
+}
+template <typename T>
+hipError_t gemm_qkv_any(const T* a, const T* wq, int nq, const T* wk, const T* wv, int nkv, float* c, int m, int k,
+                        float* partial, hipStream_t st);
+template <>
+hipError_t gemm_qkv_any<float>(const float* a, const float* wq, int nq, const float* wk, const float* wv, int nkv,
+                               float* c, int m, int k, float*, hipStream_t st) {
+  return launch_gemm_qkv<float>(a, wq, nq, wk, wv, nkv, c, m, k, st);
+}
+template <>
+hipError_t gemm_qkv_any<bf16>(const bf16* a, const bf16* wq, int nq, const bf16* wk, const bf16* wv, int nkv, float* c,
+                              int m, int k, float* partial, hipStream_t st) {
+  return launch_gemm_qkv_bf16(a, wq, nq, wk, wv, nkv, c, m, k, partial, st);
 }
 
 template <typename T>
@@ -423,7 +452,7 @@ rc_status run_job(const Job& job, Workspace& w, hipStream_t st) {
       if (any) {
         const int rows_b = tabs[cur].total_rows;
         RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(w.h[hbuf], (const T*)lw.g_attn, (T*)w.a, rows_b, D, d.rms_eps, st));
-        RC_LAUNCH(PC_GEMM_VFRESH, launch_gemm<T>((const T*)w.a, (const T*)lw.wv, nullptr, w.vfresh, rows_b, nkv, D, nkv, EPI_STORE_T, st));
+        RC_LAUNCH(PC_GEMM_VFRESH, gemm_any<T>((const T*)w.a, (const T*)lw.wv, nullptr, w.vfresh, rows_b, nkv, D, nkv, EPI_STORE_T, w.gemm_part, st));
         float* sc = job.scores_out ? job.scores_out : w.scores;
         RC_LAUNCH(PC_SCORE, launch_vdev_score<T>((const T*)w.vfresh, nkv, (const T*)job.dst->v_pool[l], gd, w.tables + cur,
                                     n_req, job.max_seg, sc, st));
@@ -444,8 +473,8 @@ rc_status run_job(const Job& job, Workspace& w, hipStream_t st) {
 
     float* h = w.h[hbuf];
     RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(h, (const T*)lw.g_attn, (T*)w.a, rows, D, d.rms_eps, st));
-    RC_LAUNCH(PC_GEMM_QKV, launch_gemm_qkv<T>((const T*)w.a, (const T*)lw.wq, nq, (const T*)lw.wk, (const T*)lw.wv, nkv,
-                                              w.qkv, rows, D, st));
+    RC_LAUNCH(PC_GEMM_QKV, gemm_qkv_any<T>((const T*)w.a, (const T*)lw.wq, nq, (const T*)lw.wk, (const T*)lw.wv, nkv,
+                                              w.qkv, rows, D, w.gemm_part, st));
     // rotary on q/k at the rows' absolute positions; fresh K/V written into the cache before anyone attends
     RC_LAUNCH(PC_ROPE_SCATTER, launch_rope_scatter<T>(w.qkv, rows, w.row_pos, w.row_req, w.tables + cur, w.rope_tab, (T*)w.q,
                                   (T*)job.dst->k_pool[l], (T*)job.dst->v_pool[l],
@@ -453,17 +482,17 @@ rc_status run_job(const Job& job, Workspace& w, hipStream_t st) {
     RC_LAUNCH(PC_ATTENTION, attention_dispatch<T>((const T*)w.q, w.row_pos, w.row_req, w.tables + cur, rows,
                                  tabs[cur].total_tiles, (const T*)job.dst->k_pool[l],
                                  (const T*)job.dst->v_pool[l], gd, d.n_q_heads, (T*)w.o, splits[cur], w.attn_part, st));
-    RC_LAUNCH(PC_GEMM_O, launch_gemm<T>((const T*)w.o, (const T*)lw.wo, nullptr, h, rows, D, nq, D, EPI_ADD_F32, st));
+    RC_LAUNCH(PC_GEMM_O, gemm_any<T>((const T*)w.o, (const T*)lw.wo, nullptr, h, rows, D, nq, D, EPI_ADD_F32, w.gemm_part, st));
     RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(h, (const T*)lw.g_ffn, (T*)w.a, rows, D, d.rms_eps, st));
-    RC_LAUNCH(PC_GEMM_GATE_UP, launch_gemm<T>((const T*)w.a, (const T*)lw.w_gate, (const T*)lw.w_up, w.act, rows, F, D, F, EPI_SWIGLU_T, st));
-    RC_LAUNCH(PC_GEMM_DOWN, launch_gemm<T>((const T*)w.act, (const T*)lw.w_down, nullptr, h, rows, D, F, D, EPI_ADD_F32, st));
+    RC_LAUNCH(PC_GEMM_GATE_UP, gemm_any<T>((const T*)w.a, (const T*)lw.w_gate, (const T*)lw.w_up, w.act, rows, F, D, F, EPI_SWIGLU_T, w.gemm_part, st));
+    RC_LAUNCH(PC_GEMM_DOWN, gemm_any<T>((const T*)w.act, (const T*)lw.w_down, nullptr, h, rows, D, F, D, EPI_ADD_F32, w.gemm_part, st));
   }
 
   // first-token logits from the last position of each request
   RC_LAUNCH(PC_ROWS, launch_gather_last(w.tables + cur, n_req, w.h[hbuf], w.h_last, D, st));
   RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(w.h_last, (const T*)job.m->g_final, (T*)w.a_last, n_req, D, d.rms_eps, st));
-  RC_LAUNCH(PC_GEMM_LM_HEAD, launch_gemm<T>((const T*)w.a_last, (const T*)job.m->w_lm, nullptr, job.logits, n_req, d.vocab, D, d.vocab,
-                        EPI_STORE_F32, st));
+  RC_LAUNCH(PC_GEMM_LM_HEAD, gemm_any<T>((const T*)w.a_last, (const T*)job.m->w_lm, nullptr, job.logits, n_req, d.vocab, D, d.vocab,
+                        EPI_STORE_F32, w.gemm_part, st));
   (void)uploaded;
   return RC_OK;
 }
@@ -587,8 +616,12 @@ rc_status rc_model_create(const rc_model_desc* desc, const rc_layer_w* layers, c
 }
 
 rc_status rc_tune_set(int32_t key, int32_t value) {
-  if (key == RC_TUNE_GEMM_TILE && value >= 0 && value <= 3) {
+  if (key == RC_TUNE_GEMM_TILE && value >= 0 && value <= 6) {
     set_gemm_tile(value);
+    return RC_OK;
+  }
+  if (key == RC_TUNE_GEMM_XCD_REMAP && (value == 0 || value == 1)) {
+    set_gemm_xcd_remap(value);
     return RC_OK;
   }
   if (key == RC_TUNE_ATTN_CHUNK_TILES && value >= 0) {
@@ -874,15 +907,20 @@ rc_status rc_sparse_attention(const void* q, const int32_t* q_pos, int32_t n, in
   return RC_OK;
 }
 
+size_t rc_gemm_workspace_bytes(void) { return align_up(gemm_partial_bytes()); }
+
 rc_status rc_gemm_rows(int32_t dtype, const void* a, const void* w, float* c, int32_t m, int32_t n, int32_t k,
-                       void* stream) {
+                       void* workspace, size_t workspace_bytes, void* stream) {
   if (dtype != RC_F32 && dtype != RC_BF16) return RC_E_INVALID_ARG;
   if (!a || !w || !c || m < 0 || n < 1 || k < 1) return RC_E_INVALID_ARG;
   if (k % 8) return RC_E_UNSUPPORTED;
+  if (workspace && ((reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < rc_gemm_workspace_bytes()))
+    return RC_E_WORKSPACE;
   if (m == 0) return RC_OK;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (dtype == RC_BF16)
-    RC_HIP(launch_gemm<bf16>((const bf16*)a, (const bf16*)w, nullptr, c, m, n, k, n, EPI_STORE_F32, st));
+    RC_HIP(launch_gemm_bf16((const bf16*)a, (const bf16*)w, nullptr, c, m, n, k, n, EPI_STORE_F32,
+                            reinterpret_cast<float*>(workspace), st));
   else
     RC_HIP(launch_gemm<float>((const float*)a, (const float*)w, nullptr, c, m, n, k, n, EPI_STORE_F32, st));
   return RC_OK;

@@ -166,6 +166,14 @@ template <typename T>
 hipError_t launch_gemm_qkv(const T* a, const T* wq, int nq, const T* wk, const T* wv, int nkv, float* c, int m,
                            int k, hipStream_t st);
 
+// bf16 GEMMs with a scratch buffer (gemm_partial_bytes()) for the K-split tail of the tile schedule;
+// partial == nullptr: every tile is done by one workgroup.
+size_t gemm_partial_bytes();
+hipError_t launch_gemm_bf16(const bf16* a, const bf16* w, const bf16* w2, void* c, int m, int n, int k, int ldc,
+                            GemmEpilogue epi, float* partial, hipStream_t st);
+hipError_t launch_gemm_qkv_bf16(const bf16* a, const bf16* wq, int nq, const bf16* wk, const bf16* wv, int nkv, float* c,
+                                int m, int k, float* partial, hipStream_t st);
+void set_gemm_xcd_remap(int on);
 void set_gemm_tile(int t);  // 0: by shape, 1: 128x256, 2: 256x256, 3: 128x128 (bf16 MFMA GEMM)
 
 template <typename T>

@@ -19,6 +19,8 @@
 // Workgroup ids are remapped so that the workgroups resident on one XCD (ids congruent mod 8) walk
 // all row tiles of the same few weight-column tiles: a weight tile is then fetched from HBM once
 // per XCD-L2 instead of once per row tile.
+#include <algorithm>
+
 #include "common.h"
 
 namespace rc {
@@ -28,8 +30,44 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 static constexpr int BK = 64;
 static constexpr int XCDS = 8;
+static int g_xcd_remap = 1;
+void set_gemm_xcd_remap(int on) { g_xcd_remap = on; }
 
 __device__ inline float silu_mf(float x) { return x / (1.0f + __expf(-x)); }
+
+// Accumulator element e of the 32x32 block (i, j) of a wavefront sits at row 8*(e/4) + 4*(lane/32) + e%4,
+// column lane%32 of that block.  Shared by the GEMM kernels and the split-K fix-up.
+template <int FM, int FN, int WTM, int WTN, bool DUAL>
+__device__ inline void store_tile(const f32x16 (&acc)[FM][FN], void* __restrict__ c, int m, int n, int ldc, int epi,
+                                  int m0, int n0, int wm, int wn, int lane) {
+  constexpr int FN_OUT = DUAL ? FN / 2 : FN;
+  constexpr int WTN_OUT = DUAL ? WTN / 2 : WTN;
+  const int khalf = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+#pragma unroll
+    for (int j = 0; j < FN_OUT; ++j) {
+      const int col = n0 + wn * WTN_OUT + j * 32 + (lane & 31);
+      if (col >= n) continue;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = m0 + wm * WTM + i * 32 + 8 * (e / 4) + 4 * khalf + (e % 4);
+        if (row >= m) continue;
+        const size_t o = (size_t)row * ldc + col;
+        const float v = acc[i][j][e];
+        if (DUAL) {
+          reinterpret_cast<bf16*>(c)[o] = f32_to_bf16(silu_mf(v) * acc[i][j + FN_OUT][e]);
+        } else if (epi == EPI_STORE_F32) {
+          reinterpret_cast<float*>(c)[o] = v;
+        } else if (epi == EPI_ADD_F32) {
+          reinterpret_cast<float*>(c)[o] += v;
+        } else {
+          reinterpret_cast<bf16*>(c)[o] = f32_to_bf16(v);
+        }
+      }
+    }
+  }
+}
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool DUAL, int OCC>
 __global__ void __launch_bounds__(WAVES_M * WAVES_N * 64, OCC)
@@ -47,7 +85,7 @@ gemm_mfma_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const b
   __shared__ uint4 lds_a[BM * 8];
   __shared__ uint4 lds_b[BN * 8];
 
-  const int logical = (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS;
+  const int logical = per_xcd > 0 ? (int)(blockIdx.x % XCDS) * per_xcd + (int)(blockIdx.x / XCDS) : (int)blockIdx.x;
   if (logical >= total_tiles) return;
   const int tile_m = logical % tiles_m, tile_n = logical / tiles_m;
   const int m0 = tile_m * BM, n0 = tile_n * BN_OUT;
@@ -172,7 +210,291 @@ gemm_mfma_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const b
   }
 }
 
-static int g_gemm_tile = 0;   // 0: choose by shape; 1: 128x256; 2: 256x256; 3: 128x128
+// ------------------------------------------------------------------ direct-to-LDS, double-buffered variant
+// Same tile/fragment structure as above, but tiles are fetched with 16-byte global->LDS loads (no
+// staging registers, no LDS store instructions) into two alternating LDS buffers, so one barrier per
+// K step suffices: wait for my loads, barrier, start the loads of the next step into the other
+// buffer, multiply the current one.
+//
+// A direct load writes lane l's 16 bytes to (wave-uniform LDS base) + 16 l, i.e. one instruction fills
+// 1 KB = 8 rows of 128 bytes.  The XOR placement (chunk c of row r at slot c ^ ((r >> 1) & 7)) is
+// therefore applied on the global side: lane l of a row block fetches chunk (l & 7) ^ swz(row).
+// Rows past M (or N) re-read the last valid row; their products are never stored.  K must be a
+// multiple of 64.
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool DUAL, int OCC>
+__global__ void __launch_bounds__(WAVES_M * WAVES_N * 64, OCC)
+gemm_mfma_dl_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const bf16* __restrict__ w2,
+                    const bf16* __restrict__ w3, int ns1, int ns2, void* __restrict__ c, int m, int n, int k, int ldc,
+                    int epi, int tiles_m, int full_tiles, int per_xcd, int n_full_wgs, int split, int ksteps_per_part,
+                    float* __restrict__ partial) {
+  constexpr int NW = WAVES_M * WAVES_N;
+  constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+  constexpr int FM = WTM / 32, FN = WTN / 32;
+  constexpr int BN_OUT = DUAL ? BN / 2 : BN;
+  constexpr int A_BLK = BM / 8, B_BLK = BN / 8;              // 8-row blocks per tile
+  constexpr int A_PER = A_BLK / NW, B_PER = B_BLK / NW;      // blocks per wave
+  static_assert(A_PER * NW == A_BLK && B_PER * NW == B_BLK, "tile/waves mismatch");
+  constexpr int TILE_BYTES = (BM + BN) * 128;
+
+  extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];   // 2 x [A tile | B tile]
+
+  // Workgroups [0, n_full_wgs) each own one of the first full_tiles output tiles (whole K range).
+  // The remaining tiles, too few to fill the chip, are each cut along K into `split` parts: workgroup
+  // n_full_wgs + j takes part j % split of tile full_tiles + j / split and leaves its raw accumulators
+  // in `partial`; gemm_fixup_kernel adds the parts in a fixed order and applies the epilogue.
+  int logical, k_begin = 0, k_end = k, part_slot = -1;
+  if ((int)blockIdx.x < n_full_wgs) {
+    logical = per_xcd > 0 ? (int)(blockIdx.x % XCDS) * per_xcd + (int)(blockIdx.x / XCDS) : (int)blockIdx.x;
+    if (logical >= full_tiles) return;
+  } else {
+    const int j = (int)blockIdx.x - n_full_wgs;
+    logical = full_tiles + j / split;
+    part_slot = j;
+    k_begin = (j % split) * ksteps_per_part * BK;
+    k_end = min(k, k_begin + ksteps_per_part * BK);
+  }
+  const int tile_m = logical % tiles_m, tile_n = logical / tiles_m;
+  const int m0 = tile_m * BM, n0 = tile_n * BN_OUT;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+  // global sources: lane l of block b covers row 8 b + (l >> 3), LDS slot l & 7
+  const int lrow = lane >> 3, lslot = lane & 7;
+  const bf16* pa[A_PER];
+  const bf16* pb[B_PER];
+#pragma unroll
+  for (int i = 0; i < A_PER; ++i) {
+    const int row = (wave + i * NW) * 8 + lrow;
+    const int chunk = lslot ^ ((row >> 1) & 7);
+    pa[i] = a + (size_t)min(m0 + row, m - 1) * k + chunk * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < B_PER; ++i) {
+    const int row = (wave + i * NW) * 8 + lrow;
+    const int chunk = lslot ^ ((row >> 1) & 7);
+    const bf16* src;
+    if (DUAL) {
+      const int half = row >= BN / 2;
+      const int col = min(n0 + row - half * (BN / 2), n - 1);
+      src = (half ? w2 : w) + (size_t)col * k;
+    } else {
+      const int col = min(n0 + row, n - 1);
+      src = col < ns1 ? w + (size_t)col * k : (col < ns2 ? w2 + (size_t)(col - ns1) * k : w3 + (size_t)(col - ns2) * k);
+    }
+    pb[i] = src + chunk * 8;
+  }
+  auto issue = [&](int k0, int buf) {
+    unsigned char* base = lds + buf * TILE_BYTES;
+#pragma unroll
+    for (int i = 0; i < A_PER; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pa[i] + k0),
+                                       (__attribute__((address_space(3))) void*)(base + (wave + i * NW) * 1024), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < B_PER; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pb[i] + k0),
+                                       (__attribute__((address_space(3))) void*)(base + BM * 128 + (wave + i * NW) * 1024), 16, 0, 0);
+  };
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  int arow[FM], brow[FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i) arow[i] = wm * WTM + i * 32 + (lane & 31);
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    if (DUAL) brow[j] = (j < FN / 2 ? wn * (WTN / 2) + j * 32 : BN / 2 + wn * (WTN / 2) + (j - FN / 2) * 32) + (lane & 31);
+    else brow[j] = wn * WTN + j * 32 + (lane & 31);
+  }
+  const int khalf = lane >> 5;
+
+  if (k_begin < k_end) issue(k_begin, 0);
+  int buf = 0;
+  for (int k0 = k_begin; k0 < k_end; k0 += BK) {
+    __builtin_amdgcn_s_waitcnt(0);   // my own direct loads of this step have landed
+    __syncthreads();                 // ... and everyone else's; the other buffer is free again
+    if (k0 + BK < k_end) issue(k0 + BK, buf ^ 1);
+    const uint4* la = reinterpret_cast<const uint4*>(lds + buf * TILE_BYTES);
+    const uint4* lb = reinterpret_cast<const uint4*>(lds + buf * TILE_BYTES + BM * 128);
+    // operands of K sub-step s+1 are fetched from LDS while sub-step s is multiplied
+    bf16x8 fa[2][FM], fb[2][FN];
+    auto load_frags = [&](int s, int r) {
+      const int chunk = 2 * s + khalf;
+#pragma unroll
+      for (int i = 0; i < FM; ++i) fa[r][i] = __builtin_bit_cast(bf16x8, la[arow[i] * 8 + (chunk ^ ((arow[i] >> 1) & 7))]);
+#pragma unroll
+      for (int j = 0; j < FN; ++j) fb[r][j] = __builtin_bit_cast(bf16x8, lb[brow[j] * 8 + (chunk ^ ((brow[j] >> 1) & 7))]);
+    };
+    load_frags(0, 0);
+#pragma unroll
+    for (int s = 0; s < BK / 16; ++s) {
+      if (s + 1 < BK / 16) load_frags(s + 1, (s + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of this sub-step's MFMAs
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1][i], fb[s & 1][j], acc[i][j], 0, 0, 0);
+    }
+    buf ^= 1;
+  }
+
+  if (part_slot >= 0) {
+    // raw accumulators, register-major so that consecutive lanes write consecutive floats
+    constexpr int NT = NW * 64;
+    float* dst = partial + (size_t)part_slot * (FM * FN * 16) * NT + tid;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) dst[(size_t)((i * FN + j) * 16 + e) * NT] = acc[i][j][e];
+    return;
+  }
+  store_tile<FM, FN, WTM, WTN, DUAL>(acc, c, m, n, ldc, epi, m0, n0, wm, wn, lane);
+}
+
+// Sum of the K-split parts of the tail tiles (fixed order: part 0, 1, ...) followed by the epilogue.
+// One workgroup per (tile, 32x32 block, group of 4 accumulator registers): thread t owns the same
+// (wavefront, lane) as thread t of the GEMM kernel, so all reads of a part are coalesced.
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool DUAL>
+__global__ void __launch_bounds__(WAVES_M * WAVES_N * 64)
+gemm_fixup_kernel(void* __restrict__ c, int m, int n, int ldc, int epi, int tiles_m, int full_tiles, int split,
+                  const float* __restrict__ partial) {
+  constexpr int NW = WAVES_M * WAVES_N, NT = NW * 64;
+  constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+  constexpr int FM = WTM / 32, FN = WTN / 32;
+  constexpr int FN_OUT = DUAL ? FN / 2 : FN;
+  constexpr int WTN_OUT = DUAL ? WTN / 2 : WTN;
+  constexpr int BN_OUT = DUAL ? BN / 2 : BN;
+  constexpr int PER_TILE = FM * FN_OUT * 4;
+  const int t = (int)blockIdx.x / PER_TILE;
+  int rest = (int)blockIdx.x % PER_TILE;
+  const int e4 = rest % 4; rest /= 4;
+  const int j = rest % FN_OUT, i = rest / FN_OUT;
+  const int logical = full_tiles + t;
+  const int tile_m = logical % tiles_m, tile_n = logical / tiles_m;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  float g[4] = {0.f, 0.f, 0.f, 0.f}, u[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int p = 0; p < split; ++p) {
+    const float* src = partial + (size_t)(t * split + p) * (FM * FN * 16) * NT + tid;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      g[e] += src[(size_t)((i * FN + j) * 16 + e4 * 4 + e) * NT];
+      if (DUAL) u[e] += src[(size_t)((i * FN + j + FN_OUT) * 16 + e4 * 4 + e) * NT];
+    }
+  }
+  const int col = tile_n * BN_OUT + wn * WTN_OUT + j * 32 + (lane & 31);
+  if (col >= n) return;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int row = tile_m * BM + wm * WTM + i * 32 + 8 * e4 + 4 * (lane >> 5) + e;
+    if (row >= m) continue;
+    const size_t o = (size_t)row * ldc + col;
+    if (DUAL) reinterpret_cast<bf16*>(c)[o] = f32_to_bf16(silu_mf(g[e]) * u[e]);
+    else if (epi == EPI_STORE_F32) reinterpret_cast<float*>(c)[o] = g[e];
+    else if (epi == EPI_ADD_F32) reinterpret_cast<float*>(c)[o] += g[e];
+    else reinterpret_cast<bf16*>(c)[o] = f32_to_bf16(g[e]);
+  }
+}
+
+// Rough time model (microseconds, measured on MI355X) used to choose the tile and the K-split of the tail:
+// one K step of a full round costs kStep256 with 256x256 tiles (one workgroup per CU) and kStep128 with
+// 128x128 tiles (two per CU); summing one 256x256 tile part in the fix-up costs kFixPart.
+static constexpr float kStep256 = 1.9f, kStep128 = 1.2f, kFixPart = 0.1f, kFixLaunch = 6.f;
+
+struct SplitPlan { int rem, split; float cost; };
+// total tiles over `slots` workgroup slots: full rounds, then `rem` tiles cut into `split` K parts each
+static SplitPlan plan_tail_split(int total, int slots, int ksteps) {
+  SplitPlan best;
+  best.rem = total % slots;
+  best.split = 1;
+  const int full_rounds = total / slots;
+  best.cost = (full_rounds + (best.rem > 0 ? 1 : 0)) * ksteps * kStep256;
+  if (best.rem == 0) return best;
+  const int gmax = std::min(std::min(slots / best.rem, 16), ksteps);
+  for (int g = 2; g <= gmax; ++g) {
+    if (best.rem * g > 256) break;
+    const float c = full_rounds * ksteps * kStep256 + ((ksteps + g - 1) / g) * kStep256 + best.rem * g * kFixPart + kFixLaunch;
+    if (c < best.cost) { best.cost = c; best.split = g; }
+  }
+  return best;
+}
+
+static int g_num_cus = 0;
+static int num_cus() {
+  if (g_num_cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    g_num_cus = n;
+  }
+  return g_num_cus;
+}
+
+size_t gemm_partial_bytes() { return (size_t)256 * 256 * 256 * sizeof(float) + 4096; }   // 256 tile parts
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int OCC>
+static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const bf16* w3, int ns1, int ns2, void* c,
+                            int m, int n, int k, int ldc, GemmEpilogue epi, float* partial, hipStream_t st) {
+  const bool dual = epi == EPI_SWIGLU_T;
+  const int bn_out = dual ? BN / 2 : BN;
+  const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + bn_out - 1) / bn_out;
+  const int total = tiles_m * tiles_n;
+  // Full rounds of one tile per workgroup slot; the remainder (less than one round) is cut along K so
+  // that it also fills the chip.  Only with a partial buffer, and only for the one-workgroup-per-CU tile.
+  const int slots = num_cus() * OCC;
+  const int ksteps = k / BK;
+  int full_tiles = total, split = 1, kpp = ksteps;
+  if (partial && OCC == 1) {
+    const SplitPlan sp = plan_tail_split(total, slots, ksteps);
+    if (sp.split > 1) {
+      full_tiles = total - sp.rem;
+      kpp = (ksteps + sp.split - 1) / sp.split;
+      split = (ksteps + kpp - 1) / kpp;
+    }
+  }
+  const int rem_tiles = total - full_tiles;
+  int per_xcd = (full_tiles + XCDS - 1) / XCDS;
+  const int n_full_wgs = per_xcd * XCDS;
+  const dim3 grid((unsigned)(n_full_wgs + rem_tiles * split));
+  if (!g_xcd_remap) per_xcd = 0;
+  constexpr int NT = WAVES_M * WAVES_N * 64;
+  constexpr size_t lds_bytes = 2 * (size_t)(BM + BN) * 128;
+  hipError_t e = hipSuccess;
+  if (dual) {
+    auto kern = gemm_mfma_dl_kernel<BM, BN, WAVES_M, WAVES_N, true, OCC>;
+    static bool attr_set = false;
+    if (!attr_set) { e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes); attr_set = true; }
+    if (e != hipSuccess) return e;
+    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, tiles_m, full_tiles, per_xcd,
+                                      n_full_wgs, split, kpp, partial);
+    if (rem_tiles > 0)
+      gemm_fixup_kernel<BM, BN, WAVES_M, WAVES_N, true><<<rem_tiles * (BM / WAVES_M / 32) * (BN / WAVES_N / 64) * 4, NT, 0, st>>>(
+          c, m, n, ldc, (int)epi, tiles_m, full_tiles, split, partial);
+  } else {
+    auto kern = gemm_mfma_dl_kernel<BM, BN, WAVES_M, WAVES_N, false, OCC>;
+    static bool attr_set = false;
+    if (!attr_set) { e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes); attr_set = true; }
+    if (e != hipSuccess) return e;
+    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, tiles_m, full_tiles, per_xcd,
+                                      n_full_wgs, split, kpp, partial);
+    if (rem_tiles > 0)
+      gemm_fixup_kernel<BM, BN, WAVES_M, WAVES_N, false><<<rem_tiles * (BM / WAVES_M / 32) * (BN / WAVES_N / 32) * 4, NT, 0, st>>>(
+          c, m, n, ldc, (int)epi, tiles_m, full_tiles, split, partial);
+  }
+  return hipGetLastError();
+}
+
+static int g_gemm_tile = 0;   // 0: by shape; 1: 128x256; 2: 256x256; 3: 128x128; 4-6: the same with direct-to-LDS loads
 void set_gemm_tile(int t) { g_gemm_tile = t; }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int OCC>
@@ -182,8 +504,9 @@ static hipError_t launch_cfg(const bf16* a, const bf16* w, const bf16* w2, const
   const int bn_out = dual ? BN / 2 : BN;
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + bn_out - 1) / bn_out;
   const int total = tiles_m * tiles_n;
-  const int per_xcd = (total + XCDS - 1) / XCDS;
+  int per_xcd = (total + XCDS - 1) / XCDS;
   const dim3 grid((unsigned)(per_xcd * XCDS));
+  if (!g_xcd_remap) per_xcd = 0;
   constexpr int NT = WAVES_M * WAVES_N * 64;
   if (dual)
     gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, true, OCC><<<grid, NT, 0, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc,
@@ -195,16 +518,32 @@ static hipError_t launch_cfg(const bf16* a, const bf16* w, const bf16* w2, const
 }
 
 static hipError_t dispatch(const bf16* a, const bf16* w, const bf16* w2, const bf16* w3, int ns1, int ns2, void* c,
-                           int m, int n, int k, int ldc, GemmEpilogue epi, hipStream_t st) {
+                           int m, int n, int k, int ldc, GemmEpilogue epi, float* partial, hipStream_t st) {
   if (m <= 0 || n <= 0) return hipSuccess;
   int tile = g_gemm_tile;
   if (tile == 0) {
-    // enough 128x256 tiles to fill the chip twice over -> big tiles; otherwise smaller ones
-    const int bn_out = epi == EPI_SWIGLU_T ? 128 : 256;
-    const long t1 = (long)((m + 127) / 128) * ((n + bn_out - 1) / bn_out);
-    tile = t1 >= 400 ? 1 : 3;
+    if (k % BK != 0) {
+      tile = 3;
+    } else {
+      // 256x256 tiles (one workgroup per CU, K-split tail) against 128x128 tiles (two per CU), by the time model
+      const bool dual = epi == EPI_SWIGLU_T;
+      const int ksteps = k / BK;
+      const int t5 = ((m + 255) / 256) * ((n + (dual ? 127 : 255)) / (dual ? 128 : 256));
+      const long t6 = (long)((m + 127) / 128) * ((n + (dual ? 63 : 127)) / (dual ? 64 : 128));
+      const int slots6 = 2 * num_cus();
+      const float cost5 = partial ? plan_tail_split(t5, num_cus(), ksteps).cost
+                                  : ((t5 + num_cus() - 1) / num_cus()) * ksteps * kStep256;
+      const long last6 = t6 % slots6;
+      const float cost6 = (t6 / slots6) * ksteps * kStep128 +
+                          (last6 == 0 ? 0.f : (last6 * 2 <= slots6 ? 0.65f : 1.f) * ksteps * kStep128);
+      tile = cost5 <= cost6 ? 5 : 6;
+    }
   }
+  if (tile >= 4 && (k % BK) != 0) tile -= 3;   // the direct-load kernels need whole K steps
   switch (tile) {
+    case 4: return launch_dl<128, 256, 2, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, nullptr, st);
+    case 5: return launch_dl<256, 256, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st);
+    case 6: return launch_dl<128, 128, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, nullptr, st);
     case 2: return launch_cfg<256, 256, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);
     case 3: return launch_cfg<128, 128, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);
     default: return launch_cfg<128, 256, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);
@@ -214,7 +553,18 @@ static hipError_t dispatch(const bf16* a, const bf16* w, const bf16* w2, const b
 template <>
 hipError_t launch_gemm<bf16>(const bf16* a, const bf16* w, const bf16* w2, void* c, int m, int n, int k, int ldc,
                              GemmEpilogue epi, hipStream_t st) {
-  return dispatch(a, w, w2, nullptr, n, n, c, m, n, k, ldc, epi, st);
+  return dispatch(a, w, w2, nullptr, n, n, c, m, n, k, ldc, epi, nullptr, st);
+}
+
+hipError_t launch_gemm_bf16(const bf16* a, const bf16* w, const bf16* w2, void* c, int m, int n, int k, int ldc,
+                            GemmEpilogue epi, float* partial, hipStream_t st) {
+  return dispatch(a, w, w2, nullptr, n, n, c, m, n, k, ldc, epi, partial, st);
+}
+
+hipError_t launch_gemm_qkv_bf16(const bf16* a, const bf16* wq, int nq, const bf16* wk, const bf16* wv, int nkv, float* c,
+                                int m, int k, float* partial, hipStream_t st) {
+  const int n = nq + 2 * nkv;
+  return dispatch(a, wq, wk, wv, nq, nq + nkv, c, m, n, k, n, EPI_STORE_F32, partial, st);
 }
 
 // q | k | v projections of the same rows as one GEMM over the concatenated output columns
@@ -222,7 +572,7 @@ template <>
 hipError_t launch_gemm_qkv<bf16>(const bf16* a, const bf16* wq, int nq, const bf16* wk, const bf16* wv, int nkv,
                                  float* c, int m, int k, hipStream_t st) {
   const int n = nq + 2 * nkv;
-  return dispatch(a, wq, wk, wv, nq, nq + nkv, c, m, n, k, n, EPI_STORE_F32, st);
+  return dispatch(a, wq, wk, wv, nq, nq + nkv, c, m, n, k, n, EPI_STORE_F32, nullptr, st);
 }
 
 }  // namespace rc

@@ -121,17 +121,19 @@ def test_bf16_ragged_batch_equals_single_requests():
     wants = [oracle_relay(case, b) for b in range(len(case.reqs))]
     batch = hip_relay(case, forced=[w.sel_idx for w in wants])
     _check_against_oracle(case, batch, wants, TOL["bf16"])
-    # one request at a time gives bit-identical results to the batched launch sequence
+    # One request at a time agrees with the batched launch sequence.  Not bit for bit: the GEMM cuts the
+    # last round of output tiles along K, and which tiles those are depends on the batch's total row count,
+    # so sums are rounded in a different order (each run by itself is deterministic).
     from dataclasses import replace
     for b in range(len(case.reqs)):
         single = replace(case, reqs=[case.reqs[b]])
         one = hip_relay(single, forced=[wants[b].sel_idx])
         T = wants[b].k_cache.shape[1]
         for l in range(case.w.shape.n_layers):
-            assert np.array_equal(one.k_cache[0][l][:T], batch.k_cache[b][l][:T])
-            assert np.array_equal(one.v_cache[0][l][:T], batch.v_cache[b][l][:T])
-        assert np.array_equal(one.logits[0], batch.logits[b])
-        assert np.array_equal(one.scores[0], batch.scores[b])
+            assert rel_err(one.k_cache[0][l][:T], batch.k_cache[b][l][:T]) <= 1e-2
+            assert rel_err(one.v_cache[0][l][:T], batch.v_cache[b][l][:T]) <= 1e-2
+        assert rel_err(one.logits[0], batch.logits[b]) <= 1e-2
+        assert np.max(np.abs(one.scores[0] - batch.scores[b])) <= 1e-4
 
 
 @pytest.mark.parametrize("chunk_tiles", [1, 3])
