@@ -47,6 +47,20 @@ def gemm_flops(w, P, S, k):
     return fl, rows
 
 
+def recorded_gemm_traffic(workload: str):
+    """Bytes crossing the L2 boundary per GEMM launch, from the committed rocprofv3 counter summary of this
+    workload (profiles/), or None if there is none.  Counters cannot be read from inside the process."""
+    path = os.path.join(ROOT, "profiles", f"rc_reuse_{workload}_l2_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("gemm_hbm_bytes_per_launch"):
+                    return float(line.split()[1])
+    except OSError:
+        pass
+    return None
+
+
 def device_model(rc, torch, w, seed):
     sh = w.shape
     g = torch.Generator(device="cuda")
@@ -232,7 +246,7 @@ def main() -> int:
                    "layers": [w.l_start, w.l_det, w.l_end], "n_layers": sh.n_layers, "d_model": sh.d_model,
                    "kv_layout": "contiguous", "batch": 1},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": recorded_gemm_traffic(w.name),
                      "kernel": "projection GEMMs (all launches of one step)",
                      "algorithmic_gflop_per_step": fl / 1e9, "gemm_ms_per_step": gemm_ms,
                      "gemm_launches_per_step": gemm_launches, "row_layers": rows},
