@@ -27,8 +27,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
 def gemm_flops(w, P, S, k):
-    """Algorithmic GEMM FLOPs of one step: 2 * W_l per active row and layer, the fresh values of the S
-    segment tokens at l_det, and the LM head on one row."""
+    """Algorithmic GEMM FLOPs of one step for one request: 2 * W_l per active row and layer, the fresh
+    values of the S segment tokens at l_det, and the LM head on one row."""
     sh = w.shape
     rows = 0
     last = 1
@@ -44,6 +44,15 @@ def gemm_flops(w, P, S, k):
     fl = 2.0 * sh.gemm_params_per_layer * rows
     fl += 2.0 * S * sh.d_model * sh.n_kv_heads * sh.head_dim
     fl += 2.0 * sh.d_model * sh.vocab
+    return fl, rows
+
+
+def gemm_flops_batch(w, lens, ks):
+    fl = rows = 0
+    for (P, S, _), k in zip(lens, ks):
+        f, r = gemm_flops(w, P, S, k)
+        fl += f
+        rows += r
     return fl, rows
 
 
@@ -137,10 +146,13 @@ def main() -> int:
     from paper_2603_13289_amd import binding as rc
     from synth import WORKLOADS, budget_to_k
 
+    from synth import make_block_table, ragged_lengths
     w = WORKLOADS[args.workload]
     sh = w.shape
-    P, S, A = w.n_prefix, w.n_seg, w.n_alt
-    k = budget_to_k(S, w.budget_pct)
+    lens = ragged_lengths(w)                       # [(P, S, alternate-prefix length)] per request
+    n_req = len(lens)
+    ks = [budget_to_k(S, w.budget_pct) for _, S, _ in lens]
+    P, S, A, k = lens[0][0], lens[0][1], lens[0][2], ks[0]
     dt = rc.rc_dtype_of(sh.dtype)
     td = rc.torch_dtype(dt)
     torch.cuda.set_device(0)
@@ -149,30 +161,40 @@ def main() -> int:
     def hidden(n):
         return torch.randn((n, sh.d_model), generator=g, device="cuda", dtype=torch.float32).to(td)
 
-    x_alt, x_seg, x_prefix = hidden(A), hidden(S), hidden(P)
+    def cache(seq_lens, seed):
+        if w.block_size > 0:
+            tab, nb = make_block_table(seq_lens, w.block_size, seed=seed)
+            return rc.PagedKV(sh.n_layers, nb, w.block_size, sh.n_kv_heads, sh.head_dim, dt, tab)
+        return rc.PagedKV.contiguous(sh.n_layers, len(seq_lens), max(seq_lens), sh.n_kv_heads, sh.head_dim, dt)
 
-    # the earlier agent: prefill of [alt ; segment] keeps pre-RoPE keys, values and h entering l_start
-    old = rc.PagedKV.contiguous(sh.n_layers, 1, A + S, sh.n_kv_heads, sh.head_dim, dt)
-    old_pre = rc.PagedKV.contiguous(sh.n_layers, 1, A + S, sh.n_kv_heads, sh.head_dim, dt)
-    h_cap = torch.zeros((A + S, sh.d_model), dtype=td, device="cuda")
-    lg = torch.zeros((1, sh.vocab), dtype=torch.float32, device="cuda")
-    ws_p = rc.alloc_workspace(rc.rc_prefill_workspace_bytes(model, [max(A + S, P + S)]))
-    rc.rc_prefill(model, [torch.cat([x_alt, x_seg]).contiguous()], [0], old, lg, ws_p, k_pre=old_pre,
-                  capture_layer=w.l_start, h_capture=[h_cap])
+    x_alt = [hidden(a) for _, _, a in lens]
+    x_seg = [hidden(s_) for _, s_, _ in lens]
+    x_prefix = [hidden(p_) for p_, _, _ in lens]
+
+    # the earlier agents: prefill of [alt_b ; segment_b] keeps pre-RoPE keys, values and h entering l_start
+    old_lens = [a + s_ for _, s_, a in lens]
+    old, old_pre = cache(old_lens, 1), cache(old_lens, 1)
+    h_cap = [torch.zeros((n, sh.d_model), dtype=td, device="cuda") for n in old_lens]
+    lg = torch.zeros((n_req, sh.vocab), dtype=torch.float32, device="cuda")
+    new_lens = [p_ + s_ for p_, s_, _ in lens]
+    ws_p = rc.alloc_workspace(max(rc.rc_prefill_workspace_bytes(model, old_lens),
+                                  rc.rc_prefill_workspace_bytes(model, new_lens)))
+    rc.rc_prefill(model, [torch.cat([x_alt[b], x_seg[b]]).contiguous() for b in range(n_req)], list(range(n_req)),
+                  old, lg, ws_p, k_pre=old_pre, capture_layer=w.l_start, h_capture=h_cap)
     torch.cuda.synchronize()
     record = rc.PagedKV.from_pools(old_pre.k, old.v, old.block_table, dt)   # pre-RoPE keys + values
-    h_start = h_cap[A:].contiguous()
+    h_start = [h_cap[b][lens[b][2]:].contiguous() for b in range(n_req)]
 
-    dst = rc.PagedKV.contiguous(sh.n_layers, 1, P + S, sh.n_kv_heads, sh.head_dim, dt)
-    req = rc.Request(x_prefix, h_start, None, src_seq=0, src_offset=A, k_is_pre_rope=True, seg_old_start_pos=A,
-                     dst_seq=0)
-    plan = rc.Plan(w.l_start, w.l_det, w.l_end, [k])
-    ws = rc.alloc_workspace(rc.rc_reuse_workspace_bytes(model, [req], plan))
-    logits = torch.zeros((1, sh.vocab), dtype=torch.float32, device="cuda")
-    sel = torch.zeros(max(k, 1), dtype=torch.int32, device="cuda")
+    dst = cache(new_lens, 2)
+    reqs = [rc.Request(x_prefix[b], h_start[b], None, src_seq=b, src_offset=lens[b][2], k_is_pre_rope=True,
+                       seg_old_start_pos=lens[b][2], dst_seq=b) for b in range(n_req)]
+    plan = rc.Plan(w.l_start, w.l_det, w.l_end, ks)
+    ws = rc.alloc_workspace(rc.rc_reuse_workspace_bytes(model, reqs, plan))
+    logits = torch.zeros((n_req, sh.vocab), dtype=torch.float32, device="cuda")
+    sel = torch.zeros(max(sum(ks), 1), dtype=torch.int32, device="cuda")
 
     def step():
-        rc.rc_reuse(model, [req], plan, record, dst, logits, sel, None, ws)
+        rc.rc_reuse(model, reqs, plan, record, dst, logits, sel, None, ws)
 
     if args.counter_pass:
         args.no_cpu_baseline = args.no_full_prefill = True
@@ -212,25 +234,27 @@ def main() -> int:
               for name, (ms, n) in prof.items() if n}
     gemm_ms = sum(v["ms_per_step"] for n, v in stages.items() if n.startswith("gemm"))
     gemm_launches = sum(v["launches_per_step"] for n, v in stages.items() if n.startswith("gemm"))
-    fl, rows = gemm_flops(w, P, S, k)
+    fl, rows = gemm_flops_batch(w, lens, ks)
     achieved = fl / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
 
     full_ms = None
     if not args.no_full_prefill:
-        full_dst = rc.PagedKV.contiguous(sh.n_layers, 1, P + S, sh.n_kv_heads, sh.head_dim, dt)
-        x_full = torch.cat([x_prefix, x_seg]).contiguous()
-        rc.rc_prefill(model, [x_full], [0], full_dst, lg, ws_p)
+        full_dst = cache(new_lens, 3)
+        x_full = [torch.cat([x_prefix[b], x_seg[b]]).contiguous() for b in range(n_req)]
+        rc.rc_prefill(model, x_full, list(range(n_req)), full_dst, lg, ws_p)
         torch.cuda.synchronize()
         ev0.record()
         for _ in range(2):
-            rc.rc_prefill(model, [x_full], [0], full_dst, lg, ws_p)
+            rc.rc_prefill(model, x_full, list(range(n_req)), full_dst, lg, ws_p)
         ev1.record()
         torch.cuda.synchronize()
         full_ms = ev0.elapsed_time(ev1) / 2
 
+    ctx_tokens = sum(new_lens)
+    recomputed = sum((w.l_det - w.l_start) * S_ + (w.l_end - w.l_det + 1) * k_ for (_, S_, _), k_ in zip(lens, ks))
     out = {
         "metric": METRIC,
-        "value": (P + S) / (ms_per_step * 1e-3),
+        "value": ctx_tokens / (ms_per_step * 1e-3),
         "unit": "context tokens/s",
         "ttft_ms": ms_per_step,
         "n_gpus": 1,
@@ -242,21 +266,25 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": sh.dtype,
         "data": "synthetic",
-        "config": {"workload": w.name, "n_prefix": P, "n_seg": S, "n_alt": A, "k": k,
+        "config": {"workload": w.name, "n_prefix": P if n_req == 1 else [l[0] for l in lens],
+                   "n_seg": S if n_req == 1 else [l[1] for l in lens], "n_alt": A if n_req == 1 else [l[2] for l in lens],
+                   "k": k if n_req == 1 else ks, "context_tokens": ctx_tokens,
                    "layers": [w.l_start, w.l_det, w.l_end], "n_layers": sh.n_layers, "d_model": sh.d_model,
-                   "kv_layout": "contiguous", "batch": 1},
+                   "kv_layout": "contiguous" if w.block_size == 0 else f"paged, {w.block_size}-token blocks, shuffled",
+                   "batch": n_req},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": recorded_gemm_traffic(w.name),
                      "kernel": "projection GEMMs (all launches of one step)",
                      "algorithmic_gflop_per_step": fl / 1e9, "gemm_ms_per_step": gemm_ms,
-                     "gemm_launches_per_step": gemm_launches, "row_layers": rows},
+                     "gemm_launches_per_step": gemm_launches,
+                     "avg_launch_us": 1e3 * gemm_ms / max(gemm_launches, 1), "row_layers": rows},
         "stages_ms": {n: round(v["ms_per_step"], 4) for n, v in stages.items()},
         "ms_per_step_with_stage_events": ms_per_step_profiled,
         "full_prefill_ms": full_ms,
         "speedup_vs_full_prefill": (full_ms / ms_per_step) if full_ms else None,
-        "reuse_rate": 1.0 - ((w.l_det - w.l_start) * S + (w.l_end - w.l_det + 1) * k) / float(sh.n_layers * S),
+        "reuse_rate": 1.0 - recomputed / float(sh.n_layers * sum(l[1] for l in lens)),
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and n_req == 1:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))
     return 0

@@ -181,33 +181,7 @@ gemm_mfma_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const b
     }
   }
 
-  // epilogue: accumulator element e of a 32x32 block sits at row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
-  constexpr int FN_OUT = DUAL ? FN / 2 : FN;
-  constexpr int WTN_OUT = DUAL ? WTN / 2 : WTN;
-#pragma unroll
-  for (int i = 0; i < FM; ++i) {
-#pragma unroll
-    for (int j = 0; j < FN_OUT; ++j) {
-      const int col = n0 + wn * WTN_OUT + j * 32 + (lane & 31);
-      if (col >= n) continue;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = m0 + wm * WTM + i * 32 + 8 * (e / 4) + 4 * khalf + (e % 4);
-        if (row >= m) continue;
-        const size_t o = (size_t)row * ldc + col;
-        const float v = acc[i][j][e];
-        if (DUAL) {
-          reinterpret_cast<bf16*>(c)[o] = f32_to_bf16(silu_mf(v) * acc[i][j + FN_OUT][e]);
-        } else if (epi == EPI_STORE_F32) {
-          reinterpret_cast<float*>(c)[o] = v;
-        } else if (epi == EPI_ADD_F32) {
-          reinterpret_cast<float*>(c)[o] += v;
-        } else {
-          reinterpret_cast<bf16*>(c)[o] = f32_to_bf16(v);
-        }
-      }
-    }
-  }
+  store_tile<FM, FN, WTM, WTN, DUAL>(acc, c, m, n, ldc, epi, m0, n0, wm, wn, lane);
 }
 
 // ------------------------------------------------------------------ direct-to-LDS, double-buffered variant
@@ -494,7 +468,7 @@ static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const 
   return hipGetLastError();
 }
 
-static int g_gemm_tile = 0;   // 0: by shape; 1: 128x256; 2: 256x256; 3: 128x128; 4-6: the same with direct-to-LDS loads
+static int g_gemm_tile = 0;   // 0: by shape; 1-3: register-staged 128x256 / 256x256 / 128x128; 5, 6: direct-to-LDS 256x256 / 128x128
 void set_gemm_tile(int t) { g_gemm_tile = t; }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int OCC>
@@ -539,9 +513,8 @@ static hipError_t dispatch(const bf16* a, const bf16* w, const bf16* w2, const b
       tile = cost5 <= cost6 ? 5 : 6;
     }
   }
-  if (tile >= 4 && (k % BK) != 0) tile -= 3;   // the direct-load kernels need whole K steps
+  if (tile >= 5 && (k % BK) != 0) tile = 3;   // the direct-load kernels need whole K steps   // the direct-load kernels need whole K steps
   switch (tile) {
-    case 4: return launch_dl<128, 256, 2, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, nullptr, st);
     case 5: return launch_dl<256, 256, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st);
     case 6: return launch_dl<128, 128, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, nullptr, st);
     case 2: return launch_cfg<256, 256, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);
