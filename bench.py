@@ -237,6 +237,53 @@ def main() -> int:
     fl, rows = gemm_flops_batch(w, lens, ks)
     achieved = fl / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
 
+    # bandwidth-bound stages and attention against their own rooflines (algorithmic bytes / FLOPs only)
+    es = 2 if sh.dtype == "bf16" else 4
+    nq, nkv = sh.n_q_heads * sh.head_dim, sh.n_kv_heads * sh.head_dim
+    sel_host = sel.cpu().numpy()
+    b_rerotate = b_scatter = b_norm = b_score = 0.0
+    attn_pairs = 0.0
+    ko = 0
+    for (P_, S_, _), k_ in zip(lens, ks):
+        b_rerotate += sh.n_layers * 2 * (2 * S_ * nkv * es)                       # K and V, read + write
+        b_score += 2 * S_ * nkv * es + 4 * S_
+        sel_pos = P_ + sel_host[ko:ko + k_].astype("float64")
+        ko += k_
+        pre_pairs = P_ * (P_ + 1) / 2.0
+        seg_pairs_all = S_ * P_ + S_ * (S_ + 1) / 2.0
+        last_pairs = float(P_ + S_)
+        for l in range(sh.n_layers):
+            if l < w.l_start:
+                rows, pairs = P_, pre_pairs
+            elif l < w.l_det:
+                rows, pairs = P_ + S_, pre_pairs + seg_pairs_all
+            elif l <= w.l_end:
+                rows, pairs = P_ + k_ + 1, pre_pairs + float((sel_pos + 1).sum()) + last_pairs
+            else:
+                rows, pairs = P_ + 1, pre_pairs + last_pairs
+            b_scatter += rows * ((nq + 2 * nkv) * 4 + nq * es + 2 * nkv * es)
+            b_norm += 2 * rows * sh.d_model * (4 + es)
+            attn_pairs += pairs
+    attn_flops = 4.0 * sh.head_dim * sh.n_q_heads * attn_pairs
+
+    def hbm(stage, nbytes):
+        ms = stages.get(stage, {}).get("ms_per_step", 0.0)
+        gbs = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        return {"bound": "hbm", "achieved": gbs, "peak": 8000.0, "unit": "GB/s", "frac": gbs / 8000.0,
+                "algorithmic_mb_per_step": nbytes / 1e6, "ms_per_step": ms}
+
+    attn_ms = stages.get("attention", {}).get("ms_per_step", 0.0)
+    stage_rooflines = {
+        "rope_rerotate": hbm("rope_rerotate", b_rerotate),
+        "rope_scatter": hbm("rope_scatter", b_scatter),
+        "rmsnorm": hbm("rmsnorm", b_norm),
+        "vdev_score": hbm("vdev_score", b_score),
+        "attention": {"bound": "mfma", "achieved": attn_flops / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else 0.0,
+                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                      "frac": (attn_flops / (attn_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS) if attn_ms > 0 else 0.0,
+                      "algorithmic_gflop_per_step": attn_flops / 1e9, "ms_per_step": attn_ms},
+    }
+
     full_ms = None
     if not args.no_full_prefill:
         full_dst = cache(new_lens, 3)
@@ -279,6 +326,7 @@ def main() -> int:
                      "gemm_launches_per_step": gemm_launches,
                      "avg_launch_us": 1e3 * gemm_ms / max(gemm_launches, 1), "row_layers": rows},
         "stages_ms": {n: round(v["ms_per_step"], 4) for n, v in stages.items()},
+        "stage_rooflines": stage_rooflines,
         "ms_per_step_with_stage_events": ms_per_step_profiled,
         "full_prefill_ms": full_ms,
         "speedup_vs_full_prefill": (full_ms / ms_per_step) if full_ms else None,

@@ -427,22 +427,28 @@ rc_status run_job(const Job& job, Workspace& w, hipStream_t st) {
     return RC_OK;
   };
 
-  bool delta_done = false;
   for (int l = 0; l < d.n_layers; ++l) {
     const rc_layer_w& lw = job.m->layers[l];
     const Phase ph = phase_of_layer(l, job.l_start, job.l_det, job.l_end);
     if (cur < 0 || (ph != cur && ph != PH_C)) RC_TRY(enter_phase(ph));
 
-    // K1: take over the reused rows of this layer (keys to their new positions, values copied)
-    if (has_seg) {
+    // K1, once: take over the reused rows of every layer (keys to their new positions, values copied).
+    // Layers that recompute rows later simply overwrite them.
+    if (l == 0 && has_seg) {
       const KvGeom gs = geom_of(*job.src, d);
-      if (!delta_done) {
-        RC_LAUNCH(PC_TABLES, launch_delta_table(w.delta_tab, w.tables + cur, n_req, d.head_dim / 2, (double)d.rope_base, st));
-        delta_done = true;
+      RC_LAUNCH(PC_TABLES, launch_delta_table(w.delta_tab, w.tables + cur, n_req, d.head_dim / 2, (double)d.rope_base, st));
+      for (int l0 = 0; l0 < d.n_layers; l0 += kRerotateLayers) {
+        const int nl = std::min(kRerotateLayers, d.n_layers - l0);
+        RerotatePtrs ptrs;
+        for (int i = 0; i < nl; ++i) {
+          ptrs.k_src[i] = job.src->k_pool[l0 + i];
+          ptrs.v_src[i] = job.src->v_pool[l0 + i];
+          ptrs.k_dst[i] = job.dst->k_pool[l0 + i];
+          ptrs.v_dst[i] = job.dst->v_pool[l0 + i];
+        }
+        RC_LAUNCH(PC_REROTATE, launch_rerotate<T>(ptrs, nl, gs, gd, w.tables + cur, n_req, job.max_seg, w.rope_tab,
+                                                  w.delta_tab, st));
       }
-      RC_LAUNCH(PC_REROTATE, launch_rerotate<T>((const T*)job.src->k_pool[l], (const T*)job.src->v_pool[l], gs,
-                                (T*)job.dst->k_pool[l], (T*)job.dst->v_pool[l], gd, w.tables + cur, n_req,
-                                job.max_seg, w.rope_tab, w.delta_tab, st));
     }
 
     // detection layer: fresh values of every segment token -> Eq. (1) -> selection
@@ -800,12 +806,12 @@ rc_status rc_rope_rerotate(const rc_kv_layer* src, int32_t src_seq, int32_t src_
   const int half = src->head_dim / 2;
   if (k_is_pre_rope) RC_HIP(launch_rope_table(rope_tab, n_pos, half, (double)rope_base, st));
   else RC_HIP(launch_delta_table(delta_tab, dt, 1, half, (double)rope_base, st));
+  RerotatePtrs ptrs;
+  ptrs.k_src[0] = src->k; ptrs.v_src[0] = src->v; ptrs.k_dst[0] = dst->k; ptrs.v_dst[0] = dst->v;
   if (src->dtype == RC_BF16)
-    RC_HIP(launch_rerotate<bf16>((const bf16*)src->k, (const bf16*)src->v, geom_of(*src), (bf16*)dst->k,
-                                 (bf16*)dst->v, geom_of(*dst), dt, 1, n_tokens, rope_tab, delta_tab, st));
+    RC_HIP(launch_rerotate<bf16>(ptrs, 1, geom_of(*src), geom_of(*dst), dt, 1, n_tokens, rope_tab, delta_tab, st));
   else
-    RC_HIP(launch_rerotate<float>((const float*)src->k, (const float*)src->v, geom_of(*src), (float*)dst->k,
-                                  (float*)dst->v, geom_of(*dst), dt, 1, n_tokens, rope_tab, delta_tab, st));
+    RC_HIP(launch_rerotate<float>(ptrs, 1, geom_of(*src), geom_of(*dst), dt, 1, n_tokens, rope_tab, delta_tab, st));
   return RC_OK;
 }
 

@@ -140,10 +140,17 @@ hipError_t launch_rope_table(float2* tab, int n_pos, int half, double base, hipS
 hipError_t launch_delta_table(float2* tab, const ReqTable* table, int n_req, int half, double base,
                               hipStream_t st);
 
+// pool pointers of up to kRerotateLayers layers, passed to the re-rotation kernel by value
+constexpr int kRerotateLayers = 32;
+struct RerotatePtrs {
+  const void* k_src[kRerotateLayers];
+  const void* v_src[kRerotateLayers];
+  void* k_dst[kRerotateLayers];
+  void* v_dst[kRerotateLayers];
+};
 template <typename T>
-hipError_t launch_rerotate(const T* k_src, const T* v_src, KvGeom gs, T* k_dst, T* v_dst, KvGeom gd,
-                           const ReqTable* table, int n_req, int max_seg, const float2* rope_tab,
-                           const float2* delta_tab, hipStream_t st);
+hipError_t launch_rerotate(const RerotatePtrs& ptrs, int n_layers, KvGeom gs, KvGeom gd, const ReqTable* table,
+                           int n_req, int max_seg, const float2* rope_tab, const float2* delta_tab, hipStream_t st);
 
 template <typename T>
 hipError_t launch_build_rows(const ReqTable* table, int total_rows, const float* h_old, float* h_new,

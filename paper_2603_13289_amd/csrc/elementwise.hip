@@ -61,13 +61,17 @@ hipError_t launch_delta_table(float2* tab, const ReqTable* table, int n_req, int
 
 // ------------------------------------------------------------------ K1: re-rotate reused keys, copy values
 // One thread moves two 16-byte chunks of one (token, head) row: elements [c, c+VEC) and their rotary
-// partners [half+c, half+c+VEC).  grid.y = request.
+// partners [half+c, half+c+VEC).  grid.y = request, grid.z = layer (pool pointers travel in the
+// kernel argument), so one launch takes over the segment in up to kRerotateLayers layers.
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
-rerotate_kernel(const T* __restrict__ k_src, const T* __restrict__ v_src, KvGeom gs, T* __restrict__ k_dst,
-                T* __restrict__ v_dst, KvGeom gd, const ReqTable* __restrict__ table,
+rerotate_kernel(RerotatePtrs ptrs, KvGeom gs, KvGeom gd, const ReqTable* __restrict__ table,
                 const float2* __restrict__ rope_tab, const float2* __restrict__ delta_tab) {
   constexpr int VEC = Vec16<T>::N;
+  const T* __restrict__ k_src = reinterpret_cast<const T*>(ptrs.k_src[blockIdx.z]);
+  const T* __restrict__ v_src = reinterpret_cast<const T*>(ptrs.v_src[blockIdx.z]);
+  T* __restrict__ k_dst = reinterpret_cast<T*>(ptrs.k_dst[blockIdx.z]);
+  T* __restrict__ v_dst = reinterpret_cast<T*>(ptrs.v_dst[blockIdx.z]);
   const ReqDev& rq = table->r[blockIdx.y];
   const int half = gs.head_dim / 2;
   const int tpr = half / VEC;  // threads per (token, head) row
@@ -98,20 +102,20 @@ rerotate_kernel(const T* __restrict__ k_src, const T* __restrict__ v_src, KvGeom
 }
 
 template <typename T>
-hipError_t launch_rerotate(const T* k_src, const T* v_src, KvGeom gs, T* k_dst, T* v_dst, KvGeom gd,
-                           const ReqTable* table, int n_req, int max_seg, const float2* rope_tab,
-                           const float2* delta_tab, hipStream_t st) {
-  if (max_seg <= 0 || n_req <= 0) return hipSuccess;
+hipError_t launch_rerotate(const RerotatePtrs& ptrs, int n_layers, KvGeom gs, KvGeom gd, const ReqTable* table,
+                           int n_req, int max_seg, const float2* rope_tab, const float2* delta_tab,
+                           hipStream_t st) {
+  if (max_seg <= 0 || n_req <= 0 || n_layers <= 0) return hipSuccess;
   const int tpr = (gs.head_dim / 2) / Vec16<T>::N;
   const long work = (long)max_seg * gs.n_kv_heads * tpr;
-  dim3 grid((unsigned)((work + kThreads - 1) / kThreads), (unsigned)n_req);
-  rerotate_kernel<T><<<grid, kThreads, 0, st>>>(k_src, v_src, gs, k_dst, v_dst, gd, table, rope_tab, delta_tab);
+  dim3 grid((unsigned)((work + kThreads - 1) / kThreads), (unsigned)n_req, (unsigned)n_layers);
+  rerotate_kernel<T><<<grid, kThreads, 0, st>>>(ptrs, gs, gd, table, rope_tab, delta_tab);
   return hipGetLastError();
 }
-template hipError_t launch_rerotate<float>(const float*, const float*, KvGeom, float*, float*, KvGeom,
-                                           const ReqTable*, int, int, const float2*, const float2*, hipStream_t);
-template hipError_t launch_rerotate<bf16>(const bf16*, const bf16*, KvGeom, bf16*, bf16*, KvGeom,
-                                          const ReqTable*, int, int, const float2*, const float2*, hipStream_t);
+template hipError_t launch_rerotate<float>(const RerotatePtrs&, int, KvGeom, KvGeom, const ReqTable*, int, int,
+                                           const float2*, const float2*, hipStream_t);
+template hipError_t launch_rerotate<bf16>(const RerotatePtrs&, int, KvGeom, KvGeom, const ReqTable*, int, int,
+                                          const float2*, const float2*, hipStream_t);
 
 // ------------------------------------------------------------------ active-row bookkeeping
 // Builds the compact residual-stream buffer of a new phase: one workgroup per destination row.

@@ -95,6 +95,11 @@ _add(Workload("qwen32b_32k", _QWEN32, 4096, 32768, 2048, 15, 16, 48, 10))
 # Parity-sized relatives: same structure, sizes the CPU oracle finishes in seconds.
 _add(Workload("tiny_f32_paged", _TINY, 100, 203, 77, 0, 1, 1, 20, block_size=16,
               note="ragged sizes, paged"))
+_TINY5 = ModelShape(5, 256, 4, 2, 64, 688, 512, 1.0e4, dtype="f32")
+_add(Workload("tiny5_f32", _TINY5, 70, 150, 33, 1, 2, 3, 20, block_size=16,
+              note="5 layers so that every phase (before / dense / sparse / after) has at least one layer"))
+_add(Workload("tiny5_f32_noprefix", _TINY5, 0, 120, 40, 1, 2, 3, 20, note="segment starts at position 0"))
+_add(Workload("tiny5_f32_one", _TINY5, 9, 1, 5, 1, 2, 3, 100, note="one-token segment"))
 _add(Workload("small_bf16", ModelShape(4, 512, 8, 2, 128, 1408, 2048, 1.0e6), 150, 333, 70, 0, 1, 2, 15,
               note="narrow bf16 model, 4 layers, head_dim 128, group 4"))
 _add(Workload("small_bf16_ragged", ModelShape(4, 512, 8, 2, 128, 1408, 2048, 1.0e6), 0, 0, 0, 0, 1, 2, 15,

@@ -99,6 +99,21 @@ def test_prefill_matches_oracle_full_prefill_f32():
     assert rel_err(logits, full.logits) <= TOL["f32"]
 
 
+@pytest.mark.parametrize("name,k,n_suffix", [("tiny5_f32", None, 0), ("tiny5_f32", None, 3), ("tiny5_f32", 0, 0),
+                                             ("tiny5_f32", 150, 0), ("tiny5_f32_noprefix", None, 0),
+                                             ("tiny5_f32_noprefix", 0, 2), ("tiny5_f32_one", None, 0),
+                                             ("tiny5_f32_one", 0, 0)])
+def test_f32_all_phases_and_edge_shapes(name, k, n_suffix):
+    """Five layers with triple (1, 2, 3): layers before l_start, a dense layer, sparse layers and a tail layer
+    all exist; plus no prefix at all, a one-token segment, zero and full budgets, with and without a suffix."""
+    case = build_case(name, k_override=k, n_suffix=n_suffix)
+    want = oracle_relay(case)
+    run = hip_relay(case)
+    kk = case.reqs[0].k
+    exact = kk in (0, case.reqs[0].S) or selection_margin(want.score, kk) > MARGIN
+    _check_against_oracle(case, run, [want], TOL["f32"], check_sel=exact)
+
+
 # ------------------------------------------------------------------ bf16 configurations
 @pytest.mark.parametrize("name", ["small_bf16", "qwen32b_trunc", "mistral7b_trunc"])
 def test_bf16_matches_oracle_with_forced_indices(name):
