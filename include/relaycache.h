@@ -125,18 +125,29 @@ typedef struct {
                             0: they carry the rotation of positions seg_old_start_pos + j */
   int32_t seg_old_start_pos;
   int32_t dst_seq;       /* row of the destination block table */
-  const float* s_inf;    /* reserved for influence scores (Eq. 6); must be NULL */
+  const float* s_inf;    /* optional [S] float: influence scores the earlier agent accumulated while decoding
+                            (Eq. 6); only read by the threshold selector; NULL: no influence term */
 } rc_request;
+
+typedef enum {
+  RC_SELECT_BUDGET = 0,    /* the k_per_req[b] tokens with the largest deviation (ties to the lower index) */
+  RC_SELECT_THRESHOLD = 1  /* the paper's selector, Eq. (5)-(10): deviation >= tau_dev * mean, united with
+                              influence >= tau_inf * mean (if s_inf is given) and the last k_suf tokens */
+} rc_selector;
 
 typedef struct {
   int32_t l_start, l_det, l_end; /* 0-based; 0 <= l_start < l_det <= l_end < n_layers.
                                     h_start is the input of layer l_start; layers [l_start, l_det)
                                     are recomputed for all S tokens, [l_det, l_end] for selected
                                     tokens only (both ends included). */
-  const int32_t* k_per_req;      /* host [n_req]: recompute budget as a token count, 0 <= k <= S */
-  const int32_t* forced_idx;     /* device, optional: concatenated per request, k_per_req[b] ascending
-                                    segment indices that replace the top-k result (scores are still
-                                    computed).  NULL: select by score. */
+  const int32_t* k_per_req;      /* host [n_req]: recompute budget as a token count, 0 <= k <= S
+                                    (RC_SELECT_BUDGET; ignored by RC_SELECT_THRESHOLD) */
+  const int32_t* forced_idx;     /* device, optional, budget selector only: concatenated per request,
+                                    k_per_req[b] ascending segment indices that replace the top-k result
+                                    (scores are still computed).  NULL: select by score. */
+  int32_t selector;              /* rc_selector */
+  float tau_dev, tau_inf;        /* Eq. (5), Eq. (7) scaling factors (paper defaults 1.5, 1.45) */
+  int32_t k_suf;                 /* Eq. (8)-(9): trailing segment tokens always selected (paper default 10) */
 } rc_plan;
 
 /* Workspace size for rc_reuse with these requests (0 on invalid arguments). */
@@ -150,8 +161,15 @@ RC_API size_t rc_reuse_workspace_bytes(const rc_model* m, const rc_request* reqs
  *   dst      in/out: on return rows 0..P+S+n_suffix-1 of every layer of sequence dst_seq hold
  *            the corrected cache: new tokens' K/V, re-rotated reused K/V, recomputed rows.
  *   logits   [n_req][vocab] float: logits of the last position of each request.
- *   sel_idx  [sum k_per_req] int32, per request ascending: the k tokens with the largest
- *            deviation at l_det, equal scores resolved to the lower index.
+ *   sel_idx  budget selector: [sum k_per_req] int32, per request ascending: the k tokens with the
+ *            largest deviation at l_det, equal scores resolved to the lower index.
+ *            threshold selector: [sum n_seg] int32; request b's selection starts at the sum of the
+ *            earlier requests' n_seg, ascending, sel_cnt[b] entries.
+ *   sel_cnt  threshold selector: [n_req] int32 (device), number of selected tokens per request;
+ *            may be NULL for the budget selector.
+ *            The threshold selector's row counts are only known after scoring: the call copies
+ *            sel_cnt to the host and waits for the stream once, at l_det, before it enqueues the
+ *            remaining layers.
  *   scores   optional [sum n_seg] float: Eq. (1) at l_det for every segment token of every
  *            request with k > 0 (others untouched); NULL to skip.
  *   With n_suffix == 0 the last segment token is recomputed from l_start to the last layer in
@@ -160,10 +178,10 @@ RC_API size_t rc_reuse_workspace_bytes(const rc_model* m, const rc_request* reqs
  *
  * Errors: RC_E_INVALID_ARG (nulls, triple, k out of range, n_seg == 0 with no new token),
  * RC_E_CAPACITY (n_req > RC_MAX_REQ, sequence longer than max_blocks_per_seq * block_size,
- * seq index out of range), RC_E_UNSUPPORTED (s_inf given, dtype/head_dim), RC_E_WORKSPACE. */
+ * seq index out of range), RC_E_UNSUPPORTED (dtype/head_dim), RC_E_WORKSPACE. */
 RC_API rc_status rc_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req, const rc_plan* plan,
                    const rc_paged_kv* src, const rc_paged_kv* dst, float* logits, int32_t* sel_idx,
-                   float* scores, void* workspace, size_t workspace_bytes, void* stream);
+                   int32_t* sel_cnt, float* scores, void* workspace, size_t workspace_bytes, void* stream);
 
 /* FULL baseline (Appendix "Baseline Descriptions") and the earlier agent's side: a plain causal
  * prefill of n_req sequences of new tokens, written into dst.  Optionally records what the cache
@@ -236,6 +254,13 @@ RC_API rc_status rc_topk(const float* score, int32_t n, int32_t k, int32_t* idx_
  * score[j] >= tau * mean(score); *count_out (device int32) their number.  idx_out holds n entries. */
 RC_API rc_status rc_threshold_select(const float* score, int32_t n, float tau, int32_t* idx_out,
                               int32_t* count_out, void* stream);
+
+/* The complete selector, Eq. (5)-(10): idx_out receives, ascending, every j with
+ * s_dev[j] >= tau_dev * mean(s_dev), or s_inf[j] >= tau_inf * mean(s_inf) (s_inf may be NULL: no such
+ * term), or j >= n - k_suf; *count_out (device int32) their number.  idx_out holds n entries.
+ * Means and comparisons are taken in double on the given float scores. */
+RC_API rc_status rc_final_select(const float* s_dev, const float* s_inf, int32_t n, float tau_dev, float tau_inf,
+                          int32_t k_suf, int32_t* idx_out, int32_t* count_out, void* stream);
 
 /* Causal grouped-query attention of n arbitrary query rows over one layer of a cache
  * (sparse rectification, Section 4.2): row i (already rotated, at position q_pos[i], ascending)

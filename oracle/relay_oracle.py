@@ -47,7 +47,7 @@ none): that part is "parity unpinned" by necessity.
 from __future__ import annotations
 
 from dataclasses import dataclass
-from typing import List, Optional, Sequence
+from typing import List, Optional, Sequence, Tuple
 
 import numpy as np
 
@@ -289,7 +289,9 @@ class RelayResult:
 
 def relay_prefill(m: OracleModel, x_prefix: np.ndarray, seg: SegmentRecord, l_start: int,
                   l_det: int, l_end: int, k: int, x_suffix: Optional[np.ndarray] = None,
-                  forced_idx: Optional[Sequence[int]] = None) -> RelayResult:
+                  forced_idx: Optional[Sequence[int]] = None,
+                  thresholds: Optional[Tuple[float, float, int]] = None,
+                  s_inf: Optional[Sequence[float]] = None) -> RelayResult:
     """Prefill of [x_prefix ; segment ; x_suffix] that takes over the segment's KV.
 
     1. every layer: reused keys moved to positions P..P+S-1, values copied;
@@ -301,6 +303,9 @@ def relay_prefill(m: OracleModel, x_prefix: np.ndarray, seg: SegmentRecord, l_st
        back before that layer's attention;
     6. layers > l_end: only new tokens (and that last token) continue.
     `forced_idx` replaces the top-k result (the score is still computed).
+    `thresholds` = (tau_dev, tau_inf, k_suf) switches step 4 from the fixed budget to the
+    selector of Eq. (5)-(10), with the influence scores `s_inf` of Eq. (6) if given; `k` is
+    then ignored and the dense layers always run.
     """
     assert 0 <= l_start < l_det <= l_end < m.n_layers
     x_prefix = np.asarray(x_prefix, F64)
@@ -308,6 +313,7 @@ def relay_prefill(m: OracleModel, x_prefix: np.ndarray, seg: SegmentRecord, l_st
     n_suf = 0 if x_suffix is None else x_suffix.shape[0]
     t = p + s + n_suf
     assert 0 <= k <= s
+    dense = k > 0 if thresholds is None else s > 0
     shape = (m.n_layers, t, m.n_kv_heads, m.head_dim)
     kc, vc = np.zeros(shape, F64), np.zeros(shape, F64)
 
@@ -335,18 +341,23 @@ def relay_prefill(m: OracleModel, x_prefix: np.ndarray, seg: SegmentRecord, l_st
 
     for l in range(m.n_layers):
         if l == l_start:
-            if k > 0:
+            if dense:
                 seg_rows = np.arange(s)
                 h_seg = np.asarray(seg.h_start, F64).copy()
             elif carries_logits:
                 seg_rows = np.array([s - 1])
                 h_seg = np.asarray(seg.h_start, F64)[s - 1:s].copy()
-        if l == l_det and k > 0:
+        if l == l_det and dense:
             w = m.layers[l]
             v_fresh = linear(rmsnorm(h_seg, w["g_attn"], m.rms_eps), w["wv"])
             v_fresh = v_fresh.reshape(s, m.n_kv_heads, m.head_dim)
             score = vdev_score(vc[l][seg_pos], v_fresh)
-            sel = topk_select(score, k) if forced_idx is None else np.sort(np.asarray(forced_idx, np.int32))
+            if thresholds is not None:
+                sel = final_selection(score, s_inf, thresholds[0], thresholds[1], thresholds[2])
+            elif forced_idx is not None:
+                sel = np.sort(np.asarray(forced_idx, np.int32))
+            else:
+                sel = topk_select(score, k)
             keep = set(sel.tolist())
             if carries_logits:
                 keep.add(s - 1)

@@ -20,11 +20,12 @@ LIB_PATH = os.path.join(_PKG, "librelaycache.so")
 RC_OK, RC_E_INVALID_ARG, RC_E_UNSUPPORTED, RC_E_WORKSPACE, RC_E_HIP, RC_E_CAPACITY = 0, -1, -2, -3, -4, -5
 RC_F32, RC_BF16 = 0, 1
 RC_MAX_REQ = 32
+RC_SELECT_BUDGET, RC_SELECT_THRESHOLD = 0, 1
 
 EXPORTS = [
     "rc_status_str", "rc_build_info", "rc_model_create", "rc_model_destroy", "rc_reuse_workspace_bytes",
     "rc_reuse", "rc_prefill_workspace_bytes", "rc_prefill", "rc_stage_workspace_bytes", "rc_rope_rerotate",
-    "rc_vdev_score", "rc_topk", "rc_threshold_select", "rc_sparse_attention", "rc_gemm_rows",
+    "rc_vdev_score", "rc_topk", "rc_threshold_select", "rc_final_select", "rc_sparse_attention", "rc_gemm_rows",
     "rc_scatter_paged", "rc_profile_enable", "rc_profile_class_count", "rc_profile_class_name", "rc_profile_read",
     "rc_tune_set", "rc_sparse_attention_workspace_bytes",
     "rc_gemm_workspace_bytes",
@@ -68,7 +69,8 @@ class rc_request(C.Structure):
 
 class rc_plan(C.Structure):
     _fields_ = [("l_start", C.c_int32), ("l_det", C.c_int32), ("l_end", C.c_int32),
-                ("k_per_req", C.POINTER(C.c_int32)), ("forced_idx", C.c_void_p)]
+                ("k_per_req", C.POINTER(C.c_int32)), ("forced_idx", C.c_void_p),
+                ("selector", C.c_int32), ("tau_dev", C.c_float), ("tau_inf", C.c_float), ("k_suf", C.c_int32)]
 
 
 def _load() -> C.CDLL:
@@ -89,7 +91,7 @@ def _load() -> C.CDLL:
     lib.rc_reuse_workspace_bytes.argtypes = [vp, C.POINTER(rc_request), i32, C.POINTER(rc_plan)]
     lib.rc_reuse.restype = C.c_int
     lib.rc_reuse.argtypes = [vp, C.POINTER(rc_request), i32, C.POINTER(rc_plan), C.POINTER(rc_paged_kv),
-                             C.POINTER(rc_paged_kv), vp, vp, vp, vp, sz, vp]
+                             C.POINTER(rc_paged_kv), vp, vp, vp, vp, vp, sz, vp]
     lib.rc_prefill_workspace_bytes.restype = sz
     lib.rc_prefill_workspace_bytes.argtypes = [vp, C.POINTER(i32), i32]
     lib.rc_prefill.restype = C.c_int
@@ -106,6 +108,8 @@ def _load() -> C.CDLL:
     lib.rc_topk.argtypes = [vp, i32, i32, vp, vp]
     lib.rc_threshold_select.restype = C.c_int
     lib.rc_threshold_select.argtypes = [vp, i32, C.c_float, vp, vp, vp]
+    lib.rc_final_select.restype = C.c_int
+    lib.rc_final_select.argtypes = [vp, vp, i32, C.c_float, C.c_float, i32, vp, vp, vp]
     lib.rc_sparse_attention.restype = C.c_int
     lib.rc_sparse_attention.argtypes = [vp, vp, i32, i32, C.POINTER(rc_kv_layer), i32, vp, vp, sz, vp]
     lib.rc_sparse_attention_workspace_bytes.restype = sz
@@ -284,12 +288,13 @@ class Request:
     k_is_pre_rope: bool = True
     seg_old_start_pos: int = 0
     dst_seq: int = 0
+    s_inf: Optional[torch.Tensor] = None      # [S] float32 influence scores (threshold selector only)
 
     def c(self) -> rc_request:
         n = lambda t: 0 if t is None else int(t.shape[0])
         return rc_request(n(self.x_prefix), _ptr(self.x_prefix), n(self.h_start), _ptr(self.h_start),
                           n(self.x_suffix), _ptr(self.x_suffix), self.src_seq, self.src_offset,
-                          1 if self.k_is_pre_rope else 0, self.seg_old_start_pos, self.dst_seq, None)
+                          1 if self.k_is_pre_rope else 0, self.seg_old_start_pos, self.dst_seq, _ptr(self.s_inf))
 
 
 @dataclass
@@ -297,13 +302,20 @@ class Plan:
     l_start: int
     l_det: int
     l_end: int
-    k_per_req: List[int]
+    k_per_req: Optional[List[int]]                # budget selector; None with the threshold selector
     forced_idx: Optional[torch.Tensor] = None     # int32 device, concatenated
+    selector: int = RC_SELECT_BUDGET
+    tau_dev: float = 1.5
+    tau_inf: float = 1.45
+    k_suf: int = 10
 
     def c(self):
-        ks = (C.c_int32 * len(self.k_per_req))(*self.k_per_req)
-        return rc_plan(self.l_start, self.l_det, self.l_end, C.cast(ks, C.POINTER(C.c_int32)),
-                       _ptr(self.forced_idx)), ks
+        ks = None
+        if self.k_per_req is not None:
+            ks = (C.c_int32 * len(self.k_per_req))(*self.k_per_req)
+        return rc_plan(self.l_start, self.l_det, self.l_end,
+                       C.cast(ks, C.POINTER(C.c_int32)) if ks is not None else None,
+                       _ptr(self.forced_idx), self.selector, self.tau_dev, self.tau_inf, self.k_suf), ks
 
 
 def _req_array(reqs: Sequence[Request]):
@@ -320,11 +332,11 @@ def rc_reuse_workspace_bytes(model: Model, reqs: Sequence[Request], plan: Plan) 
 
 def rc_reuse(model: Model, reqs: Sequence[Request], plan: Plan, src: Optional[PagedKV], dst: PagedKV,
              logits: torch.Tensor, sel_idx: Optional[torch.Tensor], scores: Optional[torch.Tensor],
-             workspace: torch.Tensor, stream=None) -> None:
+             workspace: torch.Tensor, stream=None, sel_cnt: Optional[torch.Tensor] = None) -> None:
     cplan, _keep = plan.c()
     st = lib.rc_reuse(model.handle, _req_array(reqs), len(reqs), C.byref(cplan),
                       C.byref(src.c) if src is not None else None, C.byref(dst.c), _ptr(logits), _ptr(sel_idx),
-                      _ptr(scores), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+                      _ptr(sel_cnt), _ptr(scores), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(st, "rc_reuse")
 
 
@@ -379,6 +391,12 @@ def rc_threshold_select(score: torch.Tensor, n: int, tau: float, idx_out: torch.
                         stream=None) -> None:
     _check(lib.rc_threshold_select(_ptr(score), n, tau, _ptr(idx_out), _ptr(count_out), _stream(stream)),
            "rc_threshold_select")
+
+
+def rc_final_select(s_dev: torch.Tensor, s_inf: Optional[torch.Tensor], n: int, tau_dev: float, tau_inf: float,
+                    k_suf: int, idx_out: torch.Tensor, count_out: torch.Tensor, stream=None) -> None:
+    _check(lib.rc_final_select(_ptr(s_dev), _ptr(s_inf), n, tau_dev, tau_inf, k_suf, _ptr(idx_out), _ptr(count_out),
+                               _stream(stream)), "rc_final_select")
 
 
 def rc_sparse_attention_workspace_bytes(n: int, n_q_heads: int, cache: rc_kv_layer) -> int:

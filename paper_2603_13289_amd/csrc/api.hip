@@ -294,6 +294,7 @@ struct Workspace {
   void* a_last;
   float* attn_part;   // partial attention results when a layer's KV range is split into chunks
   float* gemm_part;   // accumulators of K-split tail tiles of the bf16 GEMMs
+  size_t attn_part_floats;
   size_t bytes;
 };
 
@@ -327,6 +328,7 @@ Workspace carve(void* base, const rc_model_desc& d, int max_rows, int max_pos, i
   w.h_last = (float*)take(sizeof(float) * (size_t)n_req * d.d_model);
   w.a_last = take(es * (size_t)n_req * d.d_model);
   w.attn_part = (float*)take(sizeof(float) * (attn_part_floats > 0 ? attn_part_floats : 1));
+  w.attn_part_floats = attn_part_floats;
   w.gemm_part = (float*)take(d.dtype == RC_BF16 ? gemm_partial_bytes() : 256);
   w.bytes = off;
   return w;
@@ -343,8 +345,13 @@ struct Job {
   void* const* k_pre_pool;
   int capture_layer;              // -1: none
   const int32_t* forced_idx;
+  int selector;                   // rc_selector
+  float tau_dev, tau_inf;
+  int k_suf;
+  const float* s_inf[RC_MAX_REQ];
   float* logits;
   int32_t* sel_idx;
+  int32_t* sel_cnt;
   float* scores_out;
   int max_pos, sum_seg, max_seg;
 };
@@ -396,7 +403,7 @@ hipError_t gemm_qkv_any<bf16>(const bf16* a, const bf16* wq, int nq, const bf16*
 }
 
 template <typename T>
-rc_status run_job(const Job& job, Workspace& w, hipStream_t st) {
+rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
   const rc_model_desc& d = job.m->d;
   const int n_req = (int)job.rq.size();
   const int D = d.d_model, nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim, F = d.d_ffn;
@@ -417,6 +424,14 @@ rc_status run_job(const Job& job, Workspace& w, hipStream_t st) {
     fill_phase(&tabs[ph], job.rq, ph, cur >= 0 ? &tabs[cur] : nullptr, tile_rows);
     splits[ph] = d.dtype == RC_BF16 ? plan_phase_split(&tabs[ph], n_req, d.n_kv_heads, tile_rows, job.max_pos)
                                     : attention_no_split();
+    if (attention_partial_floats(splits[ph].total_slots, d.n_q_heads) > w.attn_part_floats) {
+      // the plan was made for other row counts than the workspace was sized for: attend unsplit
+      for (int b = 0; b < n_req; ++b) {
+        tabs[ph].r[b].long_tile_start = 1 << 30;
+        tabs[ph].r[b].part_base = 0;
+      }
+      splits[ph] = attention_no_split();
+    }
     RC_LAUNCH(PC_TABLES, launch_upload_table(tabs[ph], w.tables + ph, st));
     uploaded[ph] = true;
     const int nb = cur >= 0 ? 1 - hbuf : hbuf;
@@ -466,8 +481,24 @@ rc_status run_job(const Job& job, Workspace& w, hipStream_t st) {
           const ReqHost& r = job.rq[b];
           if (r.k <= 0) continue;
           const int sb = job.base.r[b].sel_base;
-          if (job.forced_idx) RC_LAUNCH(PC_SELECT, launch_copy_i32(job.forced_idx + sb, job.sel_idx + sb, r.k, st));
+          if (job.selector == RC_SELECT_THRESHOLD)
+            RC_LAUNCH(PC_SELECT, launch_final_select(sc + job.base.r[b].score_base, job.s_inf[b], r.S, job.tau_dev, job.tau_inf,
+                                                     job.k_suf, job.sel_idx + sb, job.sel_cnt + b, st));
+          else if (job.forced_idx) RC_LAUNCH(PC_SELECT, launch_copy_i32(job.forced_idx + sb, job.sel_idx + sb, r.k, st));
           else RC_LAUNCH(PC_SELECT, launch_topk(sc + job.base.r[b].score_base, r.S, r.k, job.sel_idx + sb, st));
+        }
+        if (job.selector == RC_SELECT_THRESHOLD) {
+          // the number of rows of the sparse layers depends on the scores: fetch the counts, then go on
+          int32_t cnt[RC_MAX_REQ];
+          if (hipMemcpyAsync(cnt, job.sel_cnt, sizeof(int32_t) * n_req, hipMemcpyDeviceToHost, st) != hipSuccess ||
+              hipStreamSynchronize(st) != hipSuccess)
+            return RC_E_HIP;
+          for (int b = 0; b < n_req; ++b) {
+            if (job.rq[b].k <= 0) continue;
+            const int c = std::min(std::max(cnt[b], 0), job.rq[b].S);
+            job.rq[b].k = c;
+            for (int p = PH_C; p < PH_COUNT; ++p) tabs[p].r[b].k = c;
+          }
         }
       }
       RC_TRY(enter_phase(PH_C));
@@ -518,8 +549,16 @@ rc_status prepare_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req
   if (!(0 <= plan->l_start && plan->l_start < plan->l_det && plan->l_det <= plan->l_end &&
         plan->l_end < d.n_layers))
     return RC_E_INVALID_ARG;
-  if (!plan->k_per_req) return RC_E_INVALID_ARG;
+  const bool by_threshold = plan->selector == RC_SELECT_THRESHOLD;
+  if (plan->selector != RC_SELECT_BUDGET && !by_threshold) return RC_E_INVALID_ARG;
+  if (!by_threshold && !plan->k_per_req) return RC_E_INVALID_ARG;
+  if (by_threshold && (plan->forced_idx || plan->k_suf < 0 || !(plan->tau_dev >= 0.f) || !(plan->tau_inf >= 0.f)))
+    return RC_E_INVALID_ARG;
   job->m = m;
+  job->selector = plan->selector;
+  job->tau_dev = plan->tau_dev;
+  job->tau_inf = plan->tau_inf;
+  job->k_suf = plan->k_suf;
   job->l_start = plan->l_start;
   job->l_det = plan->l_det;
   job->l_end = plan->l_end;
@@ -532,14 +571,15 @@ rc_status prepare_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req
   int sel = 0, seg = 0, max_pos = 0, max_seg = 0;
   for (int b = 0; b < n_req; ++b) {
     const rc_request& q = reqs[b];
-    const int k = plan->k_per_req[b];
+    // threshold selector: sized for the worst case (every token selected) until the counts are known
+    const int k = by_threshold ? q.n_seg : plan->k_per_req[b];
     if (q.n_prefix < 0 || q.n_seg < 0 || q.n_suffix < 0) return RC_E_INVALID_ARG;
     if (q.n_prefix + q.n_seg + q.n_suffix < 1) return RC_E_INVALID_ARG;
     if (q.n_prefix > 0 && !q.x_prefix) return RC_E_INVALID_ARG;
     if (q.n_seg > 0 && !q.h_start) return RC_E_INVALID_ARG;
     if (q.n_suffix > 0 && !q.x_suffix) return RC_E_INVALID_ARG;
     if (k < 0 || k > q.n_seg) return RC_E_INVALID_ARG;
-    if (q.s_inf) return RC_E_UNSUPPORTED;
+    job->s_inf[b] = by_threshold ? q.s_inf : nullptr;
     if (q.src_offset < 0 || q.seg_old_start_pos < 0) return RC_E_INVALID_ARG;
     ReqHost h;
     h.P = q.n_prefix; h.S = q.n_seg; h.nsuf = q.n_suffix; h.k = k;
@@ -550,7 +590,7 @@ rc_status prepare_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req
     r.dst_seq = q.dst_seq; r.src_seq = q.src_seq; r.src_offset = q.src_offset;
     r.k_is_pre_rope = q.k_is_pre_rope ? 1 : 0;
     r.rot_delta = q.n_prefix - q.seg_old_start_pos;
-    r.sel_base = sel; r.score_base = seg;
+    r.sel_base = by_threshold ? seg : sel; r.score_base = seg;
     r.x_prefix = q.x_prefix; r.h_start = q.h_start; r.x_suffix = q.x_suffix; r.h_capture = nullptr;
     sel += k; seg += q.n_seg;
     max_pos = std::max(max_pos, q.n_prefix + q.n_seg + q.n_suffix);
@@ -569,10 +609,17 @@ size_t attn_part_need(const Job& job) {
   const int tile_rows = attention_tile_rows(d.dtype, d.n_q_heads, d.n_kv_heads);
   size_t need = 0;
   ReqTable t = job.base;
-  for (int p = 0; p < PH_COUNT; ++p) {
-    fill_phase(&t, job.rq, (Phase)p, nullptr, tile_rows);
-    const AttnSplit sp = plan_phase_split(&t, (int)job.rq.size(), d.n_kv_heads, tile_rows, job.max_pos);
-    need = std::max(need, attention_partial_floats(sp.total_slots, d.n_q_heads));
+  std::vector<ReqHost> rq = job.rq;
+  // threshold selector: the sparse phase's row count is not known yet; size for a ladder of counts
+  // (a plan that still does not fit falls back to unsplit attention when the layers run)
+  const int rungs = job.selector == RC_SELECT_THRESHOLD ? 8 : 1;
+  for (int rung = 0; rung < rungs; ++rung) {
+    for (int p = 0; p < PH_COUNT; ++p) {
+      fill_phase(&t, rq, (Phase)p, nullptr, tile_rows);
+      const AttnSplit sp = plan_phase_split(&t, (int)rq.size(), d.n_kv_heads, tile_rows, job.max_pos);
+      need = std::max(need, attention_partial_floats(sp.total_slots, d.n_q_heads));
+    }
+    for (ReqHost& r : rq) r.k = std::max(r.k / 2, r.k > 0 ? 1 : 0);
   }
   return need;
 }
@@ -676,8 +723,8 @@ size_t rc_reuse_workspace_bytes(const rc_model* m, const rc_request* reqs, int32
 }
 
 rc_status rc_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req, const rc_plan* plan,
-                   const rc_paged_kv* src, const rc_paged_kv* dst, float* logits, int32_t* sel_idx, float* scores,
-                   void* workspace, size_t workspace_bytes, void* stream) {
+                   const rc_paged_kv* src, const rc_paged_kv* dst, float* logits, int32_t* sel_idx, int32_t* sel_cnt,
+                   float* scores, void* workspace, size_t workspace_bytes, void* stream) {
   Job job;
   RC_TRY(prepare_reuse(m, reqs, n_req, plan, &job));
   RC_TRY(check_paged(dst, m->d.n_layers));
@@ -685,6 +732,7 @@ rc_status rc_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req, con
   int sum_k = 0;
   for (const ReqHost& r : job.rq) sum_k += r.k;
   if (sum_k > 0 && !sel_idx) return RC_E_INVALID_ARG;
+  if (sum_k > 0 && job.selector == RC_SELECT_THRESHOLD && !sel_cnt) return RC_E_INVALID_ARG;
   if (job.max_seg > 0) RC_TRY(check_paged(src, m->d.n_layers));
   for (int b = 0; b < n_req; ++b) {
     RC_TRY(check_seq_fits(dst, reqs[b].dst_seq, reqs[b].n_prefix + reqs[b].n_seg + reqs[b].n_suffix));
@@ -697,6 +745,7 @@ rc_status rc_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req, con
   job.dst = dst;
   job.logits = logits;
   job.sel_idx = sel_idx;
+  job.sel_cnt = sel_cnt;
   job.scores_out = scores;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   return m->d.dtype == RC_BF16 ? run_job<bf16>(job, w, st) : run_job<float>(job, w, st);
@@ -710,6 +759,7 @@ static rc_status prepare_prefill(const rc_model* m, const void* const* x, const 
   job->m = m;
   job->l_start = job->l_det = job->l_end = m->d.n_layers;   // every layer is a "before l_start" layer
   job->forced_idx = nullptr;
+  job->selector = RC_SELECT_BUDGET;
   job->rq.clear();
   job->base = ReqTable();
   job->base.n_req = n_req;
@@ -857,6 +907,15 @@ rc_status rc_threshold_select(const float* score, int32_t n, float tau, int32_t*
   if (n < 1 || !score || !idx_out || !count_out) return RC_E_INVALID_ARG;
   if (n > (1 << 20)) return RC_E_CAPACITY;
   RC_HIP(launch_threshold_select(score, n, tau, idx_out, count_out, reinterpret_cast<hipStream_t>(stream)));
+  return RC_OK;
+}
+
+rc_status rc_final_select(const float* s_dev, const float* s_inf, int32_t n, float tau_dev, float tau_inf,
+                          int32_t k_suf, int32_t* idx_out, int32_t* count_out, void* stream) {
+  if (n < 1 || k_suf < 0 || !s_dev || !idx_out || !count_out) return RC_E_INVALID_ARG;
+  if (n > (1 << 20)) return RC_E_CAPACITY;
+  RC_HIP(launch_final_select(s_dev, s_inf, n, tau_dev, tau_inf, k_suf, idx_out, count_out,
+                             reinterpret_cast<hipStream_t>(stream)));
   return RC_OK;
 }
 

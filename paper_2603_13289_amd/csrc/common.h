@@ -223,6 +223,8 @@ hipError_t launch_vdev_score(const T* v_fresh, int fresh_row_stride, const T* v_
 hipError_t launch_topk(const float* score, int n, int k, int* idx_out, hipStream_t st);
 hipError_t launch_threshold_select(const float* score, int n, float tau, int* idx_out, int* count_out,
                                    hipStream_t st);
+hipError_t launch_final_select(const float* s_dev, const float* s_inf, int n, float tau_dev, float tau_inf, int k_suf,
+                               int* idx_out, int* count_out, hipStream_t st);
 hipError_t launch_copy_i32(const int* src, int* dst, int n, hipStream_t st);
 
 template <typename T>

@@ -141,6 +141,58 @@ threshold_select_kernel(const float* __restrict__ score, int n, float tau, int* 
   if (threadIdx.x == 0) *count_out = total;
 }
 
+// Eq. (5)-(10) in one pass: I_dev (deviation >= tau_dev * mean) united with I_inf-score (influence >=
+// tau_inf * mean, when influence scores are given) and the last k_suf tokens; ascending; count out.
+// Means are accumulated in double in a fixed order, comparisons are made in double.
+__global__ void __launch_bounds__(kSelThreads)
+final_select_kernel(const float* __restrict__ s_dev, const float* __restrict__ s_inf, int n, float tau_dev,
+                    float tau_inf, int k_suf, int* __restrict__ idx_out, int* __restrict__ count_out) {
+  __shared__ double part[2][kSelWaves];
+  __shared__ int scan_lds[kSelWaves + 1];
+  __shared__ double s_thr[2];
+  double a = 0.0, b = 0.0;
+  for (int i = threadIdx.x; i < n; i += kSelThreads) {
+    a += (double)s_dev[i];
+    if (s_inf) b += (double)s_inf[i];
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    a += __shfl_xor(a, o, 64);
+    b += __shfl_xor(b, o, 64);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    part[0][threadIdx.x >> 6] = a;
+    part[1][threadIdx.x >> 6] = b;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double sa = 0.0, sb = 0.0;
+    for (int i = 0; i < kSelWaves; ++i) { sa += part[0][i]; sb += part[1][i]; }
+    s_thr[0] = (double)tau_dev * (sa / (double)n);
+    s_thr[1] = (double)tau_inf * (sb / (double)n);
+  }
+  __syncthreads();
+  const double thr_dev = s_thr[0], thr_inf = s_thr[1];
+  const int chunk = (n + kSelThreads - 1) / kSelThreads;
+  const int lo = min(threadIdx.x * chunk, n), hi = min(lo + chunk, n);
+  auto chosen = [&](int i) {
+    return (double)s_dev[i] >= thr_dev || (s_inf && (double)s_inf[i] >= thr_inf) || i >= n - k_suf;
+  };
+  int cnt = 0;
+  for (int i = lo; i < hi; ++i) cnt += chosen(i);
+  int total;
+  int out = block_exclusive_scan(cnt, scan_lds, &total);
+  for (int i = lo; i < hi; ++i)
+    if (chosen(i)) idx_out[out++] = i;
+  if (threadIdx.x == 0) *count_out = total;
+}
+
+hipError_t launch_final_select(const float* s_dev, const float* s_inf, int n, float tau_dev, float tau_inf, int k_suf,
+                               int* idx_out, int* count_out, hipStream_t st) {
+  final_select_kernel<<<1, kSelThreads, 0, st>>>(s_dev, s_inf, n, tau_dev, tau_inf, k_suf, idx_out, count_out);
+  return hipGetLastError();
+}
+
 hipError_t launch_threshold_select(const float* score, int n, float tau, int* idx_out, int* count_out,
                                    hipStream_t st) {
   threshold_select_kernel<<<1, kSelThreads, 0, st>>>(score, n, tau, idx_out, count_out);

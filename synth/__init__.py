@@ -11,6 +11,7 @@ from .workloads import (  # noqa: F401
     budget_to_k,
     make_weights,
     make_hidden,
+    make_influence,
     make_block_table,
     ragged_lengths,
     round_to_bf16,

@@ -167,6 +167,13 @@ def make_hidden(w: Workload, tensor: str, n_tokens: int, req: int = 0, seed: int
     return _finish(g.standard_normal((n_tokens, w.shape.d_model), dtype=np.float32), w.shape.dtype)
 
 
+def make_influence(w: Workload, n_tokens: int, req: int = 0, seed: int = MASTER_SEED) -> np.ndarray:
+    """Stand-in for the per-token attention mass an earlier agent accumulated while decoding
+    (the input of the influence criterion): positive, heavy-tailed (log-normal), float32."""
+    g = stream_rng(w.name, f"s_inf#{req}", -1, seed)
+    return np.exp(g.standard_normal(n_tokens)).astype(np.float32)
+
+
 def ragged_lengths(w: Workload, seed: int = MASTER_SEED) -> List[Tuple[int, int, int]]:
     """(P_i, S_i, alt_i) per request; fixed sizes for single-request workloads."""
     if w.n_req == 1 and w.prefix_range == (0, 0):

@@ -81,11 +81,18 @@ def build_case(name: str, k_override: Optional[int] = None, pre_rope: bool = Tru
     return Case(w, weights, om, reqs)
 
 
-def oracle_relay(case: Case, b: int = 0, forced_idx=None) -> R.RelayResult:
+def oracle_relay(case: Case, b: int = 0, forced_idx=None, thresholds=None, s_inf=None) -> R.RelayResult:
     rq = case.reqs[b]
     w = case.w
     return R.relay_prefill(case.om, rq.xp, rq.seg, w.l_start, w.l_det, w.l_end, rq.k, x_suffix=rq.xsuf,
-                           forced_idx=forced_idx)
+                           forced_idx=forced_idx, thresholds=thresholds, s_inf=s_inf)
+
+
+def threshold_margin(score: np.ndarray, tau: float) -> float:
+    """Smallest relative distance of a score from the cut tau * mean(score) of Eq. (5) / Eq. (7)."""
+    score = np.asarray(score, np.float64)
+    cut = tau * float(np.mean(score))
+    return float(np.min(np.abs(score - cut)) / max(abs(cut), 1e-300))
 
 
 def selection_margin(score: np.ndarray, k: int) -> float:
@@ -106,7 +113,9 @@ class HipRun:
     scores: List[np.ndarray]
 
 
-def hip_relay(case: Case, forced: Optional[List[np.ndarray]] = None, paged_src: bool = True) -> HipRun:
+def hip_relay(case: Case, forced: Optional[List[np.ndarray]] = None, paged_src: bool = True,
+              thresholds=None, s_inf: Optional[List[Optional[np.ndarray]]] = None) -> HipRun:
+    """thresholds = (tau_dev, tau_inf, k_suf) runs the selector of Eq. (5)-(10) instead of the budget."""
     from paper_2603_13289_amd import binding as rc
     w, sh = case.w, case.w.shape
     dt = rc.rc_dtype_of(sh.dtype)
@@ -136,24 +145,37 @@ def hip_relay(case: Case, forced: Optional[List[np.ndarray]] = None, paged_src: 
             src.write("v", l, b, up(r.seg.v[l]), start=r.A)
         reqs.append(rc.Request(up(r.xp) if r.P else None, up(r.seg.h_start), None if r.xsuf is None else up(r.xsuf),
                                src_seq=b, src_offset=r.A, k_is_pre_rope=r.seg.k_is_pre_rope,
-                               seg_old_start_pos=r.seg.old_start_pos, dst_seq=b))
+                               seg_old_start_pos=r.seg.old_start_pos, dst_seq=b,
+                               s_inf=None if s_inf is None or s_inf[b] is None else
+                               torch.from_numpy(np.ascontiguousarray(s_inf[b], np.float32)).to(dev)))
     ks = [r.k for r in case.reqs]
     fidx = None
     if forced is not None:
         fidx = torch.from_numpy(np.concatenate([np.asarray(f, np.int32) for f in forced])).to(dev)
-    plan = rc.Plan(w.l_start, w.l_det, w.l_end, ks, fidx)
+    sum_seg = sum(r.S for r in case.reqs)
+    cnt = None
+    if thresholds is None:
+        plan = rc.Plan(w.l_start, w.l_det, w.l_end, ks, fidx)
+    else:
+        plan = rc.Plan(w.l_start, w.l_det, w.l_end, None, None, rc.RC_SELECT_THRESHOLD, float(thresholds[0]),
+                       float(thresholds[1]), int(thresholds[2]))
+        cnt = torch.full((n_req,), -1, dtype=torch.int32, device=dev)
     ws = rc.alloc_workspace(rc.rc_reuse_workspace_bytes(model, reqs, plan))
     logits = torch.zeros((n_req, sh.vocab), dtype=torch.float32, device=dev)
-    sel = torch.full((max(sum(ks), 1),), -1, dtype=torch.int32, device=dev)
-    scores = torch.full((sum(r.S for r in case.reqs),), -5.0, dtype=torch.float32, device=dev)
-    rc.rc_reuse(model, reqs, plan, src, dst, logits, sel, scores, ws)
+    sel = torch.full((max(sum(ks) if thresholds is None else sum_seg, 1),), -1, dtype=torch.int32, device=dev)
+    scores = torch.full((sum_seg,), -5.0, dtype=torch.float32, device=dev)
+    rc.rc_reuse(model, reqs, plan, src, dst, logits, sel, scores, ws, sel_cnt=cnt)
     torch.cuda.synchronize()
+    cnt_h = None if cnt is None else cnt.cpu().numpy()
     out_k, out_v, out_sel, out_sc = [], [], [], []
     so = ko = 0
     for b, r in enumerate(case.reqs):
         out_k.append([to_np(dst.read("k", l, b, dst_lens[b])) for l in range(sh.n_layers)])
         out_v.append([to_np(dst.read("v", l, b, dst_lens[b])) for l in range(sh.n_layers)])
-        out_sel.append(sel[ko:ko + r.k].cpu().numpy())
+        if cnt_h is None:
+            out_sel.append(sel[ko:ko + r.k].cpu().numpy())
+        else:
+            out_sel.append(sel[so:so + max(int(cnt_h[b]), 0)].cpu().numpy())
         out_sc.append(scores[so:so + r.S].cpu().numpy())
         ko += r.k
         so += r.S

@@ -88,6 +88,16 @@ def test_reuse_argument_errors_are_reported_before_any_launch():
     assert status(lambda: call([_req()], ok_plan, workspace=torch.zeros(256, dtype=torch.uint8))) == rc.RC_E_WORKSPACE
     assert status(lambda: call([_req()], ok_plan, logits_=None)) == rc.RC_E_INVALID_ARG
     assert status(lambda: call([_req()], ok_plan, src=None)) == rc.RC_E_INVALID_ARG
+    # threshold selector: no forced indices, no negative suffix count or cut, a count output is required
+    thr = lambda **kw: rc.Plan(0, 1, 2, None, None, rc.RC_SELECT_THRESHOLD, **kw)
+    assert rc.rc_reuse_workspace_bytes(m, [_req()], thr()) >= rc.rc_reuse_workspace_bytes(m, [_req()], ok_plan)
+    assert status(lambda: call([_req()], thr(k_suf=-1))) == rc.RC_E_INVALID_ARG
+    assert status(lambda: call([_req()], thr(tau_dev=-0.5))) == rc.RC_E_INVALID_ARG
+    assert status(lambda: call([_req()], thr(tau_inf=float("nan")))) == rc.RC_E_INVALID_ARG
+    assert status(lambda: call([_req()], rc.Plan(0, 1, 2, None, sel, rc.RC_SELECT_THRESHOLD))) == rc.RC_E_INVALID_ARG
+    assert status(lambda: call([_req()], thr())) == rc.RC_E_INVALID_ARG                      # sel_cnt missing
+    assert status(lambda: call([_req()], rc.Plan(0, 1, 2, [2], None, 7))) == rc.RC_E_INVALID_ARG   # unknown selector
+    assert status(lambda: call([_req()], rc.Plan(0, 1, 2, None))) == rc.RC_E_INVALID_ARG     # budget without counts
     m.close()
 
 

@@ -3,7 +3,9 @@ import numpy as np
 import pytest
 
 from oracle import relay_oracle as R
-from tests.harness import (TOL, build_case, hip_full_prefill, hip_relay, oracle_relay, rel_err, selection_margin)
+from synth import make_influence
+from tests.harness import (TOL, build_case, hip_full_prefill, hip_relay, oracle_relay, rel_err, selection_margin,
+                           threshold_margin)
 
 pytestmark = pytest.mark.gpu
 
@@ -112,6 +114,58 @@ def test_f32_all_phases_and_edge_shapes(name, k, n_suffix):
     kk = case.reqs[0].k
     exact = kk in (0, case.reqs[0].S) or selection_margin(want.score, kk) > MARGIN
     _check_against_oracle(case, run, [want], TOL["f32"], check_sel=exact)
+
+
+# ------------------------------------------------------------------ the paper's own selector, Eq. (5)-(10)
+def _safe_tau(score, tau):
+    """Nudge tau until no score sits within MARGIN of the cut (the two sides score in different precisions)."""
+    for step in range(40):
+        t = tau * (1.0 + 0.01 * step)
+        if threshold_margin(score, t) > MARGIN:
+            return t
+    raise AssertionError("no threshold with a safe margin")
+
+
+@pytest.mark.parametrize("name,n_suffix,with_inf,k_suf", [("tiny_f32", 0, True, 10), ("tiny5_f32", 0, False, 0),
+                                                          ("tiny5_f32", 4, True, 10), ("tiny_f32_paged", 0, True, 3),
+                                                          ("tiny5_f32_one", 0, False, 10)])
+def test_f32_threshold_selector_matches_oracle(name, n_suffix, with_inf, k_suf):
+    case = build_case(name, n_suffix=n_suffix)
+    S = case.reqs[0].S
+    s_inf = make_influence(case.w, S) if with_inf else None
+    probe = oracle_relay(case, thresholds=(1.5, 1.45, k_suf), s_inf=s_inf)     # scores do not depend on the cut
+    tau_dev = _safe_tau(probe.score, 1.5)
+    tau_inf = _safe_tau(s_inf, 1.45) if with_inf else 1.45
+    want = oracle_relay(case, thresholds=(tau_dev, tau_inf, k_suf), s_inf=s_inf)
+    run = hip_relay(case, thresholds=(tau_dev, tau_inf, k_suf), s_inf=[s_inf])
+    assert 0 < len(want.sel_idx) <= S
+    _check_against_oracle(case, run, [want], TOL["f32"])
+
+
+def test_f32_threshold_selector_nobody_selected():
+    """Cuts no score reaches and no suffix rule: the sparse layers only carry the last token."""
+    case = build_case("tiny5_f32")
+    want = oracle_relay(case, thresholds=(1e6, 1e6, 0))
+    run = hip_relay(case, thresholds=(1e6, 1e6, 0))
+    assert want.sel_idx.size == 0 and run.sel[0].size == 0
+    _check_against_oracle(case, run, [want], TOL["f32"])
+
+
+def test_bf16_threshold_selector_ragged_batch():
+    """bf16, three ragged requests, paged: counts and indices equal the oracle's selector applied to the
+    library's own scores (bit-exact), and the corrected cache equals the oracle forced onto those indices."""
+    case = build_case("small_bf16_ragged")
+    s_inf = [make_influence(case.w, r.S, b) for b, r in enumerate(case.reqs)]
+    th = (1.5, 1.45, 10)
+    run = hip_relay(case, thresholds=th, s_inf=s_inf)
+    wants = []
+    for b, r in enumerate(case.reqs):
+        sel = R.final_selection(run.scores[b], s_inf[b], *th)
+        assert np.array_equal(run.sel[b], sel)
+        assert 10 <= len(sel) < r.S
+        r.k = len(sel)
+        wants.append(oracle_relay(case, b, forced_idx=sel))
+    _check_against_oracle(case, run, wants, TOL["bf16"], check_sel=False)
 
 
 # ------------------------------------------------------------------ bf16 configurations

@@ -157,6 +157,26 @@ def test_threshold_select(n):
         assert np.array_equal(idx.cpu().numpy()[:c], want)
 
 
+@pytest.mark.parametrize("n", [1, 7, 1000, 33333])
+def test_final_select(n):
+    rc = _rc()
+    g = stream_rng("stage", f"fin{n}")
+    s_dev = (g.random(n, dtype=np.float32) ** 4).astype(np.float32)
+    s_inf = np.exp(g.standard_normal(n)).astype(np.float32)
+    for tau_dev, tau_inf, k_suf, use_inf in ((1.5, 1.45, 10, True), (1.5, 1.45, 0, False), (50.0, 50.0, 0, True),
+                                             (1.0, 1.0, n + 5, True), (2.0, 0.5, 3, True)):
+        idx = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+        cnt = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+        rc.rc_final_select(torch.from_numpy(s_dev).cuda(), torch.from_numpy(s_inf).cuda() if use_inf else None, n,
+                           tau_dev, tau_inf, k_suf, idx, cnt)
+        torch.cuda.synchronize()
+        want = R.final_selection(s_dev.astype(np.float64), s_inf.astype(np.float64) if use_inf else None,
+                                 float(np.float32(tau_dev)), float(np.float32(tau_inf)), k_suf)
+        c = int(cnt.item())
+        assert c == len(want)
+        assert np.array_equal(idx.cpu().numpy()[:c], want)
+
+
 # ------------------------------------------------------------------ K6
 @pytest.mark.parametrize("dtype,hq,hkv,dh", [("f32", 4, 2, 64), ("bf16", 8, 2, 128), ("bf16", 10, 2, 128),
                                               ("bf16", 4, 4, 128), ("f32", 2, 1, 128)])

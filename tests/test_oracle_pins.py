@@ -293,6 +293,37 @@ def test_zero_budget_is_pure_reuse(pre_rope):
     assert got2.active_rows == [P, P + 1, P + 1, P + 1]
 
 
+def test_threshold_selector_reduces_to_forced_indices():
+    """Eq. (5)-(10) inside the prefill: whatever set the selector yields, the pass equals the budget pass
+    forced onto that same set (which the scalar reference pins), and the set is the hand-checkable one."""
+    m, xp, xs, seg, _ = _setup()
+    S = xs.shape[0]
+    # suffix rule alone: cuts nobody can reach, last 3 tokens
+    a = R.relay_prefill(m, xp, seg, 1, 2, 3, 0, thresholds=(1e9, 1e9, 3))
+    assert a.sel_idx.tolist() == [S - 3, S - 2, S - 1]
+    b = R.relay_prefill(m, xp, seg, 1, 2, 3, 3, forced_idx=[S - 3, S - 2, S - 1])
+    assert np.array_equal(a.k_cache, b.k_cache) and np.array_equal(a.logits, b.logits)
+    assert a.active_rows == b.active_rows and np.array_equal(a.score, b.score)
+    # everything selected == full budget
+    c = R.relay_prefill(m, xp, seg, 1, 2, 3, 0, thresholds=(1e9, 1e9, S))
+    d = R.relay_prefill(m, xp, seg, 1, 2, 3, S)
+    assert c.sel_idx.tolist() == list(range(S)) and np.array_equal(c.v_cache, d.v_cache)
+    # influence alone: a spike at tokens 2 and 5 (mean 12/17, cut 1.45 * mean ~ 1.02), no suffix rule
+    s_inf = np.zeros(S)
+    s_inf[[2, 5]] = 6.0
+    e = R.relay_prefill(m, xp, seg, 1, 2, 3, 0, thresholds=(1e9, 1.45, 0), s_inf=s_inf)
+    assert e.sel_idx.tolist() == [2, 5]
+    f = R.relay_prefill(m, xp, seg, 1, 2, 3, 2, forced_idx=[2, 5])
+    assert np.array_equal(e.k_cache, f.k_cache) and np.array_equal(e.logits, f.logits)
+    # deviation rule: the cut is tau * mean of the scores the pass itself computed
+    g = R.relay_prefill(m, xp, seg, 1, 2, 3, 0, thresholds=(1.5, 1.45, 0))
+    want = [j for j in range(S) if g.score[j] >= 1.5 * sum(g.score) / S]
+    assert g.sel_idx.tolist() == want and 0 < len(want) < S
+    # nobody selected: only the logits-carrying last token stays active after the detection layer
+    h = R.relay_prefill(m, xp, seg, 1, 2, 3, 0, thresholds=(1e9, 1e9, 0))
+    assert h.sel_idx.size == 0 and h.active_rows == [9, 9 + S, 9 + 1, 9 + 1]
+
+
 def test_pre_rope_and_delta_rotation_agree():
     m, xp, xs, seg_pre, _ = _setup(pre_rope=True)
     _, _, _, seg_rot, _ = _setup(pre_rope=False)
