@@ -69,11 +69,43 @@ __device__ inline void store_tile(const f32x16 (&acc)[FM][FN], void* __restrict_
   }
 }
 
+// Order in which output tiles are handed to workgroups.  The tile rows are cut into `bands` bands of (almost)
+// equal height; inside a band tiles run row-first (M fastest), bands follow each other.  The 32 workgroups
+// that an XCD runs at a time then cover a block of about 5 x 6 tiles instead of a whole tile column, so
+// fewer distinct A and W slices have to come into that XCD's L2 per K step.
+struct TileOrder { int tiles_m, tiles_n, bands; };
+
+__device__ __host__ inline void tile_of(TileOrder o, int logical, int* tile_m, int* tile_n) {
+  const int base = o.tiles_m / o.bands, rem = o.tiles_m % o.bands;
+  const int cut = rem * (base + 1) * o.tiles_n;   // tiles in the taller bands
+  int h, m_start, r;
+  if (logical < cut) {
+    h = base + 1;
+    const int per = h * o.tiles_n;
+    m_start = (logical / per) * h;
+    r = logical % per;
+  } else {
+    h = base;
+    const int per = h * o.tiles_n;
+    const int l2 = logical - cut;
+    m_start = rem * (base + 1) + (l2 / per) * h;
+    r = l2 % per;
+  }
+  *tile_m = m_start + r % h;
+  *tile_n = r / h;
+}
+
+static inline TileOrder make_tile_order(int tiles_m, int tiles_n) {
+  TileOrder o = {tiles_m, tiles_n, (tiles_m + 5) / 6};
+  if (o.bands < 1) o.bands = 1;
+  return o;
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool DUAL, int OCC>
 __global__ void __launch_bounds__(WAVES_M * WAVES_N * 64, OCC)
 gemm_mfma_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const bf16* __restrict__ w2,
                  const bf16* __restrict__ w3, int ns1, int ns2, void* __restrict__ c, int m, int n, int k, int ldc,
-                 int epi, int tiles_m, int total_tiles, int per_xcd) {
+                 int epi, TileOrder order, int total_tiles, int per_xcd) {
   constexpr int NT = WAVES_M * WAVES_N * 64;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   constexpr int FM = WTM / 32, FN = WTN / 32;
@@ -87,7 +119,8 @@ gemm_mfma_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const b
 
   const int logical = per_xcd > 0 ? (int)(blockIdx.x % XCDS) * per_xcd + (int)(blockIdx.x / XCDS) : (int)blockIdx.x;
   if (logical >= total_tiles) return;
-  const int tile_m = logical % tiles_m, tile_n = logical / tiles_m;
+  int tile_m, tile_n;
+  tile_of(order, logical, &tile_m, &tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN_OUT;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -199,7 +232,7 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, bool DUAL, int OCC>
 __global__ void __launch_bounds__(WAVES_M * WAVES_N * 64, OCC)
 gemm_mfma_dl_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const bf16* __restrict__ w2,
                     const bf16* __restrict__ w3, int ns1, int ns2, void* __restrict__ c, int m, int n, int k, int ldc,
-                    int epi, int tiles_m, int full_tiles, int per_xcd, int n_full_wgs, int split, int ksteps_per_part,
+                    int epi, TileOrder order, int full_tiles, int per_xcd, int n_full_wgs, int split, int ksteps_per_part,
                     float* __restrict__ partial) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -227,7 +260,8 @@ gemm_mfma_dl_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, cons
     k_begin = (j % split) * ksteps_per_part * BK;
     k_end = min(k, k_begin + ksteps_per_part * BK);
   }
-  const int tile_m = logical % tiles_m, tile_n = logical / tiles_m;
+  int tile_m, tile_n;
+  tile_of(order, logical, &tile_m, &tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN_OUT;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -289,34 +323,53 @@ gemm_mfma_dl_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, cons
   }
   const int khalf = lane >> 5;
 
-  if (k_begin < k_end) issue(k_begin, 0);
+  // Pipeline: the loads of step t+1 are issued while step t is multiplied.  The barrier that frees buffer
+  // t%2 and publishes buffer (t+1)%2 sits before the last sub-step's MFMAs of step t, and the first
+  // fragments of step t+1 are fetched from LDS right after it, so that both the barrier and the LDS
+  // latency are covered by that last group of MFMAs.
+  bf16x8 fa[2][FM], fb[2][FN];
+  auto load_frags = [&](int b, int s, int r) {
+    const uint4* la = reinterpret_cast<const uint4*>(lds + b * TILE_BYTES);
+    const uint4* lb = reinterpret_cast<const uint4*>(lds + b * TILE_BYTES + BM * 128);
+    const int chunk = 2 * s + khalf;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) fa[r][i] = __builtin_bit_cast(bf16x8, la[arow[i] * 8 + (chunk ^ ((arow[i] >> 1) & 7))]);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) fb[r][j] = __builtin_bit_cast(bf16x8, lb[brow[j] * 8 + (chunk ^ ((brow[j] >> 1) & 7))]);
+  };
+  auto multiply = [&](int r) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[r][i], fb[r][j], acc[i][j], 0, 0, 0);
+  };
+  constexpr int SUB = BK / 16;
+  static_assert(SUB % 2 == 0, "fragment double buffering assumes an even number of sub-steps");
+  if (k_begin < k_end) {
+    issue(k_begin, 0);
+    if (k_begin + BK < k_end) issue(k_begin + BK, 1);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    load_frags(0, 0, 0);
+  }
   int buf = 0;
   for (int k0 = k_begin; k0 < k_end; k0 += BK) {
-    __builtin_amdgcn_s_waitcnt(0);   // my own direct loads of this step have landed
-    __syncthreads();                 // ... and everyone else's; the other buffer is free again
-    if (k0 + BK < k_end) issue(k0 + BK, buf ^ 1);
-    const uint4* la = reinterpret_cast<const uint4*>(lds + buf * TILE_BYTES);
-    const uint4* lb = reinterpret_cast<const uint4*>(lds + buf * TILE_BYTES + BM * 128);
-    // operands of K sub-step s+1 are fetched from LDS while sub-step s is multiplied
-    bf16x8 fa[2][FM], fb[2][FN];
-    auto load_frags = [&](int s, int r) {
-      const int chunk = 2 * s + khalf;
 #pragma unroll
-      for (int i = 0; i < FM; ++i) fa[r][i] = __builtin_bit_cast(bf16x8, la[arow[i] * 8 + (chunk ^ ((arow[i] >> 1) & 7))]);
-#pragma unroll
-      for (int j = 0; j < FN; ++j) fb[r][j] = __builtin_bit_cast(bf16x8, lb[brow[j] * 8 + (chunk ^ ((brow[j] >> 1) & 7))]);
-    };
-    load_frags(0, 0);
-#pragma unroll
-    for (int s = 0; s < BK / 16; ++s) {
-      if (s + 1 < BK / 16) load_frags(s + 1, (s + 1) & 1);
+    for (int s = 0; s + 1 < SUB; ++s) {
+      load_frags(buf, s + 1, (s + 1) & 1);
       __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of this sub-step's MFMAs
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1][i], fb[s & 1][j], acc[i][j], 0, 0, 0);
+      multiply(s & 1);
+      __builtin_amdgcn_sched_barrier(0);
     }
+    // last sub-step's operands are being read; once they are in registers nobody needs buffer `buf` any more
+    __builtin_amdgcn_s_waitcnt(0);   // my LDS reads and my direct loads of the next step are complete
+    __syncthreads();
+    if (k0 + 2 * BK < k_end) issue(k0 + 2 * BK, buf);
+    if (k0 + BK < k_end) load_frags(buf ^ 1, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply((SUB - 1) & 1);
+    __builtin_amdgcn_sched_barrier(0);
     buf ^= 1;
   }
 
@@ -340,7 +393,7 @@ gemm_mfma_dl_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, cons
 // (wavefront, lane) as thread t of the GEMM kernel, so all reads of a part are coalesced.
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool DUAL>
 __global__ void __launch_bounds__(WAVES_M * WAVES_N * 64)
-gemm_fixup_kernel(void* __restrict__ c, int m, int n, int ldc, int epi, int tiles_m, int full_tiles, int split,
+gemm_fixup_kernel(void* __restrict__ c, int m, int n, int ldc, int epi, TileOrder order, int full_tiles, int split,
                   const float* __restrict__ partial) {
   constexpr int NW = WAVES_M * WAVES_N, NT = NW * 64;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -354,7 +407,8 @@ gemm_fixup_kernel(void* __restrict__ c, int m, int n, int ldc, int epi, int tile
   const int e4 = rest % 4; rest /= 4;
   const int j = rest % FN_OUT, i = rest / FN_OUT;
   const int logical = full_tiles + t;
-  const int tile_m = logical % tiles_m, tile_n = logical / tiles_m;
+  int tile_m, tile_n;
+  tile_of(order, logical, &tile_m, &tile_n);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   float g[4] = {0.f, 0.f, 0.f, 0.f}, u[4] = {0.f, 0.f, 0.f, 0.f};
@@ -449,21 +503,21 @@ static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const 
     static bool attr_set = false;
     if (!attr_set) { e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes); attr_set = true; }
     if (e != hipSuccess) return e;
-    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, tiles_m, full_tiles, per_xcd,
+    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, make_tile_order(tiles_m, tiles_n), full_tiles, per_xcd,
                                       n_full_wgs, split, kpp, partial);
     if (rem_tiles > 0)
       gemm_fixup_kernel<BM, BN, WAVES_M, WAVES_N, true><<<rem_tiles * (BM / WAVES_M / 32) * (BN / WAVES_N / 64) * 4, NT, 0, st>>>(
-          c, m, n, ldc, (int)epi, tiles_m, full_tiles, split, partial);
+          c, m, n, ldc, (int)epi, make_tile_order(tiles_m, tiles_n), full_tiles, split, partial);
   } else {
     auto kern = gemm_mfma_dl_kernel<BM, BN, WAVES_M, WAVES_N, false, OCC>;
     static bool attr_set = false;
     if (!attr_set) { e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes); attr_set = true; }
     if (e != hipSuccess) return e;
-    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, tiles_m, full_tiles, per_xcd,
+    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, make_tile_order(tiles_m, tiles_n), full_tiles, per_xcd,
                                       n_full_wgs, split, kpp, partial);
     if (rem_tiles > 0)
       gemm_fixup_kernel<BM, BN, WAVES_M, WAVES_N, false><<<rem_tiles * (BM / WAVES_M / 32) * (BN / WAVES_N / 32) * 4, NT, 0, st>>>(
-          c, m, n, ldc, (int)epi, tiles_m, full_tiles, split, partial);
+          c, m, n, ldc, (int)epi, make_tile_order(tiles_m, tiles_n), full_tiles, split, partial);
   }
   return hipGetLastError();
 }
@@ -484,10 +538,10 @@ static hipError_t launch_cfg(const bf16* a, const bf16* w, const bf16* w2, const
   constexpr int NT = WAVES_M * WAVES_N * 64;
   if (dual)
     gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, true, OCC><<<grid, NT, 0, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc,
-                                                                              (int)epi, tiles_m, total, per_xcd);
+                                                                              (int)epi, make_tile_order(tiles_m, tiles_n), total, per_xcd);
   else
     gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, false, OCC><<<grid, NT, 0, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc,
-                                                                               (int)epi, tiles_m, total, per_xcd);
+                                                                               (int)epi, make_tile_order(tiles_m, tiles_n), total, per_xcd);
   return hipGetLastError();
 }
 
