@@ -226,6 +226,51 @@ def decode_record(m: OracleModel, x_alt: np.ndarray, x_seg: np.ndarray, l_start:
                          r.h_in[l_start][n_alt:].copy(), k_is_pre_rope, n_alt)
 
 
+def decode_step(m: OracleModel, x_new: np.ndarray, pos: int, k_cache: np.ndarray, v_cache: np.ndarray,
+                k_pre_rope: Optional[np.ndarray] = None, capture_layer: int = -1,
+                s_inf: Optional[np.ndarray] = None):
+    """One decoding step of the earlier agent with the cache manager's bookkeeping
+    (Figure "Overview", item 2; Eq. 6).
+
+    The token x_new[d] sits at position `pos`; k_cache / v_cache [L][cap][Hkv][dh]
+    already hold rows 0..pos-1 and receive row `pos`.  Optionally stores the key
+    before rotation in k_pre_rope[l][pos], returns the hidden state entering
+    `capture_layer`, and adds to s_inf[j], j = 0..pos, the attention weight this
+    step's query puts on position j, summed over all layers and query heads
+    (the token's weight on itself included).
+    Returns (logits[vocab], h_captured[d] or None).
+    """
+    h = np.asarray(x_new, F64).reshape(1, m.d_model)
+    g = m.n_q_heads // m.n_kv_heads
+    captured = None
+    for l in range(m.n_layers):
+        w = m.layers[l]
+        if l == capture_layer:
+            captured = h[0].copy()
+        a = rmsnorm(h, w["g_attn"], m.rms_eps)
+        q = linear(a, w["wq"]).reshape(1, m.n_q_heads, m.head_dim)
+        k = linear(a, w["wk"]).reshape(1, m.n_kv_heads, m.head_dim)
+        v = linear(a, w["wv"]).reshape(1, m.n_kv_heads, m.head_dim)
+        if k_pre_rope is not None:
+            k_pre_rope[l][pos] = k[0]
+        q = rope_rotate(q, np.array([pos]), m.rope_base)[0]
+        k_cache[l][pos] = rope_rotate(k, np.array([pos]), m.rope_base)[0]
+        v_cache[l][pos] = v[0]
+        o = np.empty((m.n_q_heads, m.head_dim), F64)
+        for i in range(m.n_q_heads):
+            keys = k_cache[l][:pos + 1, i // g, :]
+            sc = np.matmul(keys, q[i]) / np.sqrt(F64(m.head_dim))
+            alpha = np.exp(sc - np.max(sc))
+            alpha = alpha / np.sum(alpha)
+            if s_inf is not None:
+                s_inf[:pos + 1] += alpha
+            o[i] = np.matmul(alpha, v_cache[l][:pos + 1, i // g, :])
+        h = h + linear(o.reshape(1, -1), w["wo"])
+        f = rmsnorm(h, w["g_ffn"], m.rms_eps)
+        h = h + linear(silu(linear(f, w["w_gate"])) * linear(f, w["w_up"]), w["w_down"])
+    return first_token_logits(m, h[0]), captured
+
+
 # --------------------------------------------------------------------------
 # scoring and selection
 # --------------------------------------------------------------------------

@@ -146,3 +146,29 @@ def brute_relay(tm, x_prefix, k_src_pre, v_src, h_start, l_start, l_det, l_end, 
         hid = {t: token_attend(tm, l, hid[t], qs[t], t, kc[l], vc[l]) for t in active}
     logits = _matvec(tm.w_lm, _rms(hid[P + S - 1], tm.g_final, tm.eps))
     return kc, vc, sel, score, logits
+
+
+def brute_decode_influence(tm, x, n_prompt):
+    """Feed x[0..T) one token at a time; for the steps t >= n_prompt (the decoding steps) add every
+    attention weight of the step's token, over all layers and query heads, to s_inf[key position].
+    Returns (s_inf[T], logits of the last step)."""
+    T = len(x)
+    kc = [dict() for _ in range(tm.L)]
+    vc = [dict() for _ in range(tm.L)]
+    s_inf = [0.0] * T
+    h = None
+    dh, g = tm.dh, tm.hq // tm.hkv
+    for t in range(T):
+        h = list(x[t])
+        for l in range(tm.L):
+            q = token_layer(tm, l, h, t, kc[l], vc[l])
+            if t >= n_prompt:
+                for i in range(tm.hq):
+                    qi = _rot(q[i * dh:(i + 1) * dh], t, tm.base)
+                    sc = [sum(a * b for a, b in zip(qi, kc[l][j][i // g])) / math.sqrt(dh) for j in range(t + 1)]
+                    mx = max(sc)
+                    z = sum(math.exp(v - mx) for v in sc)
+                    for j in range(t + 1):
+                        s_inf[j] += math.exp(sc[j] - mx) / z
+            h = token_attend(tm, l, h, q, t, kc[l], vc[l])
+    return s_inf, _matvec(tm.w_lm, _rms(h, tm.g_final, tm.eps))

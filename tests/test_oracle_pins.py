@@ -399,3 +399,47 @@ def test_selected_rows_move_towards_full_prefill():
     assert np.array_equal(some.v_cache[3][P + rest], zero.v_cache[3][P + rest])
     # the dense layer is recomputed for everyone and is exact here
     assert np.allclose(some.v_cache[1], full.v_cache[1][:P + S + 0].tolist() + [some.v_cache[1][-1].tolist()], atol=1e-10)
+
+
+# ----------------------------------------------------------------------------
+# decoding with the cache manager's bookkeeping (Figure "Overview" item 2, Eq. 6)
+# ----------------------------------------------------------------------------
+def test_decode_chain_equals_prefill_and_scalar_influence():
+    w, m = _tiny(n_layers=3, name="dec3")
+    T, n_prompt = 9, 4
+    x = make_hidden(w, "x", T).astype(np.float64)
+    full = R.full_prefill(m, x)
+    pre = R.full_prefill(m, x[:n_prompt])
+    shape = (m.n_layers, T, m.n_kv_heads, m.head_dim)
+    kc, vc, kpre = np.zeros(shape), np.zeros(shape), np.zeros(shape)
+    kc[:, :n_prompt], vc[:, :n_prompt], kpre[:, :n_prompt] = pre.k_cache, pre.v_cache, pre.k_pre_rope
+    s_inf = np.zeros(T)
+    caps = []
+    for t in range(n_prompt, T):
+        logits, cap = R.decode_step(m, x[t], t, kc, vc, k_pre_rope=kpre, capture_layer=1, s_inf=s_inf)
+        caps.append(cap)
+    # token-by-token decoding leaves the same cache, un-rotated keys, captured states and logits as a prefill
+    assert np.allclose(kc, full.k_cache, atol=1e-11) and np.allclose(vc, full.v_cache, atol=1e-11)
+    assert np.allclose(kpre, full.k_pre_rope, atol=1e-11)
+    assert np.allclose(np.array(caps), full.h_in[1][n_prompt:], atol=1e-11)
+    assert np.allclose(logits, full.logits, atol=1e-10)
+    # every (step, layer, head) distributes exactly one unit of attention
+    assert abs(np.sum(s_inf) - (T - n_prompt) * m.n_layers * m.n_q_heads) < 1e-9
+    # a position can only have collected weight from steps at or after it
+    assert s_inf[T - 1] <= m.n_layers * m.n_q_heads + 1e-12 and np.all(s_inf > 0)
+    # scalar reference with explicit loops over steps, layers, heads and keys
+    tm = B.TinyModel(m)
+    want, blogits = B.brute_decode_influence(tm, _nested(x), n_prompt)
+    assert np.allclose(s_inf, want, atol=1e-11)
+    assert np.allclose(logits, blogits, atol=1e-10)
+
+
+def test_decode_first_token_puts_all_weight_on_itself():
+    w, m = _tiny(n_layers=2, name="dec1")
+    x = make_hidden(w, "x", 1).astype(np.float64)
+    shape = (m.n_layers, 1, m.n_kv_heads, m.head_dim)
+    kc, vc = np.zeros(shape), np.zeros(shape)
+    s_inf = np.zeros(1)
+    logits, cap = R.decode_step(m, x[0], 0, kc, vc, s_inf=s_inf)
+    assert s_inf[0] == m.n_layers * m.n_q_heads and cap is None
+    assert np.allclose(logits, R.full_prefill(m, x).logits, atol=1e-12)
