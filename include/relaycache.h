@@ -200,6 +200,31 @@ RC_API rc_status rc_prefill(const rc_model* m, const void* const* x, const int32
                      void* const* k_pre_pool, int32_t capture_layer, void* const* h_capture,
                      float* logits, void* workspace, size_t workspace_bytes, void* stream);
 
+/* One decoding step of the earlier agent with the cache manager's bookkeeping (Figure "Overview", item 2;
+ * Eq. 6): the new token of each of n_req sequences runs through every layer, attending over the rows
+ * its sequence already has in `cache` and itself; its K/V row is appended at position `pos`.
+ * Optionally the step also records what a later selective-recompute prefill needs:
+ *   k_pre_pool  host array [n_layers] of device pools with the cache's geometry that receive the
+ *               key before rotation at the same (seq, pos); NULL to skip
+ *   h_capture   per request, device [d] of T receiving the hidden state entering capture_layer
+ *   s_inf       per request, device float [pos + 1]: s_inf[j] += the attention weight the new token puts
+ *               on position j, summed over all layers and query heads (its weight on itself included).
+ *               The caller zeroes the vector before the first step and keeps passing it; rows of
+ *               the reused segment are a slice of it.
+ *   logits      [n_req][vocab] float: next-token logits.
+ * Errors as rc_prefill; RC_E_CAPACITY if pos + 1 exceeds the sequence's capacity. */
+typedef struct {
+  const void* x;     /* device [d] of T: input hidden state of the new token */
+  int32_t pos;       /* its position = number of rows the sequence already holds */
+  int32_t seq;       /* row of the cache's block table */
+  void* h_capture;   /* optional */
+  float* s_inf;      /* optional */
+} rc_decode_req;
+RC_API size_t rc_decode_workspace_bytes(const rc_model* m, const rc_decode_req* reqs, int32_t n_req);
+RC_API rc_status rc_decode_step(const rc_model* m, const rc_decode_req* reqs, int32_t n_req, const rc_paged_kv* cache,
+                         void* const* k_pre_pool, int32_t capture_layer, float* logits, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
 /* ---------------------------------------------------------------- timing
  * Optional per-stage GPU timing of rc_reuse / rc_prefill (the per-stage latency split the paper
  * reports in its Table "Per-agent TTFT breakdown").  While enabled, every kernel launch of those two

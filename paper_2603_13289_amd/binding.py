@@ -24,7 +24,7 @@ RC_SELECT_BUDGET, RC_SELECT_THRESHOLD = 0, 1
 
 EXPORTS = [
     "rc_status_str", "rc_build_info", "rc_model_create", "rc_model_destroy", "rc_reuse_workspace_bytes",
-    "rc_reuse", "rc_prefill_workspace_bytes", "rc_prefill", "rc_stage_workspace_bytes", "rc_rope_rerotate",
+    "rc_reuse", "rc_prefill_workspace_bytes", "rc_prefill", "rc_decode_workspace_bytes", "rc_decode_step", "rc_stage_workspace_bytes", "rc_rope_rerotate",
     "rc_vdev_score", "rc_topk", "rc_threshold_select", "rc_final_select", "rc_sparse_attention", "rc_gemm_rows",
     "rc_scatter_paged", "rc_profile_enable", "rc_profile_class_count", "rc_profile_class_name", "rc_profile_read",
     "rc_tune_set", "rc_sparse_attention_workspace_bytes",
@@ -67,6 +67,11 @@ class rc_request(C.Structure):
                 ("s_inf", C.c_void_p)]
 
 
+class rc_decode_req(C.Structure):
+    _fields_ = [("x", C.c_void_p), ("pos", C.c_int32), ("seq", C.c_int32), ("h_capture", C.c_void_p),
+                ("s_inf", C.c_void_p)]
+
+
 class rc_plan(C.Structure):
     _fields_ = [("l_start", C.c_int32), ("l_det", C.c_int32), ("l_end", C.c_int32),
                 ("k_per_req", C.POINTER(C.c_int32)), ("forced_idx", C.c_void_p),
@@ -92,6 +97,11 @@ def _load() -> C.CDLL:
     lib.rc_reuse.restype = C.c_int
     lib.rc_reuse.argtypes = [vp, C.POINTER(rc_request), i32, C.POINTER(rc_plan), C.POINTER(rc_paged_kv),
                              C.POINTER(rc_paged_kv), vp, vp, vp, vp, vp, sz, vp]
+    lib.rc_decode_workspace_bytes.restype = sz
+    lib.rc_decode_workspace_bytes.argtypes = [vp, C.POINTER(rc_decode_req), i32]
+    lib.rc_decode_step.restype = C.c_int
+    lib.rc_decode_step.argtypes = [vp, C.POINTER(rc_decode_req), i32, C.POINTER(rc_paged_kv), C.POINTER(vp), i32, vp,
+                                   vp, sz, vp]
     lib.rc_prefill_workspace_bytes.restype = sz
     lib.rc_prefill_workspace_bytes.argtypes = [vp, C.POINTER(i32), i32]
     lib.rc_prefill.restype = C.c_int
@@ -357,6 +367,35 @@ def rc_prefill(model: Model, x: Sequence[torch.Tensor], dst_seq: Sequence[int], 
                         capture_layer, hc, _ptr(logits), _ptr(workspace),
                         workspace.numel() * workspace.element_size(), _stream(stream))
     _check(st, "rc_prefill")
+
+
+@dataclass
+class DecodeReq:
+    x: torch.Tensor                            # [d]
+    pos: int
+    seq: int = 0
+    h_capture: Optional[torch.Tensor] = None   # [d]
+    s_inf: Optional[torch.Tensor] = None       # float32 [>= pos + 1]
+
+
+def _decode_array(reqs: Sequence[DecodeReq]):
+    arr = (rc_decode_req * len(reqs))()
+    for i, r in enumerate(reqs):
+        arr[i] = rc_decode_req(_ptr(r.x), r.pos, r.seq, _ptr(r.h_capture), _ptr(r.s_inf))
+    return arr
+
+
+def rc_decode_workspace_bytes(model: Model, reqs: Sequence[DecodeReq]) -> int:
+    return int(lib.rc_decode_workspace_bytes(model.handle, _decode_array(reqs), len(reqs)))
+
+
+def rc_decode_step(model: Model, reqs: Sequence[DecodeReq], cache: PagedKV, logits: torch.Tensor,
+                   workspace: torch.Tensor, k_pre: Optional[PagedKV] = None, capture_layer: int = -1,
+                   stream=None) -> None:
+    st = lib.rc_decode_step(model.handle, _decode_array(reqs), len(reqs), C.byref(cache.c),
+                            k_pre.c.k_pool if k_pre is not None else None, capture_layer, _ptr(logits),
+                            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "rc_decode_step")
 
 
 def alloc_workspace(n_bytes: int, device="cuda") -> torch.Tensor:

@@ -31,11 +31,11 @@ namespace {
 // ---------------------------------------------------------------- optional per-class GPU timing
 enum ProfClass : int {
   PC_REROTATE = 0, PC_ROWS, PC_RMSNORM, PC_GEMM_QKV, PC_GEMM_O, PC_GEMM_GATE_UP, PC_GEMM_DOWN, PC_GEMM_VFRESH,
-  PC_GEMM_LM_HEAD, PC_ROPE_SCATTER, PC_ATTENTION, PC_SCORE, PC_SELECT, PC_TABLES, PC_COUNT
+  PC_GEMM_LM_HEAD, PC_ROPE_SCATTER, PC_ATTENTION, PC_SCORE, PC_SELECT, PC_TABLES, PC_INFLUENCE, PC_COUNT
 };
 const char* const kProfNames[PC_COUNT] = {"rope_rerotate", "row_bookkeeping", "rmsnorm", "gemm_qkv", "gemm_o",
                                           "gemm_gate_up", "gemm_down", "gemm_vfresh", "gemm_lm_head",
-                                          "rope_scatter", "attention", "vdev_score", "select", "tables"};
+                                          "rope_scatter", "attention", "vdev_score", "select", "tables", "influence"};
 struct ProfRec { int cls; hipEvent_t a, b; };
 struct Profiler {
   bool on = false;
@@ -294,12 +294,13 @@ struct Workspace {
   void* a_last;
   float* attn_part;   // partial attention results when a layer's KV range is split into chunks
   float* gemm_part;   // accumulators of K-split tail tiles of the bf16 GEMMs
+  float* inf_scratch; // attention scores of the decoding rows (influence accumulation)
   size_t attn_part_floats;
   size_t bytes;
 };
 
 Workspace carve(void* base, const rc_model_desc& d, int max_rows, int max_pos, int n_req, int sum_seg,
-                size_t attn_part_floats) {
+                size_t attn_part_floats, size_t inf_floats = 0) {
   Workspace w;
   size_t off = 0;
   char* p = reinterpret_cast<char*>(base);
@@ -330,6 +331,7 @@ Workspace carve(void* base, const rc_model_desc& d, int max_rows, int max_pos, i
   w.attn_part = (float*)take(sizeof(float) * (attn_part_floats > 0 ? attn_part_floats : 1));
   w.attn_part_floats = attn_part_floats;
   w.gemm_part = (float*)take(d.dtype == RC_BF16 ? gemm_partial_bytes() : 256);
+  w.inf_scratch = (float*)take(sizeof(float) * (inf_floats > 0 ? inf_floats : 1));
   w.bytes = off;
   return w;
 }
@@ -354,6 +356,9 @@ struct Job {
   int32_t* sel_cnt;
   float* scores_out;
   int max_pos, sum_seg, max_seg;
+  bool takeover = true;           // false: the segment rows already sit in dst (a decoding step)
+  bool any_inf = false;
+  InfluencePtrs inf;
 };
 
 template <typename T>
@@ -449,7 +454,7 @@ rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
 
     // K1, once: take over the reused rows of every layer (keys to their new positions, values copied).
     // Layers that recompute rows later simply overwrite them.
-    if (l == 0 && has_seg) {
+    if (l == 0 && has_seg && job.takeover) {
       const KvGeom gs = geom_of(*job.src, d);
       RC_LAUNCH(PC_TABLES, launch_delta_table(w.delta_tab, w.tables + cur, n_req, d.head_dim / 2, (double)d.rope_base, st));
       for (int l0 = 0; l0 < d.n_layers; l0 += kRerotateLayers) {
@@ -516,6 +521,10 @@ rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
     RC_LAUNCH(PC_ROPE_SCATTER, launch_rope_scatter<T>(w.qkv, rows, w.row_pos, w.row_req, w.tables + cur, w.rope_tab, (T*)w.q,
                                   (T*)job.dst->k_pool[l], (T*)job.dst->v_pool[l],
                                   job.k_pre_pool ? (T*)job.k_pre_pool[l] : nullptr, gd, d.n_q_heads, st));
+    if (job.any_inf)
+      RC_LAUNCH(PC_INFLUENCE, launch_influence_accumulate<T>((const T*)w.q, w.row_pos, w.row_req, w.tables + cur, rows,
+                                                             (const T*)job.dst->k_pool[l], gd, d.n_q_heads, job.max_pos,
+                                                             job.inf, w.inf_scratch, st));
     RC_LAUNCH(PC_ATTENTION, attention_dispatch<T>((const T*)w.q, w.row_pos, w.row_req, w.tables + cur, rows,
                                  tabs[cur].total_tiles, (const T*)job.dst->k_pool[l],
                                  (const T*)job.dst->v_pool[l], gd, d.n_q_heads, (T*)w.o, splits[cur], w.attn_part, st));
@@ -810,6 +819,84 @@ rc_status rc_prefill(const rc_model* m, const void* const* x, const int32_t* n_t
   job.capture_layer = h_capture ? capture_layer : -1;
   job.logits = logits;
   job.sel_idx = nullptr;
+  job.scores_out = nullptr;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  return m->d.dtype == RC_BF16 ? run_job<bf16>(job, w, st) : run_job<float>(job, w, st);
+}
+
+// ------------------------------------------------------------------ decoding with the cache manager
+static rc_status prepare_decode(const rc_model* m, const rc_decode_req* reqs, int32_t n_req, Job* job) {
+  if (!m || !reqs) return RC_E_INVALID_ARG;
+  if (n_req < 1) return RC_E_INVALID_ARG;
+  if (n_req > RC_MAX_REQ) return RC_E_CAPACITY;
+  job->m = m;
+  job->l_start = job->l_det = job->l_end = m->d.n_layers;   // every layer only runs the new token
+  job->forced_idx = nullptr;
+  job->selector = RC_SELECT_BUDGET;
+  job->takeover = false;
+  job->any_inf = false;
+  job->rq.clear();
+  job->base = ReqTable();
+  job->base.n_req = n_req;
+  int max_pos = 0, max_seg = 0;
+  for (int b = 0; b < n_req; ++b) {
+    const rc_decode_req& q = reqs[b];
+    if (!q.x || q.pos < 0) return RC_E_INVALID_ARG;
+    // the cached rows 0..pos-1 play the part of a reused segment that is already in place; the new token
+    // is the one-row suffix behind it
+    ReqHost h;
+    h.P = 0; h.S = q.pos; h.nsuf = 1; h.k = 0; h.carries_logits = false;
+    job->rq.push_back(h);
+    ReqDev& r = job->base.r[b];
+    r.P = 0; r.S = q.pos; r.nsuf = 1; r.k = 0;
+    r.dst_seq = q.seq; r.src_seq = q.seq;
+    r.x_suffix = q.x;
+    r.h_capture = q.h_capture;
+    job->inf.s_inf[b] = q.s_inf;
+    job->any_inf = job->any_inf || q.s_inf != nullptr;
+    max_pos = std::max(max_pos, q.pos + 1);
+    max_seg = std::max(max_seg, q.pos);
+  }
+  for (int b = n_req; b < RC_MAX_REQ; ++b) job->inf.s_inf[b] = nullptr;
+  job->max_pos = max_pos;
+  job->sum_seg = 0;
+  job->max_seg = max_seg;
+  return RC_OK;
+}
+
+static size_t decode_inf_floats(const Job& job) {
+  return job.any_inf ? influence_scratch_floats((int)job.rq.size(), job.m->d.n_q_heads, job.max_pos) : 0;
+}
+
+size_t rc_decode_workspace_bytes(const rc_model* m, const rc_decode_req* reqs, int32_t n_req) {
+  Job job;
+  if (prepare_decode(m, reqs, n_req, &job) != RC_OK) return 0;
+  return carve(nullptr, m->d, max_rows_of(job), job.max_pos, n_req, 0, attn_part_need(job), decode_inf_floats(job)).bytes;
+}
+
+rc_status rc_decode_step(const rc_model* m, const rc_decode_req* reqs, int32_t n_req, const rc_paged_kv* cache,
+                         void* const* k_pre_pool, int32_t capture_layer, float* logits, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  Job job;
+  RC_TRY(prepare_decode(m, reqs, n_req, &job));
+  RC_TRY(check_paged(cache, m->d.n_layers));
+  if (!logits) return RC_E_INVALID_ARG;
+  bool any_capture = false;
+  for (int b = 0; b < n_req; ++b) {
+    RC_TRY(check_seq_fits(cache, reqs[b].seq, reqs[b].pos + 1));
+    any_capture = any_capture || reqs[b].h_capture != nullptr;
+  }
+  if (any_capture && (capture_layer < 0 || capture_layer >= m->d.n_layers)) return RC_E_INVALID_ARG;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RC_E_WORKSPACE;
+  Workspace w = carve(workspace, m->d, max_rows_of(job), job.max_pos, n_req, 0, attn_part_need(job), decode_inf_floats(job));
+  if (w.bytes > workspace_bytes) return RC_E_WORKSPACE;
+  job.src = nullptr;
+  job.dst = cache;
+  job.k_pre_pool = k_pre_pool;
+  job.capture_layer = any_capture ? capture_layer : -1;
+  job.logits = logits;
+  job.sel_idx = nullptr;
+  job.sel_cnt = nullptr;
   job.scores_out = nullptr;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   return m->d.dtype == RC_BF16 ? run_job<bf16>(job, w, st) : run_job<float>(job, w, st);

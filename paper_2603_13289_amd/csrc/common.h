@@ -223,6 +223,13 @@ hipError_t launch_vdev_score(const T* v_fresh, int fresh_row_stride, const T* v_
 hipError_t launch_topk(const float* score, int n, int k, int* idx_out, hipStream_t st);
 hipError_t launch_threshold_select(const float* score, int n, float tau, int* idx_out, int* count_out,
                                    hipStream_t st);
+// per-request influence vectors (Eq. 6), passed to the accumulation kernel by value; nullptr: not tracked
+struct InfluencePtrs { float* s_inf[RC_MAX_REQ]; };
+size_t influence_scratch_floats(int n_rows, int n_q_heads, int max_len);
+template <typename T>
+hipError_t launch_influence_accumulate(const T* q, const int* row_pos, const int* row_req, const ReqTable* table,
+                                       int n_rows, const T* k_pool, KvGeom g, int n_q_heads, int max_len,
+                                       const InfluencePtrs& out, float* scratch, hipStream_t st);
 hipError_t launch_final_select(const float* s_dev, const float* s_inf, int n, float tau_dev, float tau_inf, int k_suf,
                                int* idx_out, int* count_out, hipStream_t st);
 hipError_t launch_copy_i32(const int* src, int* dst, int n, hipStream_t st);

@@ -1,0 +1,132 @@
+// Influence accumulation of the decode-side cache manager (Eq. 6): for the one query row that a
+// decoding step adds per request, the attention weight it puts on every cached position, summed over
+// the query heads, is added to that request's s_inf vector; the caller adds up layers and steps by
+// calling once per layer and step.
+//
+// Three small memory-bound kernels per layer (K is read once; no float atomics, fixed summation order):
+//   scores   s[row][h][j] = q[row][h] . k[j][h / G] / sqrt(dh)          for j <= pos(row)
+//   norm     m[row][h] = max_j s,  l[row][h] = sum_j exp(s - m)
+//   add      s_inf[req][j] += sum_h exp(s[row][h][j] - m[row][h]) / l[row][h]   (h ascending)
+#include "common.h"
+
+namespace rc {
+
+static constexpr int kInfThreads = 256;
+
+// grid: (key chunks of 256, kv heads, rows); thread = one key position
+template <typename T>
+__global__ void __launch_bounds__(kInfThreads)
+influence_scores_kernel(const T* __restrict__ q, const int* __restrict__ row_pos, const int* __restrict__ row_req,
+                        const ReqTable* __restrict__ table, const T* __restrict__ k_pool, KvGeom g, int n_q_heads,
+                        int max_len, float* __restrict__ scores) {
+  extern __shared__ float q_lds[];   // [G][dh]
+  const int row = blockIdx.z, hk = blockIdx.y;
+  const int G = n_q_heads / g.n_kv_heads, dh = g.head_dim;
+  const int pos = row_pos[row];
+  const int j0 = blockIdx.x * kInfThreads;
+  if (j0 > pos) return;
+  const float scale = rsqrtf((float)dh);
+  for (int i = threadIdx.x; i < G * dh; i += kInfThreads)
+    q_lds[i] = to_f32(q[((size_t)row * n_q_heads + (size_t)hk * G) * dh + i]) * scale;
+  __syncthreads();
+  const int j = j0 + threadIdx.x;
+  if (j > pos) return;
+  const int seq = table->r[row_req[row]].dst_seq;
+  const T* kr = k_pool + kv_row_offset(g, seq, j, hk);
+  constexpr int VEC = Vec16<T>::N;
+  float acc[8];
+#pragma unroll
+  for (int gq = 0; gq < 8; ++gq) acc[gq] = 0.f;
+  for (int c = 0; c < dh; c += VEC) {
+    float kv[VEC];
+    Vec16<T>::load(kr + c, kv);
+#pragma unroll
+    for (int gq = 0; gq < 8; ++gq) {
+      if (gq < G) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[gq] = fmaf(q_lds[gq * dh + c + e], kv[e], acc[gq]);
+      }
+    }
+  }
+#pragma unroll
+  for (int gq = 0; gq < 8; ++gq)
+    if (gq < G) scores[((size_t)row * n_q_heads + (size_t)hk * G + gq) * max_len + j] = acc[gq];
+}
+
+// grid: (query heads, rows)
+__global__ void __launch_bounds__(kInfThreads)
+influence_norm_kernel(const float* __restrict__ scores, const int* __restrict__ row_pos, int n_q_heads, int max_len,
+                      float2* __restrict__ ml) {
+  __shared__ float red[kInfThreads / 64];
+  const int h = blockIdx.x, row = blockIdx.y;
+  const int n = row_pos[row] + 1;
+  const float* s = scores + ((size_t)row * n_q_heads + h) * max_len;
+  float m = -INFINITY;
+  for (int j = threadIdx.x; j < n; j += kInfThreads) m = fmaxf(m, s[j]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  float l = 0.f;
+  for (int j = threadIdx.x; j < n; j += kInfThreads) l += __expf(s[j] - m);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = l;
+  __syncthreads();
+  if (threadIdx.x == 0) ml[(size_t)row * n_q_heads + h] = make_float2(m, ((red[0] + red[1]) + red[2]) + red[3]);
+}
+
+// grid: (key chunks of 256, rows)
+__global__ void __launch_bounds__(kInfThreads)
+influence_add_kernel(const float* __restrict__ scores, const float2* __restrict__ ml, const int* __restrict__ row_pos,
+                     const int* __restrict__ row_req, InfluencePtrs out, int n_q_heads, int max_len) {
+  const int row = blockIdx.y;
+  const int j = blockIdx.x * kInfThreads + threadIdx.x;
+  if (j > row_pos[row]) return;
+  float* dst = out.s_inf[row_req[row]];
+  if (dst == nullptr) return;
+  float acc = 0.f;
+  for (int h = 0; h < n_q_heads; ++h) {
+    const float2 t = ml[(size_t)row * n_q_heads + h];
+    acc += __expf(scores[((size_t)row * n_q_heads + h) * max_len + j] - t.x) / t.y;
+  }
+  dst[j] += acc;
+}
+
+size_t influence_scratch_floats(int n_rows, int n_q_heads, int max_len) {
+  // scores [rows][Hq][max_len] followed by (m, l) pairs [rows][Hq]
+  return (size_t)n_rows * n_q_heads * max_len + 2 * (size_t)n_rows * n_q_heads + 64;
+}
+
+template <typename T>
+hipError_t launch_influence_accumulate(const T* q, const int* row_pos, const int* row_req, const ReqTable* table,
+                                       int n_rows, const T* k_pool, KvGeom g, int n_q_heads, int max_len,
+                                       const InfluencePtrs& out, float* scratch, hipStream_t st) {
+  if (n_rows <= 0 || max_len <= 0) return hipSuccess;
+  const int G = n_q_heads / g.n_kv_heads;
+  if (G > 8) return hipErrorInvalidValue;
+  float* scores = scratch;
+  // 8-byte aligned pair array behind the scores
+  size_t off = (size_t)n_rows * n_q_heads * max_len;
+  off = (off + 1) & ~(size_t)1;
+  float2* ml = reinterpret_cast<float2*>(scratch + off);
+  const unsigned chunks = (unsigned)((max_len + kInfThreads - 1) / kInfThreads);
+  influence_scores_kernel<T><<<dim3(chunks, (unsigned)g.n_kv_heads, (unsigned)n_rows), kInfThreads,
+                               (size_t)G * g.head_dim * sizeof(float), st>>>(q, row_pos, row_req, table, k_pool, g,
+                                                                            n_q_heads, max_len, scores);
+  influence_norm_kernel<<<dim3((unsigned)n_q_heads, (unsigned)n_rows), kInfThreads, 0, st>>>(scores, row_pos, n_q_heads,
+                                                                                           max_len, ml);
+  influence_add_kernel<<<dim3(chunks, (unsigned)n_rows), kInfThreads, 0, st>>>(scores, ml, row_pos, row_req, out,
+                                                                               n_q_heads, max_len);
+  return hipGetLastError();
+}
+template hipError_t launch_influence_accumulate<float>(const float*, const int*, const int*, const ReqTable*, int,
+                                                       const float*, KvGeom, int, int, const InfluencePtrs&, float*,
+                                                       hipStream_t);
+template hipError_t launch_influence_accumulate<bf16>(const bf16*, const int*, const int*, const ReqTable*, int,
+                                                      const bf16*, KvGeom, int, int, const InfluencePtrs&, float*,
+                                                      hipStream_t);
+
+}  // namespace rc
