@@ -225,6 +225,30 @@ RC_API rc_status rc_decode_step(const rc_model* m, const rc_decode_req* reqs, in
                          void* const* k_pre_pool, int32_t capture_layer, float* logits, void* workspace,
                          size_t workspace_bytes, void* stream);
 
+/* Offline layer-range profiler (Section 4.2, Eq. 2-4; Appendix table "Hyperparameters for Critical Layer
+ * Selection").  Host function on host memory: d is [n_layers][n_tokens] float, row l = Eq. (1) of every
+ * calibration token at layer l (what rc_vdev_score returns for that layer, copied to the host).
+ *   s_l (Eq. 2) = mean_j (1 - d[l][j]);  l_min = argmin s.
+ *   l_start = deepest l <= l_min with s_l >= tau_st (0 if none).
+ *   l_end: b = mean - std (population) of s over the last `tail` layers; scanning l = l_min, l_min+1, ...:
+ *          the first l whose next `consecutive` layers all have s >= b and |s_l' - s_{l'-1}| < lambda * std;
+ *          the last layer if there is none; never below l_start + 1.
+ *   l_det: rho_l = Spearman correlation (average ranks for ties) of rows l-1 and l; alpha_l = rho_l -
+ *          2 rho_{l-1} + rho_{l-2} (l >= 3); l* = first l with alpha_{l-1} > 0 > alpha_l and l_start < l*+1 <=
+ *          l_end; l_det = l* + 1 (l_start + 1 if there is none).
+ * Indices are rows of d.  s_out / rho_out (optional, host, [n_layers] double) receive s_l and rho_l.
+ * The "min rise samples" hyper-parameter of the appendix table is not used by the paper's rules. */
+typedef struct {
+  float tau_st;          /* 0.99 */
+  int32_t tail;          /* T = 5 */
+  float lambda;          /* 2.0 */
+  int32_t consecutive;   /* C = 2 */
+} rc_layer_profile_params;
+typedef struct { int32_t l_start, l_det, l_end; } rc_layer_triple;
+RC_API rc_status rc_layer_profile(const float* d, int32_t n_layers, int32_t n_tokens,
+                           const rc_layer_profile_params* params, rc_layer_triple* out, double* s_out,
+                           double* rho_out);
+
 /* ---------------------------------------------------------------- timing
  * Optional per-stage GPU timing of rc_reuse / rc_prefill (the per-stage latency split the paper
  * reports in its Table "Per-agent TTFT breakdown").  While enabled, every kernel launch of those two

@@ -19,6 +19,10 @@ What follows the paper, and where:
   * budget selection top floor(budget*S) -- the floor convention of the
     CacheBlend setting in Appendix "Baseline Descriptions"
   * threshold / influence / suffix selection -- Section 4.3, Eq. (5)-(10)
+  * decoding step with un-rotated keys, captured hidden state and influence
+    accumulation -- Figure "Overview of RelayCaching", item (2); Eq. (6)
+  * layer-range profiler (start / end / detection layer) -- Section 4.2,
+    Eq. (2)-(4); Appendix table "Hyperparameters for Critical Layer Selection"
   * FULL and ZERO baselines    -- Appendix "Baseline Descriptions"
   * reuse rate                 -- Section 5.1 "Metrics"
 
@@ -39,6 +43,12 @@ Readings taken where the paper is silent (all restated in the design notes):
   * Selected rows write their fresh K/V into the cache before any row of that
     layer attends.
   * k = 0 skips the dense detect layers as well (pure reuse).
+  * Influence (Eq. 6) sums over query heads and includes the new token's
+    weight on itself.
+  * Profiler: "deepest layer with s >= tau_st" is searched at or before the
+    minimum-similarity layer; standard deviations are population ones; ranks
+    of equal deviations are averaged; rho_l compares layers l-1 and l; the
+    "min rise samples" hyper-parameter is listed but never used by the text.
 
 Pins: tests/test_oracle_pins.py.  No function here is unpinned, except that
 nothing fixes the numeric values of scores on trained models (the paper prints
@@ -287,6 +297,88 @@ def vdev_score(v_reuse: np.ndarray, v_full: np.ndarray) -> np.ndarray:
 def layer_similarity(d_jl: np.ndarray) -> np.ndarray:
     """Eq. (2): s_l = mean_j (1 - d_{j,l}); d_jl is [S][L]."""
     return np.mean(1.0 - np.asarray(d_jl, F64), axis=0)
+
+
+def average_ranks(x: np.ndarray) -> np.ndarray:
+    """Ranks 1..n of x, equal values sharing the mean of the ranks they occupy."""
+    x = np.asarray(x, F64)
+    order = np.argsort(x, kind="stable")
+    ranks = np.empty(x.shape[0], F64)
+    i = 0
+    while i < x.shape[0]:
+        j = i
+        while j + 1 < x.shape[0] and x[order[j + 1]] == x[order[i]]:
+            j += 1
+        ranks[order[i:j + 1]] = 0.5 * (i + j) + 1.0
+        i = j + 1
+    return ranks
+
+
+def spearman_adjacent(d_jl: np.ndarray) -> np.ndarray:
+    """rho_l, l = 1..L-1: Spearman rank correlation of the token-wise deviations of layers l-1 and l
+    (Section 4.2, "Detection layer"); rho_0 is set to 0 (undefined).  d_jl is [S][L].
+    A layer whose deviations are all equal has no ranking: its correlations are 0."""
+    d = np.asarray(d_jl, F64)
+    n_layers = d.shape[1]
+    ranks = np.stack([average_ranks(d[:, l]) for l in range(n_layers)], axis=1)
+    rho = np.zeros(n_layers, F64)
+    for l in range(1, n_layers):
+        a = ranks[:, l - 1] - np.mean(ranks[:, l - 1])
+        b = ranks[:, l] - np.mean(ranks[:, l])
+        den = np.sqrt(np.sum(a * a) * np.sum(b * b))
+        rho[l] = np.sum(a * b) / den if den > 0 else 0.0
+    return rho
+
+
+@dataclass
+class LayerProfile:
+    l_start: int
+    l_det: int
+    l_end: int
+    s: np.ndarray        # Eq. (2) per layer
+    rho: np.ndarray      # Spearman correlation of layers l-1 and l
+    alpha: np.ndarray    # Eq. (4); 0 where undefined (l < 3)
+
+
+def profile_layers(d_jl: np.ndarray, tau_st: float = 0.99, tail: int = 5, lam: float = 2.0,
+                   consecutive: int = 2) -> LayerProfile:
+    """The offline layer-range profiler (Section 4.2, Eq. 2-4) on deviations d_jl [S][L].
+
+    Start: the deepest layer at or before l_min = argmin s with s >= tau_st (0 if none).
+    End:   b = mean - std of s over the last `tail` layers; scanning l = l_min, l_min+1, ...: the
+           first l whose next `consecutive` layers all have s >= b and |s_l' - s_{l'-1}| < lam * std
+           (the last layer if no such l).
+    Detection: alpha_l = rho_l - 2 rho_{l-1} + rho_{l-2} (l >= 3); l* = the first l with
+           alpha_{l-1} > 0 and alpha_l < 0 for which l* + 1 lies in (l_start, l_end]; l_det = l* + 1
+           (l_start + 1 if there is none).
+    All indices are layer indices of the deviation matrix."""
+    d = np.asarray(d_jl, F64)
+    n_layers = d.shape[1]
+    s = layer_similarity(d)
+    l_min = int(np.argmin(s))
+    l_start = 0
+    for l in range(l_min + 1):
+        if s[l] >= tau_st:
+            l_start = l
+    last = s[max(0, n_layers - tail):]
+    mu, sigma = float(np.mean(last)), float(np.sqrt(np.mean((last - np.mean(last)) ** 2)))
+    b = mu - sigma
+    l_end = n_layers - 1
+    for l in range(l_min, n_layers - consecutive):
+        if all(s[l2] >= b and abs(s[l2] - s[l2 - 1]) < lam * sigma for l2 in range(l + 1, l + 1 + consecutive)):
+            l_end = l
+            break
+    l_end = max(l_end, min(l_start + 1, n_layers - 1))
+    rho = spearman_adjacent(d)
+    alpha = np.zeros(n_layers, F64)
+    for l in range(3, n_layers):
+        alpha[l] = rho[l] - 2.0 * rho[l - 1] + rho[l - 2]
+    l_det = min(l_start + 1, l_end)
+    for l in range(4, n_layers):
+        if alpha[l - 1] > 0.0 and alpha[l] < 0.0 and l_start < l + 1 <= l_end:
+            l_det = l + 1
+            break
+    return LayerProfile(l_start, l_det, l_end, s, rho, alpha)
 
 
 def topk_select(score: Sequence[float], k: int) -> np.ndarray:

@@ -24,7 +24,7 @@ RC_SELECT_BUDGET, RC_SELECT_THRESHOLD = 0, 1
 
 EXPORTS = [
     "rc_status_str", "rc_build_info", "rc_model_create", "rc_model_destroy", "rc_reuse_workspace_bytes",
-    "rc_reuse", "rc_prefill_workspace_bytes", "rc_prefill", "rc_decode_workspace_bytes", "rc_decode_step", "rc_stage_workspace_bytes", "rc_rope_rerotate",
+    "rc_reuse", "rc_prefill_workspace_bytes", "rc_prefill", "rc_decode_workspace_bytes", "rc_decode_step", "rc_layer_profile", "rc_stage_workspace_bytes", "rc_rope_rerotate",
     "rc_vdev_score", "rc_topk", "rc_threshold_select", "rc_final_select", "rc_sparse_attention", "rc_gemm_rows",
     "rc_scatter_paged", "rc_profile_enable", "rc_profile_class_count", "rc_profile_class_name", "rc_profile_read",
     "rc_tune_set", "rc_sparse_attention_workspace_bytes",
@@ -72,6 +72,14 @@ class rc_decode_req(C.Structure):
                 ("s_inf", C.c_void_p)]
 
 
+class rc_layer_profile_params(C.Structure):
+    _fields_ = [("tau_st", C.c_float), ("tail", C.c_int32), ("lam", C.c_float), ("consecutive", C.c_int32)]
+
+
+class rc_layer_triple(C.Structure):
+    _fields_ = [("l_start", C.c_int32), ("l_det", C.c_int32), ("l_end", C.c_int32)]
+
+
 class rc_plan(C.Structure):
     _fields_ = [("l_start", C.c_int32), ("l_det", C.c_int32), ("l_end", C.c_int32),
                 ("k_per_req", C.POINTER(C.c_int32)), ("forced_idx", C.c_void_p),
@@ -102,6 +110,8 @@ def _load() -> C.CDLL:
     lib.rc_decode_step.restype = C.c_int
     lib.rc_decode_step.argtypes = [vp, C.POINTER(rc_decode_req), i32, C.POINTER(rc_paged_kv), C.POINTER(vp), i32, vp,
                                    vp, sz, vp]
+    lib.rc_layer_profile.restype = C.c_int
+    lib.rc_layer_profile.argtypes = [vp, i32, i32, C.POINTER(rc_layer_profile_params), C.POINTER(rc_layer_triple), vp, vp]
     lib.rc_prefill_workspace_bytes.restype = sz
     lib.rc_prefill_workspace_bytes.argtypes = [vp, C.POINTER(i32), i32]
     lib.rc_prefill.restype = C.c_int
@@ -396,6 +406,20 @@ def rc_decode_step(model: Model, reqs: Sequence[DecodeReq], cache: PagedKV, logi
                             k_pre.c.k_pool if k_pre is not None else None, capture_layer, _ptr(logits),
                             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(st, "rc_decode_step")
+
+
+def rc_layer_profile(d, tau_st: float = 0.99, tail: int = 5, lam: float = 2.0, consecutive: int = 2):
+    """d: host float32 array [n_layers][n_tokens].  Returns ((l_start, l_det, l_end), s[L], rho[L])."""
+    import numpy as np
+    d = np.ascontiguousarray(d, dtype=np.float32)
+    n_layers, n_tokens = d.shape
+    params = rc_layer_profile_params(tau_st, tail, lam, consecutive)
+    out = rc_layer_triple()
+    s = np.zeros(n_layers, np.float64)
+    rho = np.zeros(n_layers, np.float64)
+    _check(lib.rc_layer_profile(d.ctypes.data, n_layers, n_tokens, C.byref(params), C.byref(out), s.ctypes.data,
+                                rho.ctypes.data), "rc_layer_profile")
+    return (out.l_start, out.l_det, out.l_end), s, rho
 
 
 def alloc_workspace(n_bytes: int, device="cuda") -> torch.Tensor:

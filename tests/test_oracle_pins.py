@@ -443,3 +443,61 @@ def test_decode_first_token_puts_all_weight_on_itself():
     logits, cap = R.decode_step(m, x[0], 0, kc, vc, s_inf=s_inf)
     assert s_inf[0] == m.n_layers * m.n_q_heads and cap is None
     assert np.allclose(logits, R.full_prefill(m, x).logits, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------
+# layer-range profiler (Section 4.2, Eq. 2-4)
+# ----------------------------------------------------------------------------
+def _deviations_with_profile(s_target, n=40, seed=3):
+    """d[j][l] whose layer means are exactly 1 - s_target[l] (token-wise factors sum to zero)."""
+    rng = np.random.default_rng(seed)
+    eps = rng.standard_normal((n, len(s_target))) * 0.2
+    eps -= eps.mean(axis=0, keepdims=True)
+    return (1.0 - np.asarray(s_target))[None, :] * (1.0 + eps)
+
+
+def test_profiler_start_and_end_layer_hand_example():
+    # U-shaped profile; worked by hand:
+    #   l_min = 5.  Deepest layer <= 5 with s >= 0.99 is 2.
+    #   last 5 layers: 0.93 0.95 0.955 0.953 0.956 -> mean 0.9488, population std 0.00962, b = 0.93918,
+    #   lambda * std = 0.01924.  l = 5: s6 < b.  l = 6: s7 = 0.93 < b.  l = 7: |s8 - s7| = 0.02 too large.
+    #   l = 8: s9, s10 >= b with steps 0.005 and 0.002 -> l_end = 8.
+    s = [1.0, 0.995, 0.992, 0.97, 0.90, 0.85, 0.88, 0.93, 0.95, 0.955, 0.953, 0.956]
+    prof = R.profile_layers(_deviations_with_profile(s))
+    assert np.allclose(prof.s, s, atol=1e-12)
+    assert (prof.l_start, prof.l_end) == (2, 8)
+    assert prof.l_start < prof.l_det <= prof.l_end
+    # a stricter stability rule moves the end later; a laxer threshold moves the start deeper
+    assert R.profile_layers(_deviations_with_profile(s), consecutive=3).l_end == 8
+    assert R.profile_layers(_deviations_with_profile(s), lam=0.4).l_end == 9      # 0.00385: the step 0.005 into layer 9 is too large
+    assert R.profile_layers(_deviations_with_profile(s), lam=0.1).l_end == 11     # 0.00096: no step is small enough
+    assert R.profile_layers(_deviations_with_profile(s), tau_st=0.96).l_start == 3
+    assert R.profile_layers(_deviations_with_profile(s), tau_st=1.5).l_start == 0
+
+
+def test_profiler_rank_correlation_against_library_and_sign_change():
+    import scipy.stats
+    rng = np.random.default_rng(5)
+    n, L = 200, 14
+    base = rng.random(n)
+    # the ranking settles with depth: the share of the common pattern rises quickly, then saturates
+    share = 1.0 - np.exp(-0.55 * np.arange(L))
+    d = np.stack([share[l] * base + (1 - share[l]) * rng.random(n) for l in range(L)], axis=1) * 0.05
+    d[:25, 6] = d[0, 6]                                     # ties in one layer
+    rho = R.spearman_adjacent(d)
+    for l in range(1, L):
+        assert abs(rho[l] - scipy.stats.spearmanr(d[:, l - 1], d[:, l]).statistic) < 1e-12
+    assert np.array_equal(R.average_ranks([3.0, 1.0, 3.0, 2.0]), [3.5, 1.0, 3.5, 2.0])
+    # second difference by an independent route, then the first + -> - change inside the range
+    second = np.zeros(L)
+    second[3:] = np.diff(rho[1:], n=2)
+    prof = R.profile_layers(d, tau_st=0.0)                   # l_start = l_min (every layer passes the threshold)
+    assert np.allclose(prof.alpha, second, atol=1e-14)
+    want = next((l + 1 for l in range(4, L) if second[l - 1] > 0 > second[l] and prof.l_start < l + 1 <= prof.l_end),
+                min(prof.l_start + 1, prof.l_end))
+    assert prof.l_det == want
+    # constant deviations in a layer: no ranking, correlation 0 on both sides
+    d2 = d.copy()
+    d2[:, 4] = 0.01
+    rho2 = R.spearman_adjacent(d2)
+    assert rho2[4] == 0.0 and rho2[5] == 0.0
