@@ -127,6 +127,13 @@ typedef struct {
   int32_t dst_seq;       /* row of the destination block table */
   const float* s_inf;    /* optional [S] float: influence scores the earlier agent accumulated while decoding
                             (Eq. 6); only read by the threshold selector; NULL: no influence term */
+  int32_t n_cached;      /* rows 0..n_cached-1 of dst_seq are already final (an earlier call wrote them): the
+                            request's first token sits at position n_cached and attends over them.  A prompt
+                            with several reused segments from different agents (a relay chain) is taken over
+                            piece by piece, [new text ; segment] per call on the same dst_seq; under causal
+                            attention this equals one pass over the whole prompt. */
+  int32_t no_logits;     /* 1: not the last piece: with n_suffix == 0 the last segment token is not kept
+                            live for the logits (this request's logits row is then undefined) */
 } rc_request;
 
 typedef enum {

@@ -23,6 +23,9 @@ What follows the paper, and where:
     accumulation -- Figure "Overview of RelayCaching", item (2); Eq. (6)
   * layer-range profiler (start / end / detection layer) -- Section 4.2,
     Eq. (2)-(4); Appendix table "Hyperparameters for Critical Layer Selection"
+  * prompts with several reused segments (relay chains) -- Appendix "Agent
+    Configuration" (cumulative context chain); each segment scored and selected
+    on its own
   * FULL and ZERO baselines    -- Appendix "Baseline Descriptions"
   * reuse rate                 -- Section 5.1 "Metrics"
 
@@ -517,3 +520,91 @@ def relay_prefill(m: OracleModel, x_prefix: np.ndarray, seg: SegmentRecord, l_st
 
     h_last = h_suf[-1] if n_suf > 0 else h_seg[-1]
     return RelayResult(kc, vc, sel, score, first_token_logits(m, h_last), active_rows)
+
+
+# --------------------------------------------------------------------------
+# several reused segments in one prompt (relay chains)
+# --------------------------------------------------------------------------
+@dataclass
+class MultiRelayResult:
+    k_cache: np.ndarray            # [L][T][Hkv][dh]
+    v_cache: np.ndarray
+    sel_idx: List[np.ndarray]      # per segment, ascending, relative to the segment
+    score: List[Optional[np.ndarray]]
+    logits: np.ndarray
+    active_rows: List[int]
+
+
+def relay_prefill_multi(m: OracleModel, pieces: Sequence[tuple], l_start: int, l_det: int,
+                        l_end: int) -> MultiRelayResult:
+    """Prefill of a prompt made of new text and several reused segments, in one pass over the layers.
+
+    pieces: ("new", x[n][d]) or ("seg", SegmentRecord, k) in prompt order; every segment has its own
+    record (own old position), its own Eq. (1) scores at l_det and its own top-k.  The steps per layer
+    are those of relay_prefill with "the segment" read as "every segment": all new tokens are live in
+    every layer; a segment with k > 0 has all tokens live in [l_start, l_det) and its selected tokens
+    in [l_det, l_end]; if the prompt ends with a segment, that segment's last token is live from
+    l_start to the last layer and yields the logits.
+    """
+    assert 0 <= l_start < l_det <= l_end < m.n_layers
+    spans = []                                  # (kind, first position, length, payload...)
+    t = 0
+    for pc in pieces:
+        n = pc[1].shape[0] if pc[0] == "new" else pc[1].v.shape[1]
+        spans.append((pc, t, n))
+        t += n
+    shape = (m.n_layers, t, m.n_kv_heads, m.head_dim)
+    kc, vc = np.zeros(shape, F64), np.zeros(shape, F64)
+    segs = [(pc[1], p0, n, pc[2]) for pc, p0, n in spans if pc[0] == "seg"]
+    for rec, p0, n, _ in segs:
+        new_pos = p0 + np.arange(n)
+        for l in range(m.n_layers):
+            if rec.k_is_pre_rope:
+                kc[l][new_pos] = rope_rotate(rec.k[l], new_pos, m.rope_base)
+            else:
+                kc[l][new_pos] = rope_rotate(rec.k[l], new_pos - (rec.old_start_pos + np.arange(n)), m.rope_base)
+            vc[l][new_pos] = np.asarray(rec.v[l], F64)
+    ends_with_seg = len(spans) > 0 and spans[-1][0][0] == "seg"
+    hidden = {}                                  # position -> hidden state of the rows that are live
+    for pc, p0, n in spans:
+        if pc[0] == "new":
+            for i in range(n):
+                hidden[p0 + i] = np.asarray(pc[1][i], F64)
+    sel = [np.zeros(0, np.int32) for _ in segs]
+    score: List[Optional[np.ndarray]] = [None for _ in segs]
+    active_rows = []
+    last_pos = t - 1
+    for l in range(m.n_layers):
+        if l == l_start:
+            for si, (rec, p0, n, k) in enumerate(segs):
+                if k > 0:
+                    for j in range(n):
+                        hidden[p0 + j] = np.asarray(rec.h_start[j], F64)
+                elif ends_with_seg and si == len(segs) - 1:
+                    hidden[p0 + n - 1] = np.asarray(rec.h_start[n - 1], F64)
+        if l == l_det:
+            w = m.layers[l]
+            for si, (rec, p0, n, k) in enumerate(segs):
+                if k <= 0:
+                    continue
+                h_seg = np.stack([hidden[p0 + j] for j in range(n)])
+                v_fresh = linear(rmsnorm(h_seg, w["g_attn"], m.rms_eps), w["wv"]).reshape(n, m.n_kv_heads, m.head_dim)
+                score[si] = vdev_score(vc[l][p0:p0 + n], v_fresh)
+                sel[si] = topk_select(score[si], k)
+                keep = set(sel[si].tolist())
+                if ends_with_seg and si == len(segs) - 1:
+                    keep.add(n - 1)
+                for j in range(n):
+                    if j not in keep:
+                        del hidden[p0 + j]
+        if l == l_end + 1:
+            for si, (rec, p0, n, k) in enumerate(segs):
+                for j in range(n):
+                    if p0 + j in hidden and not (ends_with_seg and p0 + j == last_pos):
+                        del hidden[p0 + j]
+        pos = np.array(sorted(hidden), dtype=np.int64)
+        h_all = np.stack([hidden[p] for p in pos])
+        active_rows.append(int(pos.shape[0]))
+        h_all = decoder_layer(m, l, h_all, pos, kc[l], vc[l])
+        hidden = {int(p): h_all[i] for i, p in enumerate(pos)}
+    return MultiRelayResult(kc, vc, sel, score, first_token_logits(m, hidden[last_pos]), active_rows)

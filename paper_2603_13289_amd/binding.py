@@ -64,7 +64,7 @@ class rc_request(C.Structure):
     _fields_ = [("n_prefix", C.c_int32), ("x_prefix", C.c_void_p), ("n_seg", C.c_int32), ("h_start", C.c_void_p),
                 ("n_suffix", C.c_int32), ("x_suffix", C.c_void_p), ("src_seq", C.c_int32), ("src_offset", C.c_int32),
                 ("k_is_pre_rope", C.c_int32), ("seg_old_start_pos", C.c_int32), ("dst_seq", C.c_int32),
-                ("s_inf", C.c_void_p)]
+                ("s_inf", C.c_void_p), ("n_cached", C.c_int32), ("no_logits", C.c_int32)]
 
 
 class rc_decode_req(C.Structure):
@@ -309,12 +309,15 @@ class Request:
     seg_old_start_pos: int = 0
     dst_seq: int = 0
     s_inf: Optional[torch.Tensor] = None      # [S] float32 influence scores (threshold selector only)
+    n_cached: int = 0                         # rows of dst_seq an earlier call already finished
+    no_logits: bool = False                   # not the last piece of a multi-segment prompt
 
     def c(self) -> rc_request:
         n = lambda t: 0 if t is None else int(t.shape[0])
         return rc_request(n(self.x_prefix), _ptr(self.x_prefix), n(self.h_start), _ptr(self.h_start),
                           n(self.x_suffix), _ptr(self.x_suffix), self.src_seq, self.src_offset,
-                          1 if self.k_is_pre_rope else 0, self.seg_old_start_pos, self.dst_seq, _ptr(self.s_inf))
+                          1 if self.k_is_pre_rope else 0, self.seg_old_start_pos, self.dst_seq, _ptr(self.s_inf), self.n_cached,
+                          1 if self.no_logits else 0)
 
 
 @dataclass

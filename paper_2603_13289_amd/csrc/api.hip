@@ -208,14 +208,15 @@ constexpr int kLongKvTiles = 24;   // a query tile with more KV tiles (of 64 key
 constexpr int kKvTile = 64;
 
 int est_row_pos(const ReqDev& r, int i) {
-  if (i < r.P) return i;
+  if (i < r.P) return r.pos0 + i;
   if (i < r.P + r.n_seg_rows) {
     const int si = i - r.P;
-    if (r.seg_mode == SEG_ALL) return r.P + si;
-    if (r.seg_mode == SEG_SEL) return r.P + (int)std::min<long>((long)(si + 1) * r.S / std::max(r.n_seg_rows, 1), r.S) - 1;
-    return r.P + r.S - 1;
+    if (r.seg_mode == SEG_ALL) return r.pos0 + r.P + si;
+    if (r.seg_mode == SEG_SEL)
+      return r.pos0 + r.P + (int)std::min<long>((long)(si + 1) * r.S / std::max(r.n_seg_rows, 1), r.S) - 1;
+    return r.pos0 + r.P + r.S - 1;
   }
-  return r.P + r.S + (i - r.P - r.n_seg_rows);
+  return r.pos0 + r.P + r.S + (i - r.P - r.n_seg_rows);
 }
 
 AttnSplit plan_phase_split(ReqTable* t, int n_req, int n_kv_heads, int tile_rows, int max_pos) {
@@ -264,7 +265,7 @@ AttnSplit plan_phase_split(ReqTable* t, int n_req, int n_kv_heads, int tile_rows
     for (int j = 0; j < tiles; ++j) {
       const int i_last = std::min((j + 1) * tile_rows, r.n_rows) - 1;
       // a tile of prefix rows only has exactly known positions; any other tile may reach far
-      if (i_last >= r.P || i_last / kKvTile + 1 > thr) { start = j; break; }
+      if (i_last >= r.P || (r.pos0 + i_last) / kKvTile + 1 > thr) { start = j; break; }
     }
     r.long_tile_start = start;
     r.part_base = base;
@@ -589,20 +590,21 @@ rc_status prepare_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req
     if (q.n_suffix > 0 && !q.x_suffix) return RC_E_INVALID_ARG;
     if (k < 0 || k > q.n_seg) return RC_E_INVALID_ARG;
     job->s_inf[b] = by_threshold ? q.s_inf : nullptr;
-    if (q.src_offset < 0 || q.seg_old_start_pos < 0) return RC_E_INVALID_ARG;
+    if (q.src_offset < 0 || q.seg_old_start_pos < 0 || q.n_cached < 0) return RC_E_INVALID_ARG;
     ReqHost h;
     h.P = q.n_prefix; h.S = q.n_seg; h.nsuf = q.n_suffix; h.k = k;
-    h.carries_logits = q.n_suffix == 0;
+    h.carries_logits = q.n_suffix == 0 && !q.no_logits;
     job->rq.push_back(h);
     ReqDev& r = job->base.r[b];
     r.P = h.P; r.S = h.S; r.nsuf = h.nsuf; r.k = k;
+    r.pos0 = q.n_cached;
     r.dst_seq = q.dst_seq; r.src_seq = q.src_seq; r.src_offset = q.src_offset;
     r.k_is_pre_rope = q.k_is_pre_rope ? 1 : 0;
-    r.rot_delta = q.n_prefix - q.seg_old_start_pos;
+    r.rot_delta = q.n_cached + q.n_prefix - q.seg_old_start_pos;
     r.sel_base = by_threshold ? seg : sel; r.score_base = seg;
     r.x_prefix = q.x_prefix; r.h_start = q.h_start; r.x_suffix = q.x_suffix; r.h_capture = nullptr;
     sel += k; seg += q.n_seg;
-    max_pos = std::max(max_pos, q.n_prefix + q.n_seg + q.n_suffix);
+    max_pos = std::max(max_pos, q.n_cached + q.n_prefix + q.n_seg + q.n_suffix);
     max_seg = std::max(max_seg, q.n_seg);
   }
   job->max_pos = max_pos;
@@ -744,7 +746,7 @@ rc_status rc_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req, con
   if (sum_k > 0 && job.selector == RC_SELECT_THRESHOLD && !sel_cnt) return RC_E_INVALID_ARG;
   if (job.max_seg > 0) RC_TRY(check_paged(src, m->d.n_layers));
   for (int b = 0; b < n_req; ++b) {
-    RC_TRY(check_seq_fits(dst, reqs[b].dst_seq, reqs[b].n_prefix + reqs[b].n_seg + reqs[b].n_suffix));
+    RC_TRY(check_seq_fits(dst, reqs[b].dst_seq, reqs[b].n_cached + reqs[b].n_prefix + reqs[b].n_seg + reqs[b].n_suffix));
     if (reqs[b].n_seg > 0) RC_TRY(check_seq_fits(src, reqs[b].src_seq, reqs[b].src_offset + reqs[b].n_seg));
   }
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RC_E_WORKSPACE;

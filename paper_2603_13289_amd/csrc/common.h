@@ -117,6 +117,7 @@ enum SegMode : int { SEG_NONE = 0, SEG_ALL = 1, SEG_SEL = 2, SEG_LAST = 3 };
 
 struct ReqDev {
   int P, S, nsuf, k;
+  int pos0, pad0;   // position of the request's first row (rows 0..pos0-1 of the sequence are already final)
   int row_base, n_seg_rows, n_rows, seg_mode;           // current phase
   int old_row_base, old_n_seg_rows, old_seg_mode, has_old;  // phase being left (has_old = 0: inputs)
   int dst_seq, src_seq, src_offset, rot_delta;           // rot_delta valid when keys are rotated

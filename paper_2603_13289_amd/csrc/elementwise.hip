@@ -81,7 +81,7 @@ rerotate_kernel(RerotatePtrs ptrs, KvGeom gs, KvGeom gd, const ReqTable* __restr
   const int head = (int)(th % gs.n_kv_heads);
   const long j = th / gs.n_kv_heads;
   if (j >= rq.S) return;
-  const int new_pos = rq.P + (int)j;
+  const int new_pos = rq.pos0 + rq.P + (int)j;
   const size_t so = kv_row_offset(gs, rq.src_seq, rq.src_offset + (int)j, head);
   const size_t dof = kv_row_offset(gd, rq.dst_seq, new_pos, head);
   float lo[VEC], hi[VEC], olo[VEC], ohi[VEC];
@@ -133,7 +133,7 @@ build_rows_kernel(const ReqTable* __restrict__ table, const float* __restrict__ 
   const T* src_t = nullptr;      // input tensor row (T)
   const float* src_f = nullptr;  // row of the previous phase's buffer
   if (i < rq.P) {
-    pos = i;
+    pos = rq.pos0 + i;
     if (rq.has_old) src_f = h_old + (size_t)(rq.old_row_base + i) * d;
     else src_t = reinterpret_cast<const T*>(rq.x_prefix) + (size_t)i * d;
   } else if (i < rq.P + rq.n_seg_rows) {
@@ -143,14 +143,14 @@ build_rows_kernel(const ReqTable* __restrict__ table, const float* __restrict__ 
     else if (rq.seg_mode == SEG_SEL) j = (si < rq.k) ? sel_idx[rq.sel_base + si] : rq.S - 1;
     else j = rq.S - 1;
     j = min(max(j, 0), rq.S - 1);
-    pos = rq.P + j;
+    pos = rq.pos0 + rq.P + j;
     if (rq.old_seg_mode == SEG_ALL) src_f = h_old + (size_t)(rq.old_row_base + rq.P + j) * d;
     else if (rq.old_seg_mode == SEG_SEL) src_f = h_old + (size_t)(rq.old_row_base + rq.P + rq.old_n_seg_rows - 1) * d;
     else if (rq.old_seg_mode == SEG_LAST) src_f = h_old + (size_t)(rq.old_row_base + rq.P) * d;
     else src_t = reinterpret_cast<const T*>(rq.h_start) + (size_t)j * d;
   } else {
     const int si = i - rq.P - rq.n_seg_rows;
-    pos = rq.P + rq.S + si;
+    pos = rq.pos0 + rq.P + rq.S + si;
     if (rq.has_old) src_f = h_old + (size_t)(rq.old_row_base + rq.P + rq.old_n_seg_rows + si) * d;
     else src_t = reinterpret_cast<const T*>(rq.x_suffix) + (size_t)si * d;
   }
@@ -366,7 +366,7 @@ vdev_score_kernel(const T* __restrict__ v_fresh, int fresh_row_stride, const T* 
 #pragma unroll
     for (int e = 0; e < VEC; ++e) a[e] = b[e] = 0.f;
     if (head < g.n_kv_heads) {
-      Vec16<T>::load(v_pool + kv_row_offset(g, rq.dst_seq, rq.P + j, head) + sub * VEC, a);
+      Vec16<T>::load(v_pool + kv_row_offset(g, rq.dst_seq, rq.pos0 + rq.P + j, head) + sub * VEC, a);
       Vec16<T>::load(fresh + head * g.head_dim + sub * VEC, b);
     }
     float dot = 0.f, na = 0.f, nb = 0.f;
@@ -427,6 +427,10 @@ hipError_t launch_copy_i32(const int* src, int* dst, int n, hipStream_t st) {
 __global__ void __launch_bounds__(kThreads)
 gather_last_kernel(const ReqTable* __restrict__ table, const float* __restrict__ h, float* __restrict__ out, int d) {
   const ReqDev& rq = table->r[blockIdx.x];
+  if (rq.n_rows <= 0) {   // a request without live rows in the last phase has no logits: defined zeros
+    for (int c = threadIdx.x; c < d; c += kThreads) out[(size_t)blockIdx.x * d + c] = 0.f;
+    return;
+  }
   const float* src = h + (size_t)(rq.row_base + rq.n_rows - 1) * d;
   for (int c = threadIdx.x; c < d; c += kThreads) out[(size_t)blockIdx.x * d + c] = src[c];
 }

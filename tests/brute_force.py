@@ -172,3 +172,60 @@ def brute_decode_influence(tm, x, n_prompt):
                         s_inf[j] += math.exp(sc[j] - mx) / z
             h = token_attend(tm, l, h, q, t, kc[l], vc[l])
     return s_inf, _matvec(tm.w_lm, _rms(h, tm.g_final, tm.eps))
+
+
+def brute_relay_multi(tm, pieces, l_start, l_det, l_end):
+    """Scalar single-pass prefill of a prompt made of ("new", x) and ("seg", k_pre, v, h_start, k) pieces
+    (nested lists).  The prompt ends with new text.  Returns (kc, vc, sels, logits)."""
+    kc = [dict() for _ in range(tm.L)]
+    vc = [dict() for _ in range(tm.L)]
+    hid, segs, t = {}, [], 0
+    for pc in pieces:
+        if pc[0] == "new":
+            for row in pc[1]:
+                hid[t] = list(row)
+                t += 1
+        else:
+            _, k_pre, v, h_start, k = pc
+            n = len(h_start)
+            for l in range(tm.L):
+                for j in range(n):
+                    kc[l][t + j] = [_rot(k_pre[l][j][hh], t + j, tm.base) for hh in range(tm.hkv)]
+                    vc[l][t + j] = [list(v[l][j][hh]) for hh in range(tm.hkv)]
+            segs.append((t, n, h_start, k))
+            t += n
+    sels = [[] for _ in segs]
+    for l in range(tm.L):
+        if l == l_start:
+            for p0, n, h_start, k in segs:
+                if k > 0:
+                    for j in range(n):
+                        hid[p0 + j] = list(h_start[j])
+        if l == l_det:
+            w = tm.layers[l]
+            for si, (p0, n, h_start, k) in enumerate(segs):
+                if k <= 0:
+                    continue
+                score = []
+                for j in range(n):
+                    vf = _matvec(w["wv"], _rms(hid[p0 + j], w["g_attn"], tm.eps))
+                    acc = 0.0
+                    for hh in range(tm.hkv):
+                        a, b = vc[l][p0 + j][hh], vf[hh * tm.dh:(hh + 1) * tm.dh]
+                        dot = sum(u * v for u, v in zip(a, b))
+                        acc += dot / max(math.sqrt(sum(u * u for u in a)) * math.sqrt(sum(v * v for v in b)), 1e-12)
+                    score.append(1.0 - acc / tm.hkv)
+                ranked = sorted(range(n), key=lambda j: (-score[j], j))
+                sels[si] = sorted(ranked[:k])
+                for j in range(n):
+                    if j not in sels[si]:
+                        del hid[p0 + j]
+        if l == l_end + 1:
+            for p0, n, _, _ in segs:
+                for j in range(n):
+                    hid.pop(p0 + j, None)
+        active = sorted(hid)
+        qs = {p: token_layer(tm, l, hid[p], p, kc[l], vc[l]) for p in active}
+        hid = {p: token_attend(tm, l, hid[p], qs[p], p, kc[l], vc[l]) for p in active}
+    logits = _matvec(tm.w_lm, _rms(hid[t - 1], tm.g_final, tm.eps))
+    return kc, vc, sels, logits

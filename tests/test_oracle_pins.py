@@ -501,3 +501,72 @@ def test_profiler_rank_correlation_against_library_and_sign_change():
     d2[:, 4] = 0.01
     rho2 = R.spearman_adjacent(d2)
     assert rho2[4] == 0.0 and rho2[5] == 0.0
+
+
+# ----------------------------------------------------------------------------
+# prompts with several reused segments
+# ----------------------------------------------------------------------------
+def _multi_setup(n_layers=4, l_start=1):
+    w, m = _tiny(n_layers=n_layers, name="multi")
+    sizes = dict(a=5, s1=9, b=4, s2=7, c=3, alt1=6, alt2=2)
+    x = {k: make_hidden(w, k, n).astype(np.float64) for k, n in sizes.items()}
+    rec1 = R.decode_record(m, x["alt1"], x["s1"], l_start)
+    rec2 = R.decode_record(m, x["alt2"], x["s2"], l_start, k_is_pre_rope=False)
+    return m, x, rec1, rec2
+
+
+def test_multi_segment_reduces_to_single_segment_and_is_prefix_closed():
+    m, x, rec1, rec2 = _multi_setup()
+    one = R.relay_prefill_multi(m, [("new", x["a"]), ("seg", rec1, 3), ("new", x["b"])], 1, 2, 3)
+    ref = R.relay_prefill(m, x["a"], rec1, 1, 2, 3, 3, x_suffix=x["b"])
+    assert np.allclose(one.k_cache, ref.k_cache, atol=1e-12) and np.allclose(one.v_cache, ref.v_cache, atol=1e-12)
+    assert one.sel_idx[0].tolist() == ref.sel_idx.tolist() and np.allclose(one.logits, ref.logits, atol=1e-11)
+    assert one.active_rows == ref.active_rows
+    # ending with the segment: its last token carries the logits, as in the single-segment pass
+    tail = R.relay_prefill_multi(m, [("new", x["a"]), ("seg", rec1, 3)], 1, 2, 3)
+    ref2 = R.relay_prefill(m, x["a"], rec1, 1, 2, 3, 3)
+    assert np.allclose(tail.logits, ref2.logits, atol=1e-11) and tail.active_rows == ref2.active_rows
+    # causality: what a longer prompt leaves in the rows of its first pieces is what those pieces alone leave
+    both = R.relay_prefill_multi(m, [("new", x["a"]), ("seg", rec1, 3), ("new", x["b"]), ("seg", rec2, 2),
+                                     ("new", x["c"])], 1, 2, 3)
+    n1 = one.k_cache.shape[1]
+    assert np.allclose(both.k_cache[:, :n1], one.k_cache, atol=1e-12)
+    assert np.allclose(both.v_cache[:, :n1], one.v_cache, atol=1e-12)
+    assert both.sel_idx[0].tolist() == one.sel_idx[0].tolist() and len(both.sel_idx[1]) == 2
+
+
+def test_multi_segment_full_budget_is_full_prefill_and_zero_budget_is_reuse():
+    m, x, rec1, rec2 = _multi_setup(l_start=0)
+    prompt = np.concatenate([x["a"], x["s1"], x["b"], x["s2"], x["c"]])
+    full = R.full_prefill(m, prompt)
+    rec1.h_start, rec2.h_start = x["s1"].copy(), x["s2"].copy()       # l_start = 0: inputs are the hidden states
+    got = R.relay_prefill_multi(m, [("new", x["a"]), ("seg", rec1, 9), ("new", x["b"]), ("seg", rec2, 7),
+                                    ("new", x["c"])], 0, 1, m.n_layers - 1)
+    assert np.allclose(got.k_cache, full.k_cache, atol=1e-10) and np.allclose(got.v_cache, full.v_cache, atol=1e-10)
+    assert np.allclose(got.logits, full.logits, atol=1e-10)
+    zero = R.relay_prefill_multi(m, [("new", x["a"]), ("seg", rec1, 0), ("new", x["b"]), ("seg", rec2, 0),
+                                     ("new", x["c"])], 0, 1, 2)
+    p1, p2 = 5, 5 + 9 + 4
+    for l in range(m.n_layers):
+        assert np.array_equal(zero.v_cache[l][p1:p1 + 9], rec1.v[l]) and np.array_equal(zero.v_cache[l][p2:p2 + 7], rec2.v[l])
+        assert np.array_equal(zero.k_cache[l][p1:p1 + 9], R.rope_rotate(rec1.k[l], p1 + np.arange(9), m.rope_base))
+        # the second record stores keys rotated at their old positions 2..8: moved by the position difference
+        assert np.array_equal(zero.k_cache[l][p2:p2 + 7], R.rope_rotate(rec2.k[l], np.full(7, p2 - 2), m.rope_base))
+    assert zero.active_rows == [5 + 4 + 3] * m.n_layers
+
+
+def test_multi_segment_equals_scalar_reference():
+    m, x, rec1, _ = _multi_setup()
+    rec2 = R.decode_record(m, x["alt2"], x["s2"], 1)
+    got = R.relay_prefill_multi(m, [("new", x["a"]), ("seg", rec1, 3), ("new", x["b"]), ("seg", rec2, 2),
+                                    ("new", x["c"])], 1, 2, 2)
+    tm = B.TinyModel(m)
+    pieces = [("new", _nested(x["a"])), ("seg", _nested(rec1.k), _nested(rec1.v), _nested(rec1.h_start), 3),
+              ("new", _nested(x["b"])), ("seg", _nested(rec2.k), _nested(rec2.v), _nested(rec2.h_start), 2),
+              ("new", _nested(x["c"]))]
+    kc, vc, sels, logits = B.brute_relay_multi(tm, pieces, 1, 2, 2)
+    T = 5 + 9 + 4 + 7 + 3
+    assert [s.tolist() for s in got.sel_idx] == sels
+    assert np.allclose(got.k_cache, _cache_from_dicts(kc, T, 2, 4), atol=1e-10)
+    assert np.allclose(got.v_cache, _cache_from_dicts(vc, T, 2, 4), atol=1e-10)
+    assert np.allclose(got.logits, logits, atol=1e-10)
