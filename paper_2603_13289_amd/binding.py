@@ -281,6 +281,9 @@ class PagedKV:
                            self.head_dim, self.dtype)
 
     def _index(self, seq: int, n: int, start: int = 0):
+        if not (0 <= seq < self.n_seq and start >= 0 and start + n <= self.max_blocks * self.block_size):
+            raise IndexError(f"rows {start}..{start + n - 1} of sequence {seq} are outside the cache "
+                             f"({self.n_seq} sequences of {self.max_blocks * self.block_size} rows)")
         pos = torch.arange(start, start + n, device=self.block_table.device)
         blk = self.block_table[seq][pos // self.block_size].long()
         return blk, pos % self.block_size

@@ -228,3 +228,73 @@ def test_determinism_same_inputs_twice():
     assert np.array_equal(a.logits, b.logits)
     for l in range(case.w.shape.n_layers):
         assert np.array_equal(a.k_cache[0][l], b.k_cache[0][l])
+
+
+# ------------------------------------------------------------------ several reused segments (relay chain)
+@pytest.mark.parametrize("name,ends_with_segment", [("tiny5_f32", False), ("tiny5_f32", True), ("small_bf16", False)])
+def test_multi_segment_prompt_by_chained_calls(name, ends_with_segment):
+    """[new a][segment 1][new b][segment 2][new c]: the oracle does one pass over the whole prompt; the
+    library takes the prompt over piece by piece on the same destination sequence (n_cached)."""
+    import torch
+    from paper_2603_13289_amd import binding as rc
+    from synth import WORKLOADS, make_hidden, make_weights
+    from tests.harness import round_store, to_np
+    w = WORKLOADS[name]
+    sh = w.shape
+    dt = rc.rc_dtype_of(sh.dtype)
+    td = rc.torch_dtype(dt)
+    weights = make_weights(w)
+    om = R.OracleModel.from_shape(sh, weights)
+    model = rc.rc_model_create(sh, weights)
+    l_start, l_det, l_end = (1, 2, 3) if sh.n_layers >= 5 else (0, 1, 2)
+    sizes = dict(a=37, s1=101, b=20, s2=64, c=0 if ends_with_segment else 9, alt1=29, alt2=50)
+    x = {k: make_hidden(w, "multi_" + k, n) for k, n in sizes.items()}
+    up = lambda t: torch.from_numpy(np.ascontiguousarray(t, np.float32)).cuda().to(td).contiguous()
+
+    def record(alt, seg, pre_rope):
+        r = R.decode_record(om, alt, seg, l_start, k_is_pre_rope=pre_rope)
+        return R.SegmentRecord(round_store(r.k, sh.dtype).astype(np.float64), round_store(r.v, sh.dtype).astype(np.float64),
+                               round_store(r.h_start, sh.dtype).astype(np.float64), pre_rope, alt.shape[0])
+
+    rec1, rec2 = record(x["alt1"], x["s1"], True), record(x["alt2"], x["s2"], False)
+    k1, k2 = 15, 9
+    pieces = [("new", x["a"]), ("seg", rec1, k1), ("new", x["b"]), ("seg", rec2, k2)]
+    if not ends_with_segment:
+        pieces.append(("new", x["c"]))
+    want = R.relay_prefill_multi(om, pieces, l_start, l_det, l_end)
+    T = want.k_cache.shape[1]
+    # the earlier agents' caches
+    src = rc.PagedKV.contiguous(sh.n_layers, 2, max(sizes["alt1"] + sizes["s1"], sizes["alt2"] + sizes["s2"]),
+                                sh.n_kv_heads, sh.head_dim, dt)
+    for b, rec in enumerate((rec1, rec2)):
+        for l in range(sh.n_layers):
+            src.write("k", l, b, up(rec.k[l]), start=rec.old_start_pos)
+            src.write("v", l, b, up(rec.v[l]), start=rec.old_start_pos)
+    dst = rc.PagedKV.contiguous(sh.n_layers, 1, T, sh.n_kv_heads, sh.head_dim, dt, fill=5.0)
+    logits = torch.zeros((1, sh.vocab), dtype=torch.float32, device="cuda")
+    bf16 = sh.dtype == "bf16"
+    sels = []
+    at = 0
+    calls = [(x["a"], rec1, 0, k1, None, False), (x["b"], rec2, 1, k2, None if ends_with_segment else x["c"], True)]
+    for i, (xn, rec, seq, k, suffix, last) in enumerate(calls):
+        S = rec.v.shape[1]
+        req = rc.Request(up(xn), up(rec.h_start), None if suffix is None else up(suffix), src_seq=seq,
+                         src_offset=rec.old_start_pos, k_is_pre_rope=rec.k_is_pre_rope,
+                         seg_old_start_pos=rec.old_start_pos, dst_seq=0, n_cached=at, no_logits=not last)
+        forced = torch.from_numpy(want.sel_idx[i]).cuda() if bf16 else None      # bf16: same rows on both sides
+        plan = rc.Plan(l_start, l_det, l_end, [k], forced)
+        ws = rc.alloc_workspace(rc.rc_reuse_workspace_bytes(model, [req], plan))
+        sel = torch.full((k,), -1, dtype=torch.int32, device="cuda")
+        rc.rc_reuse(model, [req], plan, src, dst, logits, sel, None, ws)
+        torch.cuda.synchronize()
+        sels.append(sel.cpu().numpy())
+        at += xn.shape[0] + S
+    tol = TOL[sh.dtype]
+    for i in range(2):
+        if not bf16 and selection_margin(want.score[i], (k1, k2)[i]) > MARGIN:
+            assert np.array_equal(sels[i], want.sel_idx[i])
+    for l in range(sh.n_layers):
+        assert rel_err(to_np(dst.read("k", l, 0, T)), want.k_cache[l]) <= tol, l
+        assert rel_err(to_np(dst.read("v", l, 0, T)), want.v_cache[l]) <= tol, l
+    assert rel_err(to_np(logits)[0], want.logits) <= tol
+    model.close()
