@@ -1,9 +1,13 @@
-"""Parity at the benchmark's full size (Mistral-7B shape, 1024 new + 4096 reused tokens, 15 % budget in
-layers 8-24, contiguous cache): the same launch configuration bench.py times.
+"""Parity at the benchmark configurations' full sizes, in the launch configuration bench.py uses:
+  mistral7b_4k       1024 new + 4096 reused tokens, 15 % in layers 8-24 (the timed configuration)
+  llama8b_16k_b10    2048 + 16384 tokens, 10 %
+  mistral7b_ragged16 16 ragged requests, paged cache with 16-token blocks
+  qwen32b_32k        32B shape (64 layers, group 5), 4096 + 32768 tokens, 10 %
 
-A full float64 oracle run is out of reach here (about 85 TFLOP), so the checks are
-  * sampled outputs the oracle computes one by one from the stage's own inputs (re-rotated keys, dense-layer
-    K/V rows, deviation scores, sparse-layer K/V rows), and the complete top-k from the library's scores;
+A full float64 oracle run is out of reach at these sizes, so the checks are
+  * sampled outputs the oracle computes one by one from the stage's own inputs (re-rotated keys, copied values,
+    dense-layer K/V rows, deviation scores, a selected token's sparse-layer rows), and the complete top-k
+    from the library's scores;
   * properties that hold at any size (reused rows outside the selection are untouched; the same prefix on
     both sides gives zero scores and reproduces a full prefill).
 Weights and hidden states are drawn on the device (seeded) and copied to the host where the oracle needs them.
@@ -13,7 +17,7 @@ import pytest
 import torch
 
 from oracle import relay_oracle as R
-from synth import WORKLOADS, budget_to_k
+from synth import WORKLOADS, budget_to_k, make_block_table, ragged_lengths
 from tests.harness import TOL, rel_err, to_np
 
 pytestmark = pytest.mark.gpu
@@ -21,15 +25,10 @@ pytestmark = pytest.mark.gpu
 SEED = 20260313
 
 
-def _model(rc, w):
-    import bench
-    return bench.device_model(rc, torch, w, SEED)
-
-
 def _layer_np(model, l):
-    """One layer's weights as float32 numpy (the oracle up-casts to float64)."""
+    """One layer's weights as float64 numpy."""
     layers = model._keep[0]
-    return {k: to_np(v) for k, v in layers[l].items()}
+    return {k: to_np(v).astype(np.float64) for k, v in layers[l].items()}
 
 
 class _OneLayer:
@@ -42,122 +41,160 @@ class _OneLayer:
         self.layers = layers
 
 
-@pytest.fixture(scope="module")
-def run():
+@pytest.fixture(scope="module", params=["mistral7b_4k", "llama8b_16k_b10", "mistral7b_ragged16", "qwen32b_32k"])
+def run(request):
     from paper_2603_13289_amd import binding as rc
-    w = WORKLOADS["mistral7b_4k"]
+    import bench
+    w = WORKLOADS[request.param]
     sh = w.shape
-    P, S, A = w.n_prefix, w.n_seg, w.n_alt
-    k = budget_to_k(S, w.budget_pct)
+    lens = ragged_lengths(w)
+    n_req = len(lens)
+    ks = [budget_to_k(S, w.budget_pct) for _, S, _ in lens]
     dt = rc.rc_dtype_of(sh.dtype)
     td = rc.torch_dtype(dt)
-    model, g = _model(rc, w)
+    model, g = bench.device_model(rc, torch, w, SEED)
 
     def hidden(n):
         return torch.randn((n, sh.d_model), generator=g, device="cuda", dtype=torch.float32).to(td)
 
-    x_alt, x_seg, x_prefix = hidden(A), hidden(S), hidden(P)
-    old = rc.PagedKV.contiguous(sh.n_layers, 1, A + S, sh.n_kv_heads, sh.head_dim, dt)
-    old_pre = rc.PagedKV.contiguous(sh.n_layers, 1, A + S, sh.n_kv_heads, sh.head_dim, dt)
-    h_cap = torch.zeros((A + S, sh.d_model), dtype=td, device="cuda")
-    lg = torch.zeros((1, sh.vocab), dtype=torch.float32, device="cuda")
-    ws_p = rc.alloc_workspace(rc.rc_prefill_workspace_bytes(model, [P + S]))
-    rc.rc_prefill(model, [torch.cat([x_alt, x_seg]).contiguous()], [0], old, lg, ws_p, k_pre=old_pre,
-                  capture_layer=w.l_start, h_capture=[h_cap])
+    def cache(seq_lens, seed):
+        if w.block_size > 0:
+            tab, nb = make_block_table(seq_lens, w.block_size, seed=seed)
+            return rc.PagedKV(sh.n_layers, nb, w.block_size, sh.n_kv_heads, sh.head_dim, dt, tab)
+        return rc.PagedKV.contiguous(sh.n_layers, len(seq_lens), max(seq_lens), sh.n_kv_heads, sh.head_dim, dt)
+
+    x_alt = [hidden(a) for _, _, a in lens]
+    x_seg = [hidden(s) for _, s, _ in lens]
+    x_prefix = [hidden(p) for p, _, _ in lens]
+    old_lens = [a + s for _, s, a in lens]
+    new_lens = [p + s for p, s, _ in lens]
+    old, old_pre = cache(old_lens, 1), cache(old_lens, 1)
+    h_cap = [torch.zeros((n, sh.d_model), dtype=td, device="cuda") for n in old_lens]
+    lg = torch.zeros((n_req, sh.vocab), dtype=torch.float32, device="cuda")
+    ws_p = rc.alloc_workspace(max(rc.rc_prefill_workspace_bytes(model, old_lens),
+                                  rc.rc_prefill_workspace_bytes(model, new_lens)))
+    rc.rc_prefill(model, [torch.cat([x_alt[b], x_seg[b]]).contiguous() for b in range(n_req)], list(range(n_req)),
+                  old, lg, ws_p, k_pre=old_pre, capture_layer=w.l_start, h_capture=h_cap)
     record = rc.PagedKV.from_pools(old_pre.k, old.v, old.block_table, dt)
-    h_start = h_cap[A:].contiguous()
-    dst = rc.PagedKV.contiguous(sh.n_layers, 1, P + S, sh.n_kv_heads, sh.head_dim, dt)
-    req = rc.Request(x_prefix, h_start, None, src_seq=0, src_offset=A, k_is_pre_rope=True, seg_old_start_pos=A)
-    plan = rc.Plan(w.l_start, w.l_det, w.l_end, [k])
-    ws = rc.alloc_workspace(rc.rc_reuse_workspace_bytes(model, [req], plan))
-    logits = torch.zeros((1, sh.vocab), dtype=torch.float32, device="cuda")
-    sel = torch.zeros(k, dtype=torch.int32, device="cuda")
-    scores = torch.zeros(S, dtype=torch.float32, device="cuda")
-    rc.rc_reuse(model, [req], plan, record, dst, logits, sel, scores, ws)
+    h_start = [h_cap[b][lens[b][2]:].contiguous() for b in range(n_req)]
+    dst = cache(new_lens, 2)
+    reqs = [rc.Request(x_prefix[b], h_start[b], None, src_seq=b, src_offset=lens[b][2], k_is_pre_rope=True,
+                       seg_old_start_pos=lens[b][2], dst_seq=b) for b in range(n_req)]
+    plan = rc.Plan(w.l_start, w.l_det, w.l_end, ks)
+    ws = rc.alloc_workspace(rc.rc_reuse_workspace_bytes(model, reqs, plan))
+    logits = torch.zeros((n_req, sh.vocab), dtype=torch.float32, device="cuda")
+    sel = torch.zeros(sum(ks), dtype=torch.int32, device="cuda")
+    scores = torch.zeros(sum(s for _, s, _ in lens), dtype=torch.float32, device="cuda")
+    rc.rc_reuse(model, reqs, plan, record, dst, logits, sel, scores, ws)
     torch.cuda.synchronize()
-    return dict(rc=rc, w=w, model=model, P=P, S=S, A=A, k=k, record=record, dst=dst, h_start=h_start,
-                x_prefix=x_prefix, x_seg=x_seg, sel=sel.cpu().numpy(), scores=scores.cpu().numpy(),
-                logits=to_np(logits)[0], ws_p=ws_p, ws=ws, plan=plan, dt=dt)
+    sel_h, sc_h = sel.cpu().numpy(), scores.cpu().numpy()
+    sel_b, sc_b, ko, so = [], [], 0, 0
+    for b, (p, s, a) in enumerate(lens):
+        sel_b.append(sel_h[ko:ko + ks[b]])
+        sc_b.append(sc_h[so:so + s])
+        ko += ks[b]
+        so += s
+    # requests looked at in detail: the first, and (ragged batches) the one with the longest segment
+    probe = sorted({0, int(np.argmax([s for _, s, _ in lens]))})
+    yield dict(rc=rc, w=w, model=model, lens=lens, ks=ks, record=record, dst=dst, h_start=h_start, x_prefix=x_prefix,
+               x_seg=x_seg, sel=sel_b, scores=sc_b, ws_p=ws_p, ws=ws, plan=plan, dt=dt, probe=probe, cache=cache)
+    model.close()
 
 
 def test_topk_of_full_size_scores_is_bit_exact(run):
-    want = R.topk_select(run["scores"], run["k"])
-    assert run["k"] == 614 and np.array_equal(run["sel"], want)
-    assert np.all(np.diff(run["sel"]) > 0)
-    assert np.all(run["scores"] > -1e-6) and np.max(run["scores"]) > 1e-3     # different prefixes do deviate
+    for b, (p, s, a) in enumerate(run["lens"]):
+        want = R.topk_select(run["scores"][b], run["ks"][b])
+        assert np.array_equal(run["sel"][b], want), b
+        assert np.all(np.diff(run["sel"][b]) > 0)
+        assert np.all(run["scores"][b] > -1e-6) and np.max(run["scores"][b]) > 1e-4     # different prefixes do deviate
+    if run["w"].name == "mistral7b_4k":
+        assert run["ks"] == [614]
 
 
 def test_rerotated_keys_and_copied_values_sampled(run):
-    w, P, S, A = run["w"], run["P"], run["S"], run["A"]
+    w = run["w"]
     rng = np.random.default_rng(1)
-    sel = set(run["sel"].tolist()) | {S - 1}
-    for l in (0, 5, w.l_det, w.l_end, w.shape.n_layers - 1):
-        js = rng.choice(S - 1, size=24, replace=False)
-        if w.l_det <= l <= w.l_end:
-            js = np.array([j for j in js if j not in sel])          # rows the selection left alone
-        src_k = to_np(run["record"].read("k", l, 0, S, start=A))[js]
-        src_v = to_np(run["record"].read("v", l, 0, S, start=A))[js]
-        got_k = to_np(run["dst"].read("k", l, 0, S, start=P))[js]
-        got_v = to_np(run["dst"].read("v", l, 0, S, start=P))[js]
-        want_k = R.rope_rotate(src_k, P + js, w.shape.rope_base)
-        assert rel_err(got_k, want_k) <= 4e-3            # one bf16 rounding of the rotated key
-        assert np.array_equal(got_v, src_v)
+    for b in run["probe"]:
+        P, S, A = run["lens"][b]
+        sel = set(run["sel"][b].tolist()) | {S - 1}
+        for l in (0, w.l_start - 1, w.l_det, w.l_end, w.shape.n_layers - 1):
+            js = rng.choice(S - 1, size=24, replace=False)
+            if w.l_det <= l <= w.l_end:
+                js = np.array([j for j in js if j not in sel])          # rows the selection left alone
+            js = np.sort(js)
+            src_k = np.concatenate([to_np(run["record"].read("k", l, b, 1, start=A + int(j))) for j in js])
+            src_v = np.concatenate([to_np(run["record"].read("v", l, b, 1, start=A + int(j))) for j in js])
+            got_k = np.concatenate([to_np(run["dst"].read("k", l, b, 1, start=P + int(j))) for j in js])
+            got_v = np.concatenate([to_np(run["dst"].read("v", l, b, 1, start=P + int(j))) for j in js])
+            want_k = R.rope_rotate(src_k, P + js, w.shape.rope_base)
+            assert rel_err(got_k, want_k) <= 4e-3            # one bf16 rounding of the rotated key
+            assert np.array_equal(got_v, src_v)
 
 
-def _dense_layer_token(run, lw, j):
-    """Oracle, one token: hidden state leaving the dense layer l_start for segment token j, computed from
-    the cached h_start row and the library's own layer-l_start cache rows (the stage's inputs)."""
-    w, P = run["w"], run["P"]
+def _dense_layer_token(run, lw, b, j):
+    """Oracle, one token: hidden state leaving the dense layer l_start for segment token j of request b,
+    computed from the cached h_start row and the library's own layer-l_start cache rows (the stage's inputs)."""
+    w = run["w"]
+    P = run["lens"][b][0]
     sh = w.shape
     l = w.l_start
     om = _OneLayer(sh, {l: lw})
     pos = P + j
-    kc = to_np(run["dst"].read("k", l, 0, pos + 1)).astype(np.float64)
-    vc = to_np(run["dst"].read("v", l, 0, pos + 1)).astype(np.float64)
-    h = to_np(run["h_start"][j:j + 1]).astype(np.float64)
+    kc = to_np(run["dst"].read("k", l, b, pos + 1)).astype(np.float64)
+    vc = to_np(run["dst"].read("v", l, b, pos + 1)).astype(np.float64)
+    h = to_np(run["h_start"][b][j:j + 1]).astype(np.float64)
     k_before, v_before = kc[pos].copy(), vc[pos].copy()
     h_out = R.decoder_layer(om, l, h, np.array([pos]), kc, vc)      # writes the oracle's own K/V row at pos
     return h_out, kc[pos], vc[pos], k_before, v_before
 
 
 def test_dense_layer_rows_and_scores_sampled(run):
-    w, P, S = run["w"], run["P"], run["S"]
+    w = run["w"]
     sh = w.shape
     l0, l1 = w.l_start, w.l_det
     lw0, lw1 = _layer_np(run["model"], l0), _layer_np(run["model"], l1)
-    tokens = [0, 1, int(run["sel"][len(run["sel"]) // 2]), S - 2]
-    for j in tokens:
-        h_out, k_row, v_row, k_gpu, v_gpu = _dense_layer_token(run, lw0, j)
-        assert rel_err(k_gpu, k_row) <= TOL["bf16"] and rel_err(v_gpu, v_row) <= TOL["bf16"]
-        # Eq. (1) at l_det from this token's fresh value vs the reused value the earlier agent stored
-        v_fresh = R.linear(R.rmsnorm(h_out, lw1["g_attn"], sh.rms_eps), lw1["wv"]).reshape(1, sh.n_kv_heads, sh.head_dim)
-        v_reuse = to_np(run["record"].read("v", l1, 0, 1, start=run["A"] + j)).astype(np.float64)
-        want = float(R.vdev_score(v_reuse, v_fresh)[0])
-        got = float(run["scores"][j])
-        assert abs(got - want) <= 2e-2 * max(want, 1e-3) + 2e-4, (j, got, want)
-        if j in set(run["sel"].tolist()):
-            # a selected token's layer-l_det K/V rows are recomputed from that hidden state
-            kq = R.rope_rotate(R.linear(R.rmsnorm(h_out, lw1["g_attn"], sh.rms_eps), lw1["wk"]).reshape(1, sh.n_kv_heads, sh.head_dim),
-                               np.array([P + j]), sh.rope_base)[0]
-            assert rel_err(to_np(run["dst"].read("k", l1, 0, 1, start=P + j))[0], kq) <= TOL["bf16"]
-            assert rel_err(to_np(run["dst"].read("v", l1, 0, 1, start=P + j))[0], v_fresh[0]) <= TOL["bf16"]
+    big = sh.d_model > 4096 or len(run["lens"]) > 1
+    for b in run["probe"]:
+        P, S, A = run["lens"][b]
+        sel = run["sel"][b]
+        tokens = [1, int(sel[len(sel) // 2])] if big else [0, 1, int(sel[len(sel) // 2]), S - 2]
+        for j in tokens:
+            h_out, k_row, v_row, k_gpu, v_gpu = _dense_layer_token(run, lw0, b, j)
+            assert rel_err(k_gpu, k_row) <= TOL["bf16"] and rel_err(v_gpu, v_row) <= TOL["bf16"]
+            # Eq. (1) at l_det from this token's fresh value vs the reused value the earlier agent stored
+            a1 = R.rmsnorm(h_out, lw1["g_attn"], sh.rms_eps)
+            v_fresh = R.linear(a1, lw1["wv"]).reshape(1, sh.n_kv_heads, sh.head_dim)
+            v_reuse = to_np(run["record"].read("v", l1, b, 1, start=A + j)).astype(np.float64)
+            want = float(R.vdev_score(v_reuse, v_fresh)[0])
+            got = float(run["scores"][b][j])
+            assert abs(got - want) <= 2e-2 * max(want, 1e-3) + 2e-4, (b, j, got, want)
+            if j in set(sel.tolist()):
+                # a selected token's layer-l_det K/V rows are recomputed from that hidden state
+                kq = R.rope_rotate(R.linear(a1, lw1["wk"]).reshape(1, sh.n_kv_heads, sh.head_dim), np.array([P + j]),
+                                   sh.rope_base)[0]
+                assert rel_err(to_np(run["dst"].read("k", l1, b, 1, start=P + j))[0], kq) <= TOL["bf16"]
+                assert rel_err(to_np(run["dst"].read("v", l1, b, 1, start=P + j))[0], v_fresh[0]) <= TOL["bf16"]
 
 
 def test_same_prefix_reproduces_full_prefill_at_full_size(run):
     """If the earlier agent saw the same prefix, the record is already right: scores vanish and the corrected
     cache and logits equal a full prefill of [prefix ; segment] (both computed by the library)."""
     rc, w, model = run["rc"], run["w"], run["model"]
-    sh, P, S, k, dt = w.shape, run["P"], run["S"], run["k"], run["dt"]
+    if w.name not in ("mistral7b_4k", "llama8b_16k_b10"):
+        pytest.skip("checked on the two single-request 7B/8B configurations")
+    sh, dt = w.shape, run["dt"]
+    P, S, _ = run["lens"][0]
+    k = run["ks"][0]
     td = rc.torch_dtype(dt)
     full = rc.PagedKV.contiguous(sh.n_layers, 1, P + S, sh.n_kv_heads, sh.head_dim, dt)
     full_pre = rc.PagedKV.contiguous(sh.n_layers, 1, P + S, sh.n_kv_heads, sh.head_dim, dt)
     h_cap = torch.zeros((P + S, sh.d_model), dtype=td, device="cuda")
     lg_full = torch.zeros((1, sh.vocab), dtype=torch.float32, device="cuda")
-    rc.rc_prefill(model, [torch.cat([run["x_prefix"], run["x_seg"]]).contiguous()], [0], full, lg_full, run["ws_p"],
+    rc.rc_prefill(model, [torch.cat([run["x_prefix"][0], run["x_seg"][0]]).contiguous()], [0], full, lg_full, run["ws_p"],
                   k_pre=full_pre, capture_layer=w.l_start, h_capture=[h_cap])
     record = rc.PagedKV.from_pools(full_pre.k, full.v, full.block_table, dt)
     dst = rc.PagedKV.contiguous(sh.n_layers, 1, P + S, sh.n_kv_heads, sh.head_dim, dt)
-    req = rc.Request(run["x_prefix"], h_cap[P:].contiguous(), None, src_seq=0, src_offset=P, k_is_pre_rope=True,
+    req = rc.Request(run["x_prefix"][0], h_cap[P:].contiguous(), None, src_seq=0, src_offset=P, k_is_pre_rope=True,
                      seg_old_start_pos=P)
     logits = torch.zeros((1, sh.vocab), dtype=torch.float32, device="cuda")
     sel = torch.zeros(k, dtype=torch.int32, device="cuda")
