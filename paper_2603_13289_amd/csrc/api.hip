@@ -365,20 +365,22 @@ struct Job {
 template <typename T>
 hipError_t attention_dispatch(const T* q, const int* row_pos, const int* row_req, const ReqTable* table,
                               int total_rows, int total_tiles, const T* k_pool, const T* v_pool, KvGeom g,
-                              int n_q_heads, T* out, AttnSplit sp, float* part, hipStream_t st);
+                              int n_q_heads, T* out, AttnSplit sp, float* part, hipStream_t st, float* scores,
+                              int scores_len);
 template <>
 hipError_t attention_dispatch<float>(const float* q, const int* row_pos, const int* row_req, const ReqTable* table,
                                      int total_rows, int total_tiles, const float* k_pool, const float* v_pool,
-                                     KvGeom g, int n_q_heads, float* out, AttnSplit, float*, hipStream_t st) {
+                                     KvGeom g, int n_q_heads, float* out, AttnSplit, float*, hipStream_t st, float*, int) {
   return launch_attention<float>(q, row_pos, row_req, table, 0, total_rows, total_tiles, k_pool, v_pool, g,
                                  n_q_heads, out, st);
 }
 template <>
 hipError_t attention_dispatch<bf16>(const bf16* q, const int* row_pos, const int* row_req, const ReqTable* table,
                                     int total_rows, int total_tiles, const bf16* k_pool, const bf16* v_pool,
-                                    KvGeom g, int n_q_heads, bf16* out, AttnSplit sp, float* part, hipStream_t st) {
+                                    KvGeom g, int n_q_heads, bf16* out, AttnSplit sp, float* part, hipStream_t st,
+                                    float* scores, int scores_len) {
   return launch_attention_bf16(q, row_pos, row_req, table, 0, total_rows, total_tiles, k_pool, v_pool, g, n_q_heads,
-                               out, sp, part, st);
+                               out, sp, part, st, scores, scores_len);
 }
 
 template <typename T>
@@ -522,13 +524,20 @@ rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
     RC_LAUNCH(PC_ROPE_SCATTER, launch_rope_scatter<T>(w.qkv, rows, w.row_pos, w.row_req, w.tables + cur, w.rope_tab, (T*)w.q,
                                   (T*)job.dst->k_pool[l], (T*)job.dst->v_pool[l],
                                   job.k_pre_pool ? (T*)job.k_pre_pool[l] : nullptr, gd, d.n_q_heads, st));
-    if (job.any_inf)
-      RC_LAUNCH(PC_INFLUENCE, launch_influence_accumulate<T>((const T*)w.q, w.row_pos, w.row_req, w.tables + cur, rows,
-                                                             (const T*)job.dst->k_pool[l], gd, d.n_q_heads, job.max_pos,
-                                                             job.inf, w.inf_scratch, st));
+    // influence accumulation (decoding): the bf16 matrix-core attention kernel hands out its scores; the other
+    // paths compute them in a pass of their own
+    const bool scores_from_attention = job.any_inf && d.dtype == RC_BF16 && d.n_q_heads / d.n_kv_heads <= 8;
+    if (job.any_inf && !scores_from_attention)
+      RC_LAUNCH(PC_INFLUENCE, launch_influence_scores<T>((const T*)w.q, w.row_pos, w.row_req, w.tables + cur, rows,
+                                                         (const T*)job.dst->k_pool[l], gd, d.n_q_heads, job.max_pos,
+                                                         w.inf_scratch, st));
     RC_LAUNCH(PC_ATTENTION, attention_dispatch<T>((const T*)w.q, w.row_pos, w.row_req, w.tables + cur, rows,
                                  tabs[cur].total_tiles, (const T*)job.dst->k_pool[l],
-                                 (const T*)job.dst->v_pool[l], gd, d.n_q_heads, (T*)w.o, splits[cur], w.attn_part, st));
+                                 (const T*)job.dst->v_pool[l], gd, d.n_q_heads, (T*)w.o, splits[cur], w.attn_part, st,
+                                 scores_from_attention ? w.inf_scratch : nullptr, job.max_pos));
+    if (job.any_inf)
+      RC_LAUNCH(PC_INFLUENCE, launch_influence_finish(w.row_pos, w.row_req, rows, d.n_q_heads, job.max_pos, job.inf,
+                                                      w.inf_scratch, st));
     RC_LAUNCH(PC_GEMM_O, gemm_any<T>((const T*)w.o, (const T*)lw.wo, nullptr, h, rows, D, nq, D, EPI_ADD_F32, w.gemm_part, st));
     RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(h, (const T*)lw.g_ffn, (T*)w.a, rows, D, d.rms_eps, st));
     RC_LAUNCH(PC_GEMM_GATE_UP, gemm_any<T>((const T*)w.a, (const T*)lw.w_gate, (const T*)lw.w_up, w.act, rows, F, D, F, EPI_SWIGLU_T, w.gemm_part, st));

@@ -32,12 +32,15 @@ static constexpr int DH = 128;
 static constexpr int KROW = DH * 2 + 16;   // bytes between K rows in LDS
 static constexpr int VROW = BKV * 2 + 16;  // bytes between V^T rows in LDS
 
-template <int G>
+// SCORES: additionally write every visible score q.k / sqrt(dh) of every valid row to
+// scores[(row * n_q_heads + head) * scores_len + key] (the decode-side influence accumulation reads them).
+template <int G, bool SCORES>
 __global__ void __launch_bounds__(64 * G, (G <= 4 ? 2 : 1))
 attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, const ReqTable* __restrict__ table,
                  int fixed_seq, int total_rows, int total_tiles, const bf16* __restrict__ k_pool,
                  const bf16* __restrict__ v_pool, KvGeom g, bf16* __restrict__ out, AttnSplit sp,
-                 float* __restrict__ part_o, float2* __restrict__ part_ml) {
+                 float* __restrict__ part_o, float2* __restrict__ part_ml, float* __restrict__ scores,
+                 int scores_len) {
   constexpr int NT = 64 * G;
   // K rows are 256 + 16 bytes, V^T rows 128 + 16 bytes apart.  With 64 banks of 4 bytes, the 16 lanes
   // that fetch the same 16-byte chunk of 16 consecutive rows then hit every bank exactly once, and every
@@ -209,6 +212,19 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
           if (key > my_pos) acc_s[b][e] = -INFINITY;
         }
     }
+    if (SCORES) {
+      if (q_ok) {
+        float* srow = scores + ((size_t)my_row * n_q_heads + head) * scores_len;
+        const float inv_sqrt = 1.0f / sqrtf((float)DH);
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int key = kv0 + 32 * b + 8 * (e >> 2) + 4 * half + (e & 3);
+            if (key <= my_pos) srow[key] = acc_s[b][e] * inv_sqrt;
+          }
+      }
+    }
     float mx = acc_s[0][0];
 #pragma unroll
     for (int b = 0; b < 2; ++b)
@@ -343,30 +359,35 @@ size_t attention_partial_floats(int total_slots, int n_q_heads) {
 template <int G>
 static hipError_t launch_g(const bf16* q, const int* row_pos, const ReqTable* table, int fixed_seq, int total_rows,
                            int total_tiles, const bf16* k_pool, const bf16* v_pool, KvGeom g, bf16* out,
-                           AttnSplit sp, float* part, hipStream_t st) {
+                           AttnSplit sp, float* part, float* scores, int scores_len, hipStream_t st) {
   dim3 grid((unsigned)(total_tiles * sp.n_chunks), (unsigned)g.n_kv_heads);
   float* part_o = part;
   float2* part_ml = reinterpret_cast<float2*>(part + (size_t)sp.total_slots * g.n_kv_heads * G * BQ * DH);
-  attn_mfma_kernel<G><<<grid, 64 * G, 0, st>>>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool, v_pool,
-                                               g, out, sp, part_o, part_ml);
+  if (scores)
+    attn_mfma_kernel<G, true><<<grid, 64 * G, 0, st>>>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool,
+                                                       v_pool, g, out, sp, part_o, part_ml, scores, scores_len);
+  else
+    attn_mfma_kernel<G, false><<<grid, 64 * G, 0, st>>>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool,
+                                                        v_pool, g, out, sp, part_o, part_ml, nullptr, 0);
   return hipGetLastError();
 }
 
 hipError_t launch_attention_bf16(const bf16* q, const int* row_pos, const int* row_req, const ReqTable* table,
                                  int fixed_seq, int total_rows, int total_tiles, const bf16* k_pool,
                                  const bf16* v_pool, KvGeom g, int n_q_heads, bf16* out, AttnSplit sp, float* part,
-                                 hipStream_t st) {
+                                 hipStream_t st, float* scores, int scores_len) {
   if (total_rows <= 0) return hipSuccess;
   const int G = n_q_heads / g.n_kv_heads;
   if (!part || sp.total_slots <= 0) sp = attention_no_split();
   hipError_t e;
   switch (G) {
 #define RC_ATTN_CASE(GG) \
-    case GG: e = launch_g<GG>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool, v_pool, g, out, sp, part, st); break;
+    case GG: e = launch_g<GG>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool, v_pool, g, out, sp, part, scores, scores_len, st); break;
     RC_ATTN_CASE(1) RC_ATTN_CASE(2) RC_ATTN_CASE(3) RC_ATTN_CASE(4)
     RC_ATTN_CASE(5) RC_ATTN_CASE(6) RC_ATTN_CASE(7) RC_ATTN_CASE(8)
 #undef RC_ATTN_CASE
     default:  // wider groups: one wavefront per (row, head) on the vector ALUs
+      if (scores) return hipErrorInvalidValue;
       return launch_attention_simt<bf16>(q, row_pos, row_req, table, fixed_seq, total_rows, k_pool, v_pool, g,
                                          n_q_heads, out, st);
   }

@@ -169,6 +169,11 @@ template <typename T>
 hipError_t launch_gemm(const T* a, const T* w, const T* w2, void* c, int m, int n, int k, int ldc,
                        GemmEpilogue epi, hipStream_t st);
 
+// few-row variant (M <= 32, weights streamed once); columns < ns1 come from w, < ns2 from w2, the rest from w3
+bool gemm_skinny_applies(int m, int n, int k, int ns1, int ns2);
+hipError_t launch_gemm_skinny_bf16(const bf16* a, const bf16* w, const bf16* w2, const bf16* w3, int ns1, int ns2,
+                                   void* c, int m, int n, int k, int ldc, GemmEpilogue epi, hipStream_t st);
+
 // C[M][nq + 2 nkv] (float) = A * [wq; wk; wv]^T
 template <typename T>
 hipError_t launch_gemm_qkv(const T* a, const T* wq, int nq, const T* wk, const T* wv, int nkv, float* c, int m,
@@ -215,7 +220,7 @@ size_t attention_partial_floats(int total_slots, int n_q_heads);
 hipError_t launch_attention_bf16(const bf16* q, const int* row_pos, const int* row_req, const ReqTable* table,
                                  int fixed_seq, int total_rows, int total_tiles, const bf16* k_pool,
                                  const bf16* v_pool, KvGeom g, int n_q_heads, bf16* out, AttnSplit sp, float* part,
-                                 hipStream_t st);
+                                 hipStream_t st, float* scores = nullptr, int scores_len = 0);
 
 template <typename T>
 hipError_t launch_vdev_score(const T* v_fresh, int fresh_row_stride, const T* v_pool, KvGeom g,
@@ -227,10 +232,14 @@ hipError_t launch_threshold_select(const float* score, int n, float tau, int* id
 // per-request influence vectors (Eq. 6), passed to the accumulation kernel by value; nullptr: not tracked
 struct InfluencePtrs { float* s_inf[RC_MAX_REQ]; };
 size_t influence_scratch_floats(int n_rows, int n_q_heads, int max_len);
+// scratch holds the scores [rows][Hq][max_len]; they are either written by launch_influence_scores or by the
+// bf16 attention kernel's score output, then turned into weights and added by launch_influence_finish
 template <typename T>
-hipError_t launch_influence_accumulate(const T* q, const int* row_pos, const int* row_req, const ReqTable* table,
-                                       int n_rows, const T* k_pool, KvGeom g, int n_q_heads, int max_len,
-                                       const InfluencePtrs& out, float* scratch, hipStream_t st);
+hipError_t launch_influence_scores(const T* q, const int* row_pos, const int* row_req, const ReqTable* table,
+                                   int n_rows, const T* k_pool, KvGeom g, int n_q_heads, int max_len, float* scratch,
+                                   hipStream_t st);
+hipError_t launch_influence_finish(const int* row_pos, const int* row_req, int n_rows, int n_q_heads, int max_len,
+                                   const InfluencePtrs& out, float* scratch, hipStream_t st);
 hipError_t launch_final_select(const float* s_dev, const float* s_inf, int n, float tau_dev, float tau_inf, int k_suf,
                                int* idx_out, int* count_out, hipStream_t st);
 hipError_t launch_copy_i32(const int* src, int* dst, int n, hipStream_t st);

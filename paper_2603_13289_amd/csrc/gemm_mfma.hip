@@ -549,6 +549,8 @@ static hipError_t dispatch(const bf16* a, const bf16* w, const bf16* w2, const b
                            int m, int n, int k, int ldc, GemmEpilogue epi, float* partial, hipStream_t st) {
   if (m <= 0 || n <= 0) return hipSuccess;
   int tile = g_gemm_tile;
+  if (tile == 0 && gemm_skinny_applies(m, n, k, ns1, ns2))
+    return launch_gemm_skinny_bf16(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);
   if (tile == 0) {
     if (k % BK != 0) {
       tile = 3;

@@ -13,44 +13,69 @@ namespace rc {
 
 static constexpr int kInfThreads = 256;
 
-// grid: (key chunks of 256, kv heads, rows); thread = one key position
+// grid: (key chunks of kInfKeys, kv heads, rows).  dh / VEC consecutive lanes share one key row (each a
+// 16-byte piece, so a row is read with one coalesced access), keep the matching pieces of the G query heads
+// in registers, and add their partial dot products up with shuffles.  Key rows are requested kInfAhead
+// passes at a time before the first of them is used.
+static constexpr int kInfKeys = 512;
+static constexpr int kInfAhead = 8;
+
 template <typename T>
 __global__ void __launch_bounds__(kInfThreads)
 influence_scores_kernel(const T* __restrict__ q, const int* __restrict__ row_pos, const int* __restrict__ row_req,
                         const ReqTable* __restrict__ table, const T* __restrict__ k_pool, KvGeom g, int n_q_heads,
                         int max_len, float* __restrict__ scores) {
-  extern __shared__ float q_lds[];   // [G][dh]
+  constexpr int VEC = Vec16<T>::N;
   const int row = blockIdx.z, hk = blockIdx.y;
   const int G = n_q_heads / g.n_kv_heads, dh = g.head_dim;
   const int pos = row_pos[row];
-  const int j0 = blockIdx.x * kInfThreads;
+  const int j0 = blockIdx.x * kInfKeys;
   if (j0 > pos) return;
+  const int lpr = dh / VEC;                  // lanes per key row: 16 or 32
+  const int sub = threadIdx.x % lpr;         // my 16-byte piece of the row
+  const int keys_per_pass = kInfThreads / lpr;
   const float scale = rsqrtf((float)dh);
-  for (int i = threadIdx.x; i < G * dh; i += kInfThreads)
-    q_lds[i] = to_f32(q[((size_t)row * n_q_heads + (size_t)hk * G) * dh + i]) * scale;
-  __syncthreads();
-  const int j = j0 + threadIdx.x;
-  if (j > pos) return;
   const int seq = table->r[row_req[row]].dst_seq;
-  const T* kr = k_pool + kv_row_offset(g, seq, j, hk);
-  constexpr int VEC = Vec16<T>::N;
-  float acc[8];
+  const int j_end = min(j0 + kInfKeys, pos + 1);
+  const bool contig = g.max_blocks == 1;     // one block per sequence: rows are a linear function of the position
+  const T* kbase = contig ? k_pool + kv_row_offset(g, seq, 0, hk) + sub * VEC : nullptr;
+  float qv[8][VEC];
 #pragma unroll
-  for (int gq = 0; gq < 8; ++gq) acc[gq] = 0.f;
-  for (int c = 0; c < dh; c += VEC) {
-    float kv[VEC];
-    Vec16<T>::load(kr + c, kv);
+  for (int gq = 0; gq < 8; ++gq) {
+    if (gq < G) {
+      Vec16<T>::load(q + ((size_t)row * n_q_heads + (size_t)hk * G + gq) * dh + sub * VEC, qv[gq]);
 #pragma unroll
-    for (int gq = 0; gq < 8; ++gq) {
-      if (gq < G) {
+      for (int e = 0; e < VEC; ++e) qv[gq][e] *= scale;
+    }
+  }
+  float* srow = scores + ((size_t)row * n_q_heads + (size_t)hk * G) * max_len;
+  for (int jb = j0 + threadIdx.x / lpr; jb < j_end + keys_per_pass; jb += kInfAhead * keys_per_pass) {
+    if (jb - (int)(threadIdx.x / lpr) >= j_end) break;       // uniform: the whole pass group is past the end
+    float kv[kInfAhead][VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[gq] = fmaf(q_lds[gq * dh + c + e], kv[e], acc[gq]);
+    for (int p = 0; p < kInfAhead; ++p) {
+      const int j = jb + p * keys_per_pass;
+      if (j < j_end) Vec16<T>::load(contig ? kbase + (size_t)j * dh : k_pool + kv_row_offset(g, seq, j, hk) + sub * VEC, kv[p]);
+      else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) kv[p][e] = 0.f;
+      }
+    }
+#pragma unroll
+    for (int p = 0; p < kInfAhead; ++p) {
+      const int j = jb + p * keys_per_pass;
+#pragma unroll
+      for (int gq = 0; gq < 8; ++gq) {
+        if (gq < G) {
+          float acc = 0.f;
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) acc = fmaf(qv[gq][e], kv[p][e], acc);
+          for (int o = lpr >> 1; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+          if (j < j_end && sub == 0) srow[(size_t)gq * max_len + j] = acc;
+        }
       }
     }
   }
-#pragma unroll
-  for (int gq = 0; gq < 8; ++gq)
-    if (gq < G) scores[((size_t)row * n_q_heads + (size_t)hk * G + gq) * max_len + j] = acc[gq];
 }
 
 // grid: (query heads, rows)
@@ -101,32 +126,34 @@ size_t influence_scratch_floats(int n_rows, int n_q_heads, int max_len) {
 }
 
 template <typename T>
-hipError_t launch_influence_accumulate(const T* q, const int* row_pos, const int* row_req, const ReqTable* table,
-                                       int n_rows, const T* k_pool, KvGeom g, int n_q_heads, int max_len,
-                                       const InfluencePtrs& out, float* scratch, hipStream_t st) {
+hipError_t launch_influence_scores(const T* q, const int* row_pos, const int* row_req, const ReqTable* table,
+                                   int n_rows, const T* k_pool, KvGeom g, int n_q_heads, int max_len, float* scratch,
+                                   hipStream_t st) {
   if (n_rows <= 0 || max_len <= 0) return hipSuccess;
-  const int G = n_q_heads / g.n_kv_heads;
-  if (G > 8) return hipErrorInvalidValue;
-  float* scores = scratch;
-  // 8-byte aligned pair array behind the scores
+  if (n_q_heads / g.n_kv_heads > 8) return hipErrorInvalidValue;
+  const unsigned key_chunks = (unsigned)((max_len + kInfKeys - 1) / kInfKeys);
+  influence_scores_kernel<T><<<dim3(key_chunks, (unsigned)g.n_kv_heads, (unsigned)n_rows), kInfThreads, 0, st>>>(
+      q, row_pos, row_req, table, k_pool, g, n_q_heads, max_len, scratch);
+  return hipGetLastError();
+}
+template hipError_t launch_influence_scores<float>(const float*, const int*, const int*, const ReqTable*, int,
+                                                   const float*, KvGeom, int, int, float*, hipStream_t);
+template hipError_t launch_influence_scores<bf16>(const bf16*, const int*, const int*, const ReqTable*, int,
+                                                  const bf16*, KvGeom, int, int, float*, hipStream_t);
+
+hipError_t launch_influence_finish(const int* row_pos, const int* row_req, int n_rows, int n_q_heads, int max_len,
+                                   const InfluencePtrs& out, float* scratch, hipStream_t st) {
+  if (n_rows <= 0 || max_len <= 0) return hipSuccess;
+  // 8-byte aligned (m, l) pair array behind the scores
   size_t off = (size_t)n_rows * n_q_heads * max_len;
   off = (off + 1) & ~(size_t)1;
   float2* ml = reinterpret_cast<float2*>(scratch + off);
   const unsigned chunks = (unsigned)((max_len + kInfThreads - 1) / kInfThreads);
-  influence_scores_kernel<T><<<dim3(chunks, (unsigned)g.n_kv_heads, (unsigned)n_rows), kInfThreads,
-                               (size_t)G * g.head_dim * sizeof(float), st>>>(q, row_pos, row_req, table, k_pool, g,
-                                                                            n_q_heads, max_len, scores);
-  influence_norm_kernel<<<dim3((unsigned)n_q_heads, (unsigned)n_rows), kInfThreads, 0, st>>>(scores, row_pos, n_q_heads,
+  influence_norm_kernel<<<dim3((unsigned)n_q_heads, (unsigned)n_rows), kInfThreads, 0, st>>>(scratch, row_pos, n_q_heads,
                                                                                            max_len, ml);
-  influence_add_kernel<<<dim3(chunks, (unsigned)n_rows), kInfThreads, 0, st>>>(scores, ml, row_pos, row_req, out,
+  influence_add_kernel<<<dim3(chunks, (unsigned)n_rows), kInfThreads, 0, st>>>(scratch, ml, row_pos, row_req, out,
                                                                                n_q_heads, max_len);
   return hipGetLastError();
 }
-template hipError_t launch_influence_accumulate<float>(const float*, const int*, const int*, const ReqTable*, int,
-                                                       const float*, KvGeom, int, int, const InfluencePtrs&, float*,
-                                                       hipStream_t);
-template hipError_t launch_influence_accumulate<bf16>(const bf16*, const int*, const int*, const ReqTable*, int,
-                                                      const bf16*, KvGeom, int, int, const InfluencePtrs&, float*,
-                                                      hipStream_t);
 
 }  // namespace rc

@@ -79,7 +79,8 @@ def _hip_chain(rc, w, model, xs, n_prompts, capture_layer, paged):
     return cache, kpre, caps, logits, s_inf
 
 
-@pytest.mark.parametrize("name,paged", [("tiny5_f32", False), ("tiny5_f32", True), ("small_bf16", True)])
+@pytest.mark.parametrize("name,paged", [("tiny5_f32", False), ("tiny5_f32", True), ("small_bf16", True),
+                                        ("mistral7b_trunc", False)])
 def test_decode_chain_matches_oracle(name, paged):
     rc, w, om, model = _setup(name)
     tol = TOL[w.shape.dtype]

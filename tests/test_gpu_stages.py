@@ -213,7 +213,9 @@ def test_sparse_attention(dtype, hq, hkv, dh, block_size, split):
 # ------------------------------------------------------------------ K3
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("m,n,k", [(1, 64, 64), (51, 192, 256), (129, 1000, 688), (300, 257, 1408), (1639, 512, 1024),
-                                   (700, 2100, 512)])
+                                   (700, 2100, 512),
+                                   # few rows: the weight-streaming kernel of the decoding path (bf16)
+                                   (1, 64, 256), (16, 1024, 512), (17, 4096, 1024), (32, 96, 14336), (5, 6144, 4096)])
 @pytest.mark.parametrize("tail_split", [False, True])
 def test_gemm_rows(dtype, m, n, k, tail_split):
     rc = _rc()
