@@ -134,6 +134,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-prefill", action="store_true")
     ap.add_argument("--seed", type=int, default=20260313)
+    ap.add_argument("--decode-steps", type=int, default=0,
+                    help="after the prefill measurement, also time this many decoding steps (one token per request) on "
+                         "the corrected cache, with the cache manager's bookkeeping on; reported under \"decode\"")
     ap.add_argument("--counter-pass", action="store_true",
                     help="for rocprofv3 --pmc runs: one warm-up, the timed steps, then a 1 GiB device copy whose "
                          "FETCH_SIZE / WRITE_SIZE readings calibrate the counters; no CPU baseline, no full prefill")
@@ -297,6 +300,39 @@ def main() -> int:
         torch.cuda.synchronize()
         full_ms = ev0.elapsed_time(ev1) / 2
 
+    decode = None
+    if args.decode_steps > 0:
+        # the next agent's own generation: corrected cache from one more rc_reuse call into a cache with spare rows,
+        # then one token per request and step; un-rotated keys, hidden states at l_start and influence scores kept
+        nd = args.decode_steps
+        dec_lens = [n + nd + 2 for n in new_lens]
+        dec_cache, dec_pre = cache(dec_lens, 4), cache(dec_lens, 4)
+        rc.rc_reuse(model, reqs, plan, record, dec_cache, logits, sel, None, ws)
+        xs = hidden(n_req)
+        s_inf = [torch.zeros(n, dtype=torch.float32, device="cuda") for n in dec_lens]
+        h_keep = torch.zeros((n_req, sh.d_model), dtype=td, device="cuda")
+        lg_d = torch.zeros((n_req, sh.vocab), dtype=torch.float32, device="cuda")
+
+        def dreqs(t):
+            return [rc.DecodeReq(xs[b], new_lens[b] + t, b, h_keep[b], s_inf[b]) for b in range(n_req)]
+        ws_d = rc.alloc_workspace(rc.rc_decode_workspace_bytes(model, dreqs(nd + 1)))
+        rc.rc_decode_step(model, dreqs(0), dec_cache, lg_d, ws_d, k_pre=dec_pre, capture_layer=w.l_start)
+        torch.cuda.synchronize()
+        ev0.record()
+        for t in range(1, nd + 1):
+            rc.rc_decode_step(model, dreqs(t), dec_cache, lg_d, ws_d, k_pre=dec_pre, capture_layer=w.l_start)
+        ev1.record()
+        torch.cuda.synchronize()
+        dms = ev0.elapsed_time(ev1) / nd
+        wbytes = (sh.n_layers * sh.gemm_params_per_layer + sh.vocab * sh.d_model) * es
+        kvbytes = sum(sh.n_layers * 2 * (n + nd // 2) * nkv * es for n in new_lens)
+        gbs = (wbytes + kvbytes) / (dms * 1e-3) / 1e9
+        decode = {"ms_per_step": dms, "tokens_per_s": n_req / (dms * 1e-3), "batch": n_req, "steps": nd,
+                  "bookkeeping": "un-rotated keys, hidden state at l_start, influence scores (Eq. 6)",
+                  "roofline": {"bound": "hbm", "achieved": gbs, "peak": 8000.0, "unit": "GB/s", "frac": gbs / 8000.0,
+                               "algorithmic_mb_per_step": (wbytes + kvbytes) / 1e6,
+                               "note": "weights once + K and V of every cached row once per step"}}
+
     ctx_tokens = sum(new_lens)
     recomputed = sum((w.l_det - w.l_start) * S_ + (w.l_end - w.l_det + 1) * k_ for (_, S_, _), k_ in zip(lens, ks))
     out = {
@@ -332,6 +368,8 @@ def main() -> int:
         "speedup_vs_full_prefill": (full_ms / ms_per_step) if full_ms else None,
         "reuse_rate": 1.0 - recomputed / float(sh.n_layers * sum(l[1] for l in lens)),
     }
+    if decode is not None:
+        out["decode"] = decode
     if not args.no_cpu_baseline and n_req == 1:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

@@ -298,3 +298,62 @@ def test_multi_segment_prompt_by_chained_calls(name, ends_with_segment):
         assert rel_err(to_np(dst.read("v", l, 0, T)), want.v_cache[l]) <= tol, l
     assert rel_err(to_np(logits)[0], want.logits) <= tol
     model.close()
+
+
+# ------------------------------------------------------------------ graph capture
+def test_reuse_call_can_be_captured_in_a_graph_and_replayed():
+    """rc_reuse with the budget selector only enqueues kernels on the caller's stream (no allocation, no copy, no
+    wait), so a caller may capture it in a HIP graph.  Every replay, with eager work in between, reproduces the
+    eager result bit for bit."""
+    import torch
+    from paper_2603_13289_amd import binding as rc
+    from synth import WORKLOADS, make_hidden, make_weights
+    w = WORKLOADS["small_bf16"]
+    sh = w.shape
+    dt = rc.rc_dtype_of(sh.dtype)
+    td = rc.torch_dtype(dt)
+    model = rc.rc_model_create(sh, make_weights(w))
+    P, S, A, k = w.n_prefix, w.n_seg, w.n_alt, 50
+    up = lambda x: torch.from_numpy(np.ascontiguousarray(x, np.float32)).cuda().to(td).contiguous()
+    x_old = up(np.concatenate([make_hidden(w, "g_alt", A), make_hidden(w, "g_seg", S)]))
+    x_new = up(make_hidden(w, "g_new", P))
+    old = rc.PagedKV.contiguous(sh.n_layers, 1, A + S, sh.n_kv_heads, sh.head_dim, dt)
+    old_pre = rc.PagedKV.contiguous(sh.n_layers, 1, A + S, sh.n_kv_heads, sh.head_dim, dt)
+    h_cap = torch.zeros((A + S, sh.d_model), dtype=td, device="cuda")
+    lg = torch.zeros((1, sh.vocab), dtype=torch.float32, device="cuda")
+    rc.rc_prefill(model, [x_old], [0], old, lg, rc.alloc_workspace(rc.rc_prefill_workspace_bytes(model, [A + S])),
+                  k_pre=old_pre, capture_layer=w.l_start, h_capture=[h_cap])
+    record = rc.PagedKV.from_pools(old_pre.k, old.v, old.block_table, dt)
+    dst = rc.PagedKV.contiguous(sh.n_layers, 1, P + S, sh.n_kv_heads, sh.head_dim, dt)
+    req = rc.Request(x_new, h_cap[A:].contiguous(), None, src_seq=0, src_offset=A, k_is_pre_rope=True, seg_old_start_pos=A)
+    plan = rc.Plan(w.l_start, w.l_det, w.l_end, [k])
+    ws = rc.alloc_workspace(rc.rc_reuse_workspace_bytes(model, [req], plan))
+    logits = torch.zeros((1, sh.vocab), dtype=torch.float32, device="cuda")
+    sel = torch.zeros(k, dtype=torch.int32, device="cuda")
+    scores = torch.zeros(S, dtype=torch.float32, device="cuda")
+
+    def call(stream=None):
+        rc.rc_reuse(model, [req], plan, record, dst, logits, sel, scores, ws, stream=stream)
+
+    call()
+    torch.cuda.synchronize()
+    ref = [logits.clone(), sel.clone(), scores.clone()] + [t.clone() for t in dst.k] + [t.clone() for t in dst.v]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call(side)                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in [logits, scores] + dst.k + dst.v:     # eager work between the replays: wipe the outputs
+            t.zero_()
+        sel.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        now = [logits, sel, scores] + dst.k + dst.v
+        assert all(torch.equal(a, b) for a, b in zip(now, ref)), rep
+    model.close()
