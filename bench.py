@@ -244,7 +244,7 @@ def main() -> int:
     es = 2 if sh.dtype == "bf16" else 4
     nq, nkv = sh.n_q_heads * sh.head_dim, sh.n_kv_heads * sh.head_dim
     sel_host = sel.cpu().numpy()
-    b_rerotate = b_scatter = b_norm = b_score = 0.0
+    b_rerotate = b_scatter = b_norm = b_score = b_attn = 0.0
     attn_pairs = 0.0
     ko = 0
     for (P_, S_, _), k_ in zip(lens, ks):
@@ -264,6 +264,9 @@ def main() -> int:
                 rows, pairs = P_ + k_ + 1, pre_pairs + float((sel_pos + 1).sum()) + last_pairs
             else:
                 rows, pairs = P_ + 1, pre_pairs + last_pairs
+            # attention: the visible K and V rows once per layer, plus the live rows' Q read and O written
+            visible = (P_ + S_) if l >= w.l_start else P_
+            b_attn += 2 * visible * nkv * es + 2 * rows * nq * es
             b_scatter += rows * ((nq + 2 * nkv) * 4 + nq * es + 2 * nkv * es)
             b_norm += 2 * rows * sh.d_model * (4 + es)
             attn_pairs += pairs
@@ -281,6 +284,7 @@ def main() -> int:
         "rope_scatter": hbm("rope_scatter", b_scatter),
         "rmsnorm": hbm("rmsnorm", b_norm),
         "vdev_score": hbm("vdev_score", b_score),
+        "attention_hbm": hbm("attention", b_attn),
         "attention": {"bound": "mfma", "achieved": attn_flops / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else 0.0,
                       "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                       "frac": (attn_flops / (attn_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS) if attn_ms > 0 else 0.0,
@@ -299,6 +303,22 @@ def main() -> int:
         ev1.record()
         torch.cuda.synchronize()
         full_ms = ev0.elapsed_time(ev1) / 2
+
+    # the same call with the new prefix already in the destination cache (its rows are not recomputed)
+    reuse_only_ms = None
+    if not args.no_full_prefill and all(p_ > 0 for p_, _, _ in lens):
+        ro_dst = cache(new_lens, 5)
+        rc.rc_prefill(model, x_prefix, list(range(n_req)), ro_dst, lg, ws_p)
+        ro_reqs = [rc.Request(None, h_start[b], None, src_seq=b, src_offset=lens[b][2], k_is_pre_rope=True,
+                              seg_old_start_pos=lens[b][2], dst_seq=b, n_cached=lens[b][0]) for b in range(n_req)]
+        rc.rc_reuse(model, ro_reqs, plan, record, ro_dst, logits, sel, None, ws)
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(args.steps):
+            rc.rc_reuse(model, ro_reqs, plan, record, ro_dst, logits, sel, None, ws)
+        ev1.record()
+        torch.cuda.synchronize()
+        reuse_only_ms = ev0.elapsed_time(ev1) / args.steps
 
     decode = None
     if args.decode_steps > 0:
@@ -365,6 +385,7 @@ def main() -> int:
         "stage_rooflines": stage_rooflines,
         "ms_per_step_with_stage_events": ms_per_step_profiled,
         "full_prefill_ms": full_ms,
+        "reuse_only_ms": reuse_only_ms,
         "speedup_vs_full_prefill": (full_ms / ms_per_step) if full_ms else None,
         "reuse_rate": 1.0 - recomputed / float(sh.n_layers * sum(l[1] for l in lens)),
     }
