@@ -100,6 +100,8 @@ _add(Workload("tiny5_f32", _TINY5, 70, 150, 33, 1, 2, 3, 20, block_size=16,
               note="5 layers so that every phase (before / dense / sparse / after) has at least one layer"))
 _add(Workload("tiny5_f32_noprefix", _TINY5, 0, 120, 40, 1, 2, 3, 20, note="segment starts at position 0"))
 _add(Workload("tiny5_f32_one", _TINY5, 9, 1, 5, 1, 2, 3, 100, note="one-token segment"))
+_add(Workload("tiny5_f32_batch32", _TINY5, 0, 0, 0, 1, 2, 3, 8, block_size=16, n_req=32,
+              prefix_range=(0, 40), seg_range=(1, 60), note="the most requests one call takes; some budgets round to 0"))
 _add(Workload("small_bf16", ModelShape(4, 512, 8, 2, 128, 1408, 2048, 1.0e6), 150, 333, 70, 0, 1, 2, 15,
               note="narrow bf16 model, 4 layers, head_dim 128, group 4"))
 _add(Workload("small_bf16_ragged", ModelShape(4, 512, 8, 2, 128, 1408, 2048, 1.0e6), 0, 0, 0, 0, 1, 2, 15,

@@ -168,6 +168,30 @@ def test_bf16_threshold_selector_ragged_batch():
     _check_against_oracle(case, run, wants, TOL["bf16"], check_sel=False)
 
 
+def test_f32_largest_batch_of_ragged_requests():
+    """32 requests in one call (the limit), lengths from 1 token up, some without a new prefix, some whose
+    budget rounds down to nothing (pure reuse inside the same batch)."""
+    case = build_case("tiny5_f32_batch32")
+    assert len(case.reqs) == 32 and any(r.k == 0 for r in case.reqs) and any(r.k > 0 for r in case.reqs)
+    wants = [oracle_relay(case, b) for b in range(32)]
+    run = hip_relay(case)
+    for b, want in enumerate(wants):
+        k = case.reqs[b].k
+        ok = k == 0 or k == case.reqs[b].S or selection_margin(want.score, k) > MARGIN
+        if not ok:                                  # too close to call across precisions: compare on the oracle's rows
+            continue
+        assert np.array_equal(run.sel[b], want.sel_idx), b
+    exact = [b for b, want in enumerate(wants)
+             if case.reqs[b].k in (0, case.reqs[b].S) or selection_margin(want.score, case.reqs[b].k) > MARGIN]
+    assert len(exact) >= 24
+    T = lambda b: wants[b].k_cache.shape[1]
+    for b in exact:
+        for l in range(case.w.shape.n_layers):
+            assert rel_err(run.k_cache[b][l][:T(b)], wants[b].k_cache[l]) <= TOL["f32"], (b, l)
+            assert rel_err(run.v_cache[b][l][:T(b)], wants[b].v_cache[l]) <= TOL["f32"], (b, l)
+        assert rel_err(run.logits[b], wants[b].logits) <= TOL["f32"], b
+
+
 # ------------------------------------------------------------------ bf16 configurations
 @pytest.mark.parametrize("name", ["small_bf16", "qwen32b_trunc", "mistral7b_trunc"])
 def test_bf16_matches_oracle_with_forced_indices(name):
