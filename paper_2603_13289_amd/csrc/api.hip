@@ -421,7 +421,6 @@ rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
 
   ReqTable tabs[PH_COUNT];
   AttnSplit splits[PH_COUNT];
-  bool uploaded[PH_COUNT] = {false, false, false, false};
   for (int p = 0; p < PH_COUNT; ++p) tabs[p] = job.base;
 
   RC_LAUNCH(PC_TABLES, launch_rope_table(w.rope_tab, job.max_pos, d.head_dim / 2, (double)d.rope_base, st));
@@ -441,7 +440,6 @@ rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
       splits[ph] = attention_no_split();
     }
     RC_LAUNCH(PC_TABLES, launch_upload_table(tabs[ph], w.tables + ph, st));
-    uploaded[ph] = true;
     const int nb = cur >= 0 ? 1 - hbuf : hbuf;
     RC_LAUNCH(PC_ROWS, launch_build_rows<T>(w.tables + ph, tabs[ph].total_rows, w.h[hbuf], w.h[nb], w.row_pos, w.row_req,
                                 job.sel_idx, D, st));
@@ -549,7 +547,6 @@ rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
   RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(w.h_last, (const T*)job.m->g_final, (T*)w.a_last, n_req, D, d.rms_eps, st));
   RC_LAUNCH(PC_GEMM_LM_HEAD, gemm_any<T>((const T*)w.a_last, (const T*)job.m->w_lm, nullptr, job.logits, n_req, d.vocab, D, d.vocab,
                         EPI_STORE_F32, w.gemm_part, st));
-  (void)uploaded;
   return RC_OK;
 }
 

@@ -569,7 +569,7 @@ static hipError_t dispatch(const bf16* a, const bf16* w, const bf16* w2, const b
       tile = cost5 <= cost6 ? 5 : 6;
     }
   }
-  if (tile >= 5 && (k % BK) != 0) tile = 3;   // the direct-load kernels need whole K steps   // the direct-load kernels need whole K steps
+  if (tile >= 5 && (k % BK) != 0) tile = 3;   // the direct-load kernels need whole K steps
   switch (tile) {
     case 5: return launch_dl<256, 256, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st);
     case 6: return launch_dl<128, 128, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, nullptr, st);
