@@ -116,3 +116,11 @@ def test_stage_argument_errors():
     assert status(lambda: rc.rc_sparse_attention(s, idx, 1, 2, lay, 5, s, None)) == rc.RC_E_CAPACITY
     assert status(lambda: rc.rc_gemm_rows(rc.RC_F32, s, s, s, 1, 1, 4, None)) == rc.RC_E_UNSUPPORTED      # k % 8
     assert rc.rc_stage_workspace_bytes(10, 64) > 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
