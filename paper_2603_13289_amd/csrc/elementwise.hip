@@ -215,26 +215,66 @@ __device__ inline float block_sum(float v, float* lds /* >= 4 floats */) {
   return s;
 }
 
+// four consecutive elements of T from / to four floats
+__device__ inline void store4(float* p, const float* v) { *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]); }
+__device__ inline void store4(bf16* p, const float* v) {
+  uint2 pk;
+  pk.x = (uint32_t)f32_to_bf16(v[0]).v | ((uint32_t)f32_to_bf16(v[1]).v << 16);
+  pk.y = (uint32_t)f32_to_bf16(v[2]).v | ((uint32_t)f32_to_bf16(v[3]).v << 16);
+  *reinterpret_cast<uint2*>(p) = pk;
+}
+__device__ inline void load4(const float* p, float* v) {
+  const float4 t = *reinterpret_cast<const float4*>(p);
+  v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+}
+__device__ inline void load4(const bf16* p, float* v) {
+  const uint2 t = *reinterpret_cast<const uint2*>(p);
+  v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+  v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+}
+
 // ------------------------------------------------------------------ K2: RMSNorm on the active rows
+// One workgroup per row; the row stays in registers between the sum of squares and the scaling when it is
+// at most kNormKeep floats per thread (d <= 8192), else it is read again.
+constexpr int kNormKeep = 8;
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
 rmsnorm_kernel(const float* __restrict__ h, const T* __restrict__ gain, T* __restrict__ out, int d, float eps) {
   __shared__ float red[kThreads / 64];
   const float* x = h + (size_t)blockIdx.x * d;
+  float4 keep[kNormKeep];
   float ss = 0.f;
-  for (int c = threadIdx.x * 4; c < d; c += kThreads * 4) {
+#pragma unroll
+  for (int u = 0; u < kNormKeep; ++u) {
+    const int c = (threadIdx.x + u * kThreads) * 4;
+    if (c < d) {
+      keep[u] = *reinterpret_cast<const float4*>(x + c);
+      ss += keep[u].x * keep[u].x + keep[u].y * keep[u].y + keep[u].z * keep[u].z + keep[u].w * keep[u].w;
+    }
+  }
+  for (int c = (threadIdx.x + kNormKeep * kThreads) * 4; c < d; c += kThreads * 4) {
     const float4 v = *reinterpret_cast<const float4*>(x + c);
     ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
   }
   ss = block_sum(ss, red);
   const float r = 1.0f / sqrtf(ss / (float)d + eps);
   T* o = out + (size_t)blockIdx.x * d;
-  for (int c = threadIdx.x * 4; c < d; c += kThreads * 4) {
+#pragma unroll
+  for (int u = 0; u < kNormKeep; ++u) {
+    const int c = (threadIdx.x + u * kThreads) * 4;
+    if (c < d) {
+      float gv[4];
+      load4(gain + c, gv);
+      const float y[4] = {keep[u].x * r * gv[0], keep[u].y * r * gv[1], keep[u].z * r * gv[2], keep[u].w * r * gv[3]};
+      store4(o + c, y);
+    }
+  }
+  for (int c = (threadIdx.x + kNormKeep * kThreads) * 4; c < d; c += kThreads * 4) {
     const float4 v = *reinterpret_cast<const float4*>(x + c);
-    o[c + 0] = from_f32<T>(v.x * r * to_f32(gain[c + 0]));
-    o[c + 1] = from_f32<T>(v.y * r * to_f32(gain[c + 1]));
-    o[c + 2] = from_f32<T>(v.z * r * to_f32(gain[c + 2]));
-    o[c + 3] = from_f32<T>(v.w * r * to_f32(gain[c + 3]));
+    float gv[4];
+    load4(gain + c, gv);
+    const float y[4] = {v.x * r * gv[0], v.y * r * gv[1], v.z * r * gv[2], v.w * r * gv[3]};
+    store4(o + c, y);
   }
 }
 
@@ -248,8 +288,9 @@ template hipError_t launch_rmsnorm<float>(const float*, const float*, float*, in
 template hipError_t launch_rmsnorm<bf16>(const float*, const bf16*, bf16*, int, int, float, hipStream_t);
 
 // ------------------------------------------------------------------ rotary on fresh q/k + K7: paged scatter
-// One workgroup per active row.  qkv is the float output of the three projections laid out
-// [row][Hq*dh | Hkv*dh | Hkv*dh].
+// One workgroup per live row.  qkv is the float output of the three projections laid out
+// [row][Hq*dh | Hkv*dh | Hkv*dh].  A work item is four consecutive rotary pairs of one head (q or k) or four
+// consecutive value elements, so every access is 16 bytes of float or 8 bytes of bf16.
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
 rope_scatter_kernel(const float* __restrict__ qkv, const int* __restrict__ row_pos, const int* __restrict__ row_req,
@@ -259,33 +300,50 @@ rope_scatter_kernel(const float* __restrict__ qkv, const int* __restrict__ row_p
   const int r = blockIdx.x;
   const int pos = row_pos[r];
   const int seq = table->r[row_req[r]].dst_seq;
-  const int dh = g.head_dim, half = dh / 2;
+  const int dh = g.head_dim, half = dh / 2, quads = half / 4;
   const int nq = n_q_heads * dh, nkv = g.n_kv_heads * dh;
   const float* row = qkv + (size_t)r * (nq + 2 * nkv);
   const float2* cs = rope_tab + (size_t)pos * half;
-  // query heads
-  for (int p = threadIdx.x; p < n_q_heads * half; p += kThreads) {
-    const int head = p / half, i = p - head * half;
-    const float a = row[head * dh + i], b = row[head * dh + half + i];
-    const float2 t = cs[i];
-    T* o = q_out + (size_t)r * nq + head * dh;
-    o[i] = from_f32<T>(a * t.x - b * t.y);
-    o[half + i] = from_f32<T>(b * t.x + a * t.y);
-  }
-  // key heads: rotated into the cache (and optionally un-rotated into the pre-RoPE pool); values as they are
-  for (int p = threadIdx.x; p < g.n_kv_heads * half; p += kThreads) {
-    const int head = p / half, i = p - head * half;
-    const size_t off = kv_row_offset(g, seq, pos, head);
-    const float a = row[nq + head * dh + i], b = row[nq + head * dh + half + i];
-    const float2 t = cs[i];
-    k_pool[off + i] = from_f32<T>(a * t.x - b * t.y);
-    k_pool[off + half + i] = from_f32<T>(b * t.x + a * t.y);
-    if (k_pre_pool) {
-      k_pre_pool[off + i] = from_f32<T>(a);
-      k_pre_pool[off + half + i] = from_f32<T>(b);
+  const int n_rot = (n_q_heads + g.n_kv_heads) * quads;    // query heads first, then key heads
+  const int n_val = g.n_kv_heads * (dh / 4);
+  for (int item = threadIdx.x; item < n_rot + n_val; item += kThreads) {
+    if (item < n_rot) {
+      const int head = item / quads, i = (item - head * quads) * 4;
+      const bool is_q = head < n_q_heads;
+      const float* src = row + (is_q ? head * dh : nq + (head - n_q_heads) * dh);
+      const float4 a4 = *reinterpret_cast<const float4*>(src + i);
+      const float4 b4 = *reinterpret_cast<const float4*>(src + half + i);
+      const float4 t01 = *reinterpret_cast<const float4*>(cs + i);        // (cos, sin) of pairs i, i+1
+      const float4 t23 = *reinterpret_cast<const float4*>(cs + i + 2);    // pairs i+2, i+3
+      const float a[4] = {a4.x, a4.y, a4.z, a4.w}, b[4] = {b4.x, b4.y, b4.z, b4.w};
+      const float c[4] = {t01.x, t01.z, t23.x, t23.z}, sn[4] = {t01.y, t01.w, t23.y, t23.w};
+      float lo[4], hi[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        lo[e] = a[e] * c[e] - b[e] * sn[e];
+        hi[e] = b[e] * c[e] + a[e] * sn[e];
+      }
+      if (is_q) {
+        T* o = q_out + (size_t)r * nq + head * dh;
+        store4(o + i, lo);
+        store4(o + half + i, hi);
+      } else {
+        // rotated into the cache (and optionally un-rotated into the pre-RoPE pool)
+        const size_t off = kv_row_offset(g, seq, pos, head - n_q_heads);
+        store4(k_pool + off + i, lo);
+        store4(k_pool + off + half + i, hi);
+        if (k_pre_pool) {
+          store4(k_pre_pool + off + i, a);
+          store4(k_pre_pool + off + half + i, b);
+        }
+      }
+    } else {
+      const int vi = item - n_rot;
+      const int head = vi / (dh / 4), i = (vi - head * (dh / 4)) * 4;
+      const float4 v4 = *reinterpret_cast<const float4*>(row + nq + nkv + head * dh + i);
+      const float v[4] = {v4.x, v4.y, v4.z, v4.w};
+      store4(v_pool + kv_row_offset(g, seq, pos, head) + i, v);
     }
-    v_pool[off + i] = from_f32<T>(row[nq + nkv + head * dh + i]);
-    v_pool[off + half + i] = from_f32<T>(row[nq + nkv + head * dh + half + i]);
   }
 }
 
