@@ -18,6 +18,8 @@
 // KV tiles entirely above the tile's last query position are skipped; the causal mask is applied
 // only in tiles that reach above the tile's first query position.  Workgroups are issued longest
 // first.
+#include <type_traits>
+
 #include "common.h"
 
 namespace rc {
@@ -115,17 +117,20 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
     kbase = k_pool + o + kch * 8;
     vbase = v_pool + o;
   }
-  uint4 rk[KPER], rv[VPER][4];
-  auto fetch = [&](int kv0) {
+  // two register sets: the tile fetched at step t is staged at step t + 2, so a fetch has two multiply phases
+  // to arrive
+  uint4 rk[2][KPER], rv[2][VPER][4];
+  auto fetch = [&](int kv0, auto set) {
+    constexpr int SET = decltype(set)::value;
     const bool full = kv0 + BKV - 1 <= last_pos;   // uniform: only a query tile's last KV tile can be ragged
 #pragma unroll
     for (int i = 0; i < KPER; ++i) {
       const int row = krow0 + i * KSTEP;
       const int pos = kv0 + row;
-      rk[i] = make_uint4(0, 0, 0, 0);
+      rk[SET][i] = make_uint4(0, 0, 0, 0);
       if (row < BKV && (full || pos <= last_pos)) {
         const bf16* src = contig ? kbase + (size_t)pos * DH : k_pool + kv_row_offset(g, seq, pos, kvh) + kch * 8;
-        rk[i] = *reinterpret_cast<const uint4*>(src);
+        rk[SET][i] = *reinterpret_cast<const uint4*>(src);
       }
     }
 #pragma unroll
@@ -134,10 +139,10 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         const int pos = kv0 + vquad * 4 + kk;
-        rv[i][kk] = make_uint4(0, 0, 0, 0);
+        rv[SET][i][kk] = make_uint4(0, 0, 0, 0);
         if (dch < 16 && (full || pos <= last_pos)) {
           const bf16* src = contig ? vbase + (size_t)pos * DH + dch * 8 : v_pool + kv_row_offset(g, seq, pos, kvh) + dch * 8;
-          rv[i][kk] = *reinterpret_cast<const uint4*>(src);
+          rv[SET][i][kk] = *reinterpret_cast<const uint4*>(src);
         }
       }
     }
@@ -147,17 +152,18 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   const int vcol = (vkey0 & ~15) + 8 * ((vkey0 >> 2) & 1) + 4 * ((vkey0 >> 3) & 1);
   unsigned char* const k_wr = lds_k + krow0 * KROW + kch * 16;
   unsigned char* const v_wr = lds_vt + vdch0 * 8 * VROW + vcol * 2;
-  auto stage = [&]() {
+  auto stage = [&](auto set) {
+    constexpr int SET = decltype(set)::value;
 #pragma unroll
     for (int i = 0; i < KPER; ++i)
-      if (krow0 + i * KSTEP < BKV) *reinterpret_cast<uint4*>(k_wr + i * KSTEP * KROW) = rk[i];
+      if (krow0 + i * KSTEP < BKV) *reinterpret_cast<uint4*>(k_wr + i * KSTEP * KROW) = rk[SET][i];
 #pragma unroll
     for (int i = 0; i < VPER; ++i) {
       if (vdch0 + i * KSTEP >= 16) continue;
-      const uint32_t w[4][4] = {{rv[i][0].x, rv[i][0].y, rv[i][0].z, rv[i][0].w},
-                                {rv[i][1].x, rv[i][1].y, rv[i][1].z, rv[i][1].w},
-                                {rv[i][2].x, rv[i][2].y, rv[i][2].z, rv[i][2].w},
-                                {rv[i][3].x, rv[i][3].y, rv[i][3].z, rv[i][3].w}};
+      const uint32_t w[4][4] = {{rv[SET][i][0].x, rv[SET][i][0].y, rv[SET][i][0].z, rv[SET][i][0].w},
+                                {rv[SET][i][1].x, rv[SET][i][1].y, rv[SET][i][1].z, rv[SET][i][1].w},
+                                {rv[SET][i][2].x, rv[SET][i][2].y, rv[SET][i][2].z, rv[SET][i][2].w},
+                                {rv[SET][i][3].x, rv[SET][i][3].y, rv[SET][i][3].z, rv[SET][i][3].w}};
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int wi = e >> 1;
@@ -179,13 +185,16 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   const int t_begin = is_split ? chunk * sp.chunk_tiles : 0;
   const int t_end = is_split ? min(n_kv_tiles, t_begin + sp.chunk_tiles) : n_kv_tiles;
   if (t_begin >= t_end || (!is_split && chunk != 0)) return;   // nothing for this workgroup (uniform)
-  fetch(t_begin * BKV);
-  for (int t = t_begin; t < t_end; ++t) {
+  const std::integral_constant<int, 0> set0;
+  const std::integral_constant<int, 1> set1;
+  fetch(t_begin * BKV, set0);
+  if (t_begin + 1 < t_end) fetch((t_begin + 1) * BKV, set1);
+  auto tile_step = [&](int t, auto set) {
     const int kv0 = t * BKV;
     __syncthreads();   // previous tile fully consumed
-    stage();
+    stage(set);
     __syncthreads();
-    if (t + 1 < t_end) fetch(kv0 + BKV);
+    if (t + 2 < t_end) fetch(kv0 + 2 * BKV, set);
 
     // S^T = K Q^T : two blocks of 32 keys
     f32x16 acc_s[2];
@@ -268,6 +277,10 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
         acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[tt], acc_o[db], 0, 0, 0);
       }
     }
+  };
+  for (int t = t_begin; t < t_end; t += 2) {
+    tile_step(t, set0);
+    if (t + 1 < t_end) tile_step(t + 1, set1);
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
