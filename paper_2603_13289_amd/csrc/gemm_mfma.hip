@@ -11,7 +11,8 @@
 // rows (one MFMA operand fetch) touch 16 different (row parity, slot) pairs = all 64 banks once, and
 // the row-contiguous fill is conflict free as well.  No padding is needed.
 // The next K step is fetched into registers while the current one is multiplied.
-// Each wavefront owns a (BM/WAVES_M) x (BN/WAVES_N) sub-tile built from 32x32x16 MFMA blocks.
+// Each wavefront owns a (BM/WAVES_M) x (BN/WAVES_N) sub-tile, built from 32x32x16 MFMA blocks in the
+// register-staged kernel (any K) and from 16x16x32 blocks in the direct-to-LDS kernel (K a multiple of 64).
 //
 // SwiGLU epilogue (DUAL): the B tile stacks BN/2 rows of W_gate on BN/2 rows of W_up for the same
 // output columns, every wavefront holds matching gate/up accumulators and writes silu(gate)*up.
@@ -36,7 +37,7 @@ void set_gemm_xcd_remap(int on) { g_xcd_remap = on; }
 __device__ inline float silu_mf(float x) { return x / (1.0f + __expf(-x)); }
 
 // Accumulator element e of the 32x32 block (i, j) of a wavefront sits at row 8*(e/4) + 4*(lane/32) + e%4,
-// column lane%32 of that block.  Shared by the GEMM kernels and the split-K fix-up.
+// column lane%32 of that block.
 template <int FM, int FN, int WTM, int WTN, bool DUAL>
 __device__ inline void store_tile(const f32x16 (&acc)[FM][FN], void* __restrict__ c, int m, int n, int ldc, int epi,
                                   int m0, int n0, int wm, int wn, int lane) {
@@ -217,30 +218,87 @@ gemm_mfma_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const b
   store_tile<FM, FN, WTM, WTN, DUAL>(acc, c, m, n, ldc, epi, m0, n0, wm, wn, lane);
 }
 
-// ------------------------------------------------------------------ direct-to-LDS, double-buffered variant
-// Same tile/fragment structure as above, but tiles are fetched with 16-byte global->LDS loads (no
-// staging registers, no LDS store instructions) into two alternating LDS buffers, so one barrier per
-// K step suffices: wait for my loads, barrier, start the loads of the next step into the other
-// buffer, multiply the current one.
+// ------------------------------------------------------------------ direct-to-LDS, double-buffered kernel
+// Tiles are fetched with 16-byte global->LDS loads (no staging registers, no LDS store instructions) into two
+// alternating LDS buffers, so one barrier per K step suffices: wait for my loads, barrier, start the loads
+// of the step after next into the buffer just freed, multiply the current one.
 //
 // A direct load writes lane l's 16 bytes to (wave-uniform LDS base) + 16 l, i.e. one instruction fills
 // 1 KB = 8 rows of 128 bytes.  The XOR placement (chunk c of row r at slot c ^ ((r >> 1) & 7)) is
 // therefore applied on the global side: lane l of a row block fetches chunk (l & 7) ^ swz(row).
 // Rows past M (or N) re-read the last valid row; their products are never stored.  K must be a
 // multiple of 64.
+//
+// The wavefront sub-tile is built from 16x16x32 MFMA blocks (measured: with the same LDS and load traffic
+// this shape sustains about 9 % more matrix throughput than 32x32x16 under the chip's power limit).  A K
+// step of 64 is two sub-steps of 32; each sub-step is multiplied in two halves of the weight-column blocks,
+// so a pipeline unit is FM x FN/2 MFMAs with the LDS reads of the next unit in flight.  16 lanes reading the
+// same chunk of 16 consecutive rows (one operand fetch) touch all 64 LDS banks once, as in the kernel above.
+//
+// The weight fragment is passed as the first MFMA operand, so that accumulator (i, j) of a lane holds
+//   row    i*16 + lane%16                 of the wavefront's activation rows,
+//   column j*16 + 4*(lane/16) + e         of its output columns, e = 0..3:
+// four consecutive output columns per lane, stored with one 16-byte (f32) or 8-byte (bf16) access.
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+template <int FM, int FN, int WTM, int WTN, bool DUAL>
+__device__ inline void store_tile16(const f32x4 (&acc)[FM][FN], void* __restrict__ c, int m, int n, int ldc, int epi,
+                                    int m0, int n0, int wm, int wn, int lane) {
+  constexpr int FN_OUT = DUAL ? FN / 2 : FN;
+  constexpr int WTN_OUT = DUAL ? WTN / 2 : WTN;
+  const bool f32_out = !DUAL && (epi == EPI_STORE_F32 || epi == EPI_ADD_F32);
+  const bool vec_ok = (ldc & 3) == 0 && (reinterpret_cast<size_t>(c) & (f32_out ? 15 : 7)) == 0;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    const int row = m0 + wm * WTM + i * 16 + (lane & 15);
+    if (row >= m) continue;
+#pragma unroll
+    for (int j = 0; j < FN_OUT; ++j) {
+      const int col = n0 + wn * WTN_OUT + j * 16 + 4 * (lane >> 4);
+      if (col >= n) continue;
+      const size_t o = (size_t)row * ldc + col;
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = DUAL ? silu_mf(acc[i][j][e]) * acc[i][j + FN_OUT][e] : acc[i][j][e];
+      if (vec_ok && col + 3 < n) {
+        if (f32_out) {
+          float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(c) + o);
+          float4 t = make_float4(v[0], v[1], v[2], v[3]);
+          if (epi == EPI_ADD_F32) { const float4 old = *dst; t.x += old.x; t.y += old.y; t.z += old.z; t.w += old.w; }
+          *dst = t;
+        } else {
+          union { bf16 h[4]; uint2 u; } pk;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) pk.h[e] = f32_to_bf16(v[e]);
+          *reinterpret_cast<uint2*>(reinterpret_cast<bf16*>(c) + o) = pk.u;
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (col + e >= n) continue;
+          if (!f32_out) reinterpret_cast<bf16*>(c)[o + e] = f32_to_bf16(v[e]);
+          else if (epi == EPI_ADD_F32) reinterpret_cast<float*>(c)[o + e] += v[e];
+          else reinterpret_cast<float*>(c)[o + e] = v[e];
+        }
+      }
+    }
+  }
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool DUAL, int OCC>
 __global__ void __launch_bounds__(WAVES_M * WAVES_N * 64, OCC)
 gemm_mfma_dl_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const bf16* __restrict__ w2,
-                    const bf16* __restrict__ w3, int ns1, int ns2, void* __restrict__ c, int m, int n, int k, int ldc,
-                    int epi, TileOrder order, int full_tiles, int per_xcd, int n_full_wgs, int split, int ksteps_per_part,
-                    float* __restrict__ partial) {
+                      const bf16* __restrict__ w3, int ns1, int ns2, void* __restrict__ c, int m, int n, int k, int ldc,
+                      int epi, TileOrder order, int full_tiles, int per_xcd, int n_full_wgs, int split, int ksteps_per_part,
+                      float* __restrict__ partial) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
-  constexpr int FM = WTM / 32, FN = WTN / 32;
+  constexpr int FM = WTM / 16, FN = WTN / 16, FH = FN / 2;
   constexpr int BN_OUT = DUAL ? BN / 2 : BN;
-  constexpr int A_BLK = BM / 8, B_BLK = BN / 8;              // 8-row blocks per tile
-  constexpr int A_PER = A_BLK / NW, B_PER = B_BLK / NW;      // blocks per wave
+  constexpr int A_BLK = BM / 8, B_BLK = BN / 8;
+  constexpr int A_PER = A_BLK / NW, B_PER = B_BLK / NW;
   static_assert(A_PER * NW == A_BLK && B_PER * NW == B_BLK, "tile/waves mismatch");
+  static_assert(FN % 2 == 0 && BK == 64, "two sub-steps of 32, two halves of the column blocks");
   constexpr int TILE_BYTES = (BM + BN) * 128;
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];   // 2 x [A tile | B tile]
@@ -268,7 +326,6 @@ gemm_mfma_dl_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, cons
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
-  // global sources: lane l of block b covers row 8 b + (l >> 3), LDS slot l & 7
   const int lrow = lane >> 3, lslot = lane & 7;
   const bf16* pa[A_PER];
   const bf16* pb[B_PER];
@@ -305,70 +362,79 @@ gemm_mfma_dl_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, cons
                                        (__attribute__((address_space(3))) void*)(base + BM * 128 + (wave + i * NW) * 1024), 16, 0, 0);
   };
 
-  f32x16 acc[FM][FN];
+  f32x4 acc[FM][FN];
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
+  // LDS rows this lane reads its operands from: lane%16 selects the row of a 16-row block, lane/16 the 8-k chunk
   int arow[FM], brow[FN];
 #pragma unroll
-  for (int i = 0; i < FM; ++i) arow[i] = wm * WTM + i * 32 + (lane & 31);
+  for (int i = 0; i < FM; ++i) arow[i] = wm * WTM + i * 16 + (lane & 15);
 #pragma unroll
   for (int j = 0; j < FN; ++j) {
-    if (DUAL) brow[j] = (j < FN / 2 ? wn * (WTN / 2) + j * 32 : BN / 2 + wn * (WTN / 2) + (j - FN / 2) * 32) + (lane & 31);
-    else brow[j] = wn * WTN + j * 32 + (lane & 31);
+    if (DUAL) brow[j] = (j < FH ? wn * (WTN / 2) + j * 16 : BN / 2 + wn * (WTN / 2) + (j - FH) * 16) + (lane & 15);
+    else brow[j] = wn * WTN + j * 16 + (lane & 15);
   }
-  const int khalf = lane >> 5;
+  const int kq = lane >> 4;
 
-  // Pipeline: the loads of step t+1 are issued while step t is multiplied.  The barrier that frees buffer
-  // t%2 and publishes buffer (t+1)%2 sits before the last sub-step's MFMAs of step t, and the first
-  // fragments of step t+1 are fetched from LDS right after it, so that both the barrier and the LDS
-  // latency are covered by that last group of MFMAs.
-  bf16x8 fa[2][FM], fb[2][FN];
-  auto load_frags = [&](int b, int s, int r) {
+  bf16x8 fa[2][FM], fb[2][FH];
+  auto load_a = [&](int b, int s) {
     const uint4* la = reinterpret_cast<const uint4*>(lds + b * TILE_BYTES);
-    const uint4* lb = reinterpret_cast<const uint4*>(lds + b * TILE_BYTES + BM * 128);
-    const int chunk = 2 * s + khalf;
+    const int chunk = 4 * s + kq;
 #pragma unroll
-    for (int i = 0; i < FM; ++i) fa[r][i] = __builtin_bit_cast(bf16x8, la[arow[i] * 8 + (chunk ^ ((arow[i] >> 1) & 7))]);
-#pragma unroll
-    for (int j = 0; j < FN; ++j) fb[r][j] = __builtin_bit_cast(bf16x8, lb[brow[j] * 8 + (chunk ^ ((brow[j] >> 1) & 7))]);
+    for (int i = 0; i < FM; ++i) fa[s][i] = __builtin_bit_cast(bf16x8, la[arow[i] * 8 + (chunk ^ ((arow[i] >> 1) & 7))]);
   };
-  auto multiply = [&](int r) {
+  auto load_b = [&](int b, int s, int h) {
+    const uint4* lb = reinterpret_cast<const uint4*>(lds + b * TILE_BYTES + BM * 128);
+    const int chunk = 4 * s + kq;
+#pragma unroll
+    for (int j = 0; j < FH; ++j) {
+      const int r = brow[h * FH + j];
+      fb[h][j] = __builtin_bit_cast(bf16x8, lb[r * 8 + (chunk ^ ((r >> 1) & 7))]);
+    }
+  };
+  auto multiply = [&](int s, int h) {
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
-      for (int j = 0; j < FN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[r][i], fb[r][j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < FH; ++j)
+        acc[i][h * FH + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[h][j], fa[s][i], acc[i][h * FH + j], 0, 0, 0);
   };
-  constexpr int SUB = BK / 16;
-  static_assert(SUB % 2 == 0, "fragment double buffering assumes an even number of sub-steps");
+
   if (k_begin < k_end) {
     issue(k_begin, 0);
     if (k_begin + BK < k_end) issue(k_begin + BK, 1);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    load_frags(0, 0, 0);
+    load_a(0, 0);
+    load_b(0, 0, 0);
   }
   int buf = 0;
   for (int k0 = k_begin; k0 < k_end; k0 += BK) {
-#pragma unroll
-    for (int s = 0; s + 1 < SUB; ++s) {
-      load_frags(buf, s + 1, (s + 1) & 1);
-      __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of this sub-step's MFMAs
-      multiply(s & 1);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // last sub-step's operands are being read; once they are in registers nobody needs buffer `buf` any more
+    load_b(buf, 0, 1);
+    __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads of the next unit ahead of this unit's MFMAs
+    multiply(0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_a(buf, 1);
+    load_b(buf, 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(0, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_b(buf, 1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    // the last unit's operands are being read; once they are in registers nobody needs buffer `buf` any more
     __builtin_amdgcn_s_waitcnt(0);   // my LDS reads and my direct loads of the next step are complete
     __syncthreads();
     if (k0 + 2 * BK < k_end) issue(k0 + 2 * BK, buf);
-    if (k0 + BK < k_end) load_frags(buf ^ 1, 0, 0);
+    if (k0 + BK < k_end) { load_a(buf ^ 1, 0); load_b(buf ^ 1, 0, 0); }
     __builtin_amdgcn_sched_barrier(0);
-    multiply((SUB - 1) & 1);
+    multiply(1, 1);
     __builtin_amdgcn_sched_barrier(0);
     buf ^= 1;
   }
@@ -376,62 +442,54 @@ gemm_mfma_dl_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, cons
   if (part_slot >= 0) {
     // raw accumulators, register-major so that consecutive lanes write consecutive floats
     constexpr int NT = NW * 64;
-    float* dst = partial + (size_t)part_slot * (FM * FN * 16) * NT + tid;
+    float* dst = partial + (size_t)part_slot * (FM * FN * 4) * NT + tid;
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
       for (int j = 0; j < FN; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) dst[(size_t)((i * FN + j) * 16 + e) * NT] = acc[i][j][e];
+        for (int e = 0; e < 4; ++e) dst[(size_t)((i * FN + j) * 4 + e) * NT] = acc[i][j][e];
     return;
   }
-  store_tile<FM, FN, WTM, WTN, DUAL>(acc, c, m, n, ldc, epi, m0, n0, wm, wn, lane);
+  store_tile16<FM, FN, WTM, WTN, DUAL>(acc, c, m, n, ldc, epi, m0, n0, wm, wn, lane);
 }
 
-// Sum of the K-split parts of the tail tiles (fixed order: part 0, 1, ...) followed by the epilogue.
-// One workgroup per (tile, 32x32 block, group of 4 accumulator registers): thread t owns the same
-// (wavefront, lane) as thread t of the GEMM kernel, so all reads of a part are coalesced.
+// Sum of the K-split parts of the tail tiles (fixed order: part 0, 1, ...) followed by the epilogue.  One
+// workgroup per (tile, accumulator (i, j)); thread t owns the same (wavefront, lane) as thread t of the GEMM
+// kernel, so all reads of a part are coalesced.
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool DUAL>
 __global__ void __launch_bounds__(WAVES_M * WAVES_N * 64)
 gemm_fixup_kernel(void* __restrict__ c, int m, int n, int ldc, int epi, TileOrder order, int full_tiles, int split,
-                  const float* __restrict__ partial) {
+                    const float* __restrict__ partial) {
   constexpr int NW = WAVES_M * WAVES_N, NT = NW * 64;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
-  constexpr int FM = WTM / 32, FN = WTN / 32;
+  constexpr int FM = WTM / 16, FN = WTN / 16;
   constexpr int FN_OUT = DUAL ? FN / 2 : FN;
-  constexpr int WTN_OUT = DUAL ? WTN / 2 : WTN;
   constexpr int BN_OUT = DUAL ? BN / 2 : BN;
-  constexpr int PER_TILE = FM * FN_OUT * 4;
+  constexpr int PER_TILE = FM * FN_OUT;
   const int t = (int)blockIdx.x / PER_TILE;
-  int rest = (int)blockIdx.x % PER_TILE;
-  const int e4 = rest % 4; rest /= 4;
+  const int rest = (int)blockIdx.x % PER_TILE;
   const int j = rest % FN_OUT, i = rest / FN_OUT;
-  const int logical = full_tiles + t;
   int tile_m, tile_n;
-  tile_of(order, logical, &tile_m, &tile_n);
+  tile_of(order, full_tiles + t, &tile_m, &tile_n);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  float g[4] = {0.f, 0.f, 0.f, 0.f}, u[4] = {0.f, 0.f, 0.f, 0.f};
+  // the sums land in a one-accumulator "tile" so that the epilogue code is the GEMM kernel's own
+  f32x4 one[1][DUAL ? 2 : 1];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { one[0][0][e] = 0.f; if (DUAL) one[0][DUAL ? 1 : 0][e] = 0.f; }
   for (int p = 0; p < split; ++p) {
-    const float* src = partial + (size_t)(t * split + p) * (FM * FN * 16) * NT + tid;
+    const float* src = partial + (size_t)(t * split + p) * (FM * FN * 4) * NT + tid;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      g[e] += src[(size_t)((i * FN + j) * 16 + e4 * 4 + e) * NT];
-      if (DUAL) u[e] += src[(size_t)((i * FN + j + FN_OUT) * 16 + e4 * 4 + e) * NT];
+      one[0][0][e] += src[(size_t)((i * FN + j) * 4 + e) * NT];
+      if (DUAL) one[0][DUAL ? 1 : 0][e] += src[(size_t)((i * FN + j + FN_OUT) * 4 + e) * NT];
     }
   }
-  const int col = tile_n * BN_OUT + wn * WTN_OUT + j * 32 + (lane & 31);
-  if (col >= n) return;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const int row = tile_m * BM + wm * WTM + i * 32 + 8 * e4 + 4 * (lane >> 5) + e;
-    if (row >= m) continue;
-    const size_t o = (size_t)row * ldc + col;
-    if (DUAL) reinterpret_cast<bf16*>(c)[o] = f32_to_bf16(silu_mf(g[e]) * u[e]);
-    else if (epi == EPI_STORE_F32) reinterpret_cast<float*>(c)[o] = g[e];
-    else if (epi == EPI_ADD_F32) reinterpret_cast<float*>(c)[o] += g[e];
-    else reinterpret_cast<bf16*>(c)[o] = f32_to_bf16(g[e]);
-  }
+  // row/column origin of accumulator (i, j) of this wavefront
+  const int m_org = tile_m * BM + wm * WTM + i * 16;
+  const int n_org = tile_n * BN_OUT + wn * (DUAL ? WTN / 2 : WTN) + j * 16;
+  store_tile16<1, DUAL ? 2 : 1, 16, DUAL ? 32 : 16, DUAL>(one, c, m, n, ldc, epi, m_org, n_org, 0, 0, lane);
 }
 
 // Rough time model (microseconds, measured on MI355X) used to choose the tile and the K-split of the tail:
@@ -506,7 +564,7 @@ static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const 
     kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, make_tile_order(tiles_m, tiles_n), full_tiles, per_xcd,
                                       n_full_wgs, split, kpp, partial);
     if (rem_tiles > 0)
-      gemm_fixup_kernel<BM, BN, WAVES_M, WAVES_N, true><<<rem_tiles * (BM / WAVES_M / 32) * (BN / WAVES_N / 64) * 4, NT, 0, st>>>(
+      gemm_fixup_kernel<BM, BN, WAVES_M, WAVES_N, true><<<rem_tiles * (BM / WAVES_M / 16) * (BN / WAVES_N / 32), NT, 0, st>>>(
           c, m, n, ldc, (int)epi, make_tile_order(tiles_m, tiles_n), full_tiles, split, partial);
   } else {
     auto kern = gemm_mfma_dl_kernel<BM, BN, WAVES_M, WAVES_N, false, OCC>;
@@ -516,7 +574,7 @@ static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const 
     kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, make_tile_order(tiles_m, tiles_n), full_tiles, per_xcd,
                                       n_full_wgs, split, kpp, partial);
     if (rem_tiles > 0)
-      gemm_fixup_kernel<BM, BN, WAVES_M, WAVES_N, false><<<rem_tiles * (BM / WAVES_M / 32) * (BN / WAVES_N / 32) * 4, NT, 0, st>>>(
+      gemm_fixup_kernel<BM, BN, WAVES_M, WAVES_N, false><<<rem_tiles * (BM / WAVES_M / 16) * (BN / WAVES_N / 16), NT, 0, st>>>(
           c, m, n, ldc, (int)epi, make_tile_order(tiles_m, tiles_n), full_tiles, split, partial);
   }
   return hipGetLastError();
