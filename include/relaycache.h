@@ -337,6 +337,18 @@ RC_API size_t rc_gemm_workspace_bytes(void);
 RC_API rc_status rc_gemm_rows(int32_t dtype, const void* a, const void* w, float* c, int32_t m, int32_t n,
                               int32_t k, void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same GEMM with the epilogues the decoder layer applies in place (the layer function whose outputs
+ * Eq. (1) compares: attention and SwiGLU MLP sub-blocks with residual connections):
+ *   RC_GEMM_STORE   c (float [M][N])  = A W^T
+ *   RC_GEMM_STORE_T c (T [M][N])      = A W^T                          (fresh value rows)
+ *   RC_GEMM_ADD     c (float [M][N]) += A W^T                          (residual add of the o and down projections)
+ *   RC_GEMM_SWIGLU  c (T [M][N])      = silu(A W^T) * (A W2^T)         (gate and up projections in one pass)
+ * w2 [N][K] of T is read by RC_GEMM_SWIGLU only (NULL otherwise).  Other arguments as for rc_gemm_rows. */
+typedef enum { RC_GEMM_STORE = 0, RC_GEMM_STORE_T = 1, RC_GEMM_ADD = 2, RC_GEMM_SWIGLU = 3 } rc_gemm_epilogue;
+RC_API rc_status rc_gemm_rows_fused(int32_t dtype, int32_t epilogue, const void* a, const void* w, const void* w2,
+                                    void* c, int32_t m, int32_t n, int32_t k, void* workspace,
+                                    size_t workspace_bytes, void* stream);
+
 /* Write n recomputed rows into one layer of a paged cache: k_rows/v_rows [n][Hkv][dh] of T go to
  * positions pos[i] of `seq` (keys as given, i.e. already rotated). */
 RC_API rc_status rc_scatter_paged(const void* k_rows, const void* v_rows, const int32_t* pos, int32_t n,

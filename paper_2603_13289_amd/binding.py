@@ -25,7 +25,7 @@ RC_SELECT_BUDGET, RC_SELECT_THRESHOLD = 0, 1
 EXPORTS = [
     "rc_status_str", "rc_build_info", "rc_model_create", "rc_model_destroy", "rc_reuse_workspace_bytes",
     "rc_reuse", "rc_prefill_workspace_bytes", "rc_prefill", "rc_decode_workspace_bytes", "rc_decode_step", "rc_layer_profile", "rc_stage_workspace_bytes", "rc_rope_rerotate",
-    "rc_vdev_score", "rc_topk", "rc_threshold_select", "rc_final_select", "rc_sparse_attention", "rc_gemm_rows",
+    "rc_vdev_score", "rc_topk", "rc_threshold_select", "rc_final_select", "rc_sparse_attention", "rc_gemm_rows", "rc_gemm_rows_fused",
     "rc_scatter_paged", "rc_profile_enable", "rc_profile_class_count", "rc_profile_class_name", "rc_profile_read",
     "rc_tune_set", "rc_sparse_attention_workspace_bytes",
     "rc_gemm_workspace_bytes",
@@ -136,6 +136,8 @@ def _load() -> C.CDLL:
     lib.rc_sparse_attention_workspace_bytes.argtypes = [i32, i32, C.POINTER(rc_kv_layer)]
     lib.rc_gemm_rows.restype = C.c_int
     lib.rc_gemm_rows.argtypes = [i32, vp, vp, vp, i32, i32, i32, vp, sz, vp]
+    lib.rc_gemm_rows_fused.restype = C.c_int
+    lib.rc_gemm_rows_fused.argtypes = [i32, i32, vp, vp, vp, vp, i32, i32, i32, vp, sz, vp]
     lib.rc_gemm_workspace_bytes.restype = sz
     lib.rc_gemm_workspace_bytes.argtypes = []
     lib.rc_scatter_paged.restype = C.c_int
@@ -488,6 +490,17 @@ def rc_gemm_rows(dtype: int, a: torch.Tensor, w: torch.Tensor, c: torch.Tensor, 
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.rc_gemm_rows(dtype, _ptr(a), _ptr(w), _ptr(c), m, n, k, _ptr(workspace), nbytes, _stream(stream)),
            "rc_gemm_rows")
+
+
+RC_GEMM_STORE, RC_GEMM_STORE_T, RC_GEMM_ADD, RC_GEMM_SWIGLU = 0, 1, 2, 3
+
+
+def rc_gemm_rows_fused(dtype: int, epilogue: int, a: torch.Tensor, w: torch.Tensor, w2: Optional[torch.Tensor],
+                       c: torch.Tensor, m: int, n: int, k: int, workspace: Optional[torch.Tensor] = None,
+                       stream=None) -> None:
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.rc_gemm_rows_fused(dtype, epilogue, _ptr(a), _ptr(w), _ptr(w2), _ptr(c), m, n, k, _ptr(workspace),
+                                  nbytes, _stream(stream)), "rc_gemm_rows_fused")
 
 
 def rc_scatter_paged(k_rows: torch.Tensor, v_rows: torch.Tensor, pos: torch.Tensor, n: int, dst: rc_kv_layer,

@@ -1086,6 +1086,28 @@ rc_status rc_gemm_rows(int32_t dtype, const void* a, const void* w, float* c, in
   return RC_OK;
 }
 
+rc_status rc_gemm_rows_fused(int32_t dtype, int32_t epilogue, const void* a, const void* w, const void* w2, void* c,
+                             int32_t m, int32_t n, int32_t k, void* workspace, size_t workspace_bytes, void* stream) {
+  if (dtype != RC_F32 && dtype != RC_BF16) return RC_E_INVALID_ARG;
+  if (epilogue < RC_GEMM_STORE || epilogue > RC_GEMM_SWIGLU) return RC_E_INVALID_ARG;
+  if (!a || !w || !c || m < 0 || n < 1 || k < 1) return RC_E_INVALID_ARG;
+  if ((epilogue == RC_GEMM_SWIGLU) != (w2 != nullptr)) return RC_E_INVALID_ARG;
+  if (k % 8) return RC_E_UNSUPPORTED;
+  if (workspace && ((reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < rc_gemm_workspace_bytes()))
+    return RC_E_WORKSPACE;
+  if (m == 0) return RC_OK;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  static_assert((int)RC_GEMM_STORE == (int)EPI_STORE_F32 && (int)RC_GEMM_STORE_T == (int)EPI_STORE_T &&
+                (int)RC_GEMM_ADD == (int)EPI_ADD_F32 && (int)RC_GEMM_SWIGLU == (int)EPI_SWIGLU_T, "epilogue codes");
+  const GemmEpilogue epi = static_cast<GemmEpilogue>(epilogue);
+  if (dtype == RC_BF16)
+    RC_HIP(gemm_any<bf16>((const bf16*)a, (const bf16*)w, (const bf16*)w2, c, m, n, k, n, epi,
+                          reinterpret_cast<float*>(workspace), st));
+  else
+    RC_HIP(gemm_any<float>((const float*)a, (const float*)w, (const float*)w2, c, m, n, k, n, epi, nullptr, st));
+  return RC_OK;
+}
+
 rc_status rc_scatter_paged(const void* k_rows, const void* v_rows, const int32_t* pos, int32_t n,
                            const rc_kv_layer* dst, int32_t seq, void* stream) {
   RC_TRY(check_kv_layer(dst));

@@ -115,6 +115,9 @@ def test_stage_argument_errors():
     assert status(lambda: rc.rc_sparse_attention(s, idx, 1, 3, lay, 0, s, None)) == rc.RC_E_INVALID_ARG   # 3 % 2 heads
     assert status(lambda: rc.rc_sparse_attention(s, idx, 1, 2, lay, 5, s, None)) == rc.RC_E_CAPACITY
     assert status(lambda: rc.rc_gemm_rows(rc.RC_F32, s, s, s, 1, 1, 4, None)) == rc.RC_E_UNSUPPORTED      # k % 8
+    assert status(lambda: rc.rc_gemm_rows_fused(rc.RC_F32, 4, s, s, None, s, 1, 1, 8)) == rc.RC_E_INVALID_ARG   # epilogue
+    assert status(lambda: rc.rc_gemm_rows_fused(rc.RC_F32, rc.RC_GEMM_SWIGLU, s, s, None, s, 1, 1, 8)) == rc.RC_E_INVALID_ARG
+    assert status(lambda: rc.rc_gemm_rows_fused(rc.RC_F32, rc.RC_GEMM_ADD, s, s, s, s, 1, 1, 8)) == rc.RC_E_INVALID_ARG
     assert rc.rc_stage_workspace_bytes(10, 64) > 0
 
 

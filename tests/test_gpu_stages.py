@@ -233,6 +233,37 @@ def test_gemm_rows(dtype, m, n, k, tail_split):
     assert rel_err(to_np(c), want) <= 2e-6 * np.sqrt(k)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("epilogue", ["store_t", "add", "swiglu"])
+@pytest.mark.parametrize("m,n,k", [(51, 192, 256), (129, 1000, 688), (300, 258, 1408), (1639, 512, 1024),
+                                   (700, 2100, 512), (17, 4096, 1024)])
+def test_gemm_rows_fused(dtype, epilogue, m, n, k):
+    """The epilogues the layer applies in place: type-T store, residual add, SwiGLU of a gate/up pair."""
+    rc = _rc()
+    a = _rand((m, k), dtype, f"fa{m}{k}")
+    w = _rand((n, k), dtype, f"fw{n}{k}", 0.05)
+    w2 = _rand((n, k), dtype, f"fu{n}{k}", 0.05)
+    ws = rc.alloc_workspace(rc.rc_gemm_workspace_bytes()) if dtype == "bf16" else None
+    t = rc.rc_dtype_of(dtype)
+    prod = R.linear(a.astype(np.float64), w.astype(np.float64))
+    if epilogue == "add":
+        c0 = _rand((m, n), "f32", f"fc{m}{n}")
+        c = torch.from_numpy(c0).cuda()
+        rc.rc_gemm_rows_fused(t, rc.RC_GEMM_ADD, _up(a, dtype), _up(w, dtype), None, c, m, n, k, ws)
+        want, tol = c0.astype(np.float64) + prod, 2e-6 * np.sqrt(k)
+    elif epilogue == "store_t":
+        c = torch.zeros((m, n), dtype=torch.float32 if dtype == "f32" else torch.bfloat16, device="cuda")
+        rc.rc_gemm_rows_fused(t, rc.RC_GEMM_STORE_T, _up(a, dtype), _up(w, dtype), None, c, m, n, k, ws)
+        want, tol = prod, (2e-6 * np.sqrt(k) if dtype == "f32" else 4e-3)
+    else:
+        c = torch.zeros((m, n), dtype=torch.float32 if dtype == "f32" else torch.bfloat16, device="cuda")
+        rc.rc_gemm_rows_fused(t, rc.RC_GEMM_SWIGLU, _up(a, dtype), _up(w, dtype), _up(w2, dtype), c, m, n, k, ws)
+        want = R.silu(prod) * R.linear(a.astype(np.float64), w2.astype(np.float64))
+        tol = 4e-6 * np.sqrt(k) if dtype == "f32" else 4e-3     # bf16: one rounding of the stored product
+    torch.cuda.synchronize()
+    assert rel_err(to_np(c), want) <= tol
+
+
 # ------------------------------------------------------------------ K7
 @pytest.mark.parametrize("dtype,hkv,dh", [("f32", 2, 64), ("bf16", 8, 128)])
 @pytest.mark.parametrize("block_size", [0, 16])
