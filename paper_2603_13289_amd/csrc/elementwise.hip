@@ -418,38 +418,46 @@ vdev_score_kernel(const T* __restrict__ v_fresh, int fresh_row_stride, const T* 
   const int sub = lane % lph, hslot = lane / lph;
   const T* fresh = v_fresh + (size_t)(rq.row_base + rq.P + j) * fresh_row_stride;
   float dev_sum = 0.f;
-  for (int h0 = 0; h0 < g.n_kv_heads; h0 += hpp) {
-    const int head = h0 + hslot;
-    float a[VEC], b[VEC];
+  // two passes of heads at a time, so that four 16-byte loads per lane are in flight before the first reduction
+  for (int h0 = 0; h0 < g.n_kv_heads; h0 += 2 * hpp) {
+    float a[2][VEC], b[2][VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) a[e] = b[e] = 0.f;
-    if (head < g.n_kv_heads) {
-      Vec16<T>::load(v_pool + kv_row_offset(g, rq.dst_seq, rq.pos0 + rq.P + j, head) + sub * VEC, a);
-      Vec16<T>::load(fresh + head * g.head_dim + sub * VEC, b);
-    }
-    float dot = 0.f, na = 0.f, nb = 0.f;
+    for (int u = 0; u < 2; ++u) {
+      const int head = h0 + u * hpp + hslot;
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-      dot += a[e] * b[e];
-      na += a[e] * a[e];
-      nb += b[e] * b[e];
+      for (int e = 0; e < VEC; ++e) a[u][e] = b[u][e] = 0.f;
+      if (head < g.n_kv_heads) {
+        Vec16<T>::load(v_pool + kv_row_offset(g, rq.dst_seq, rq.pos0 + rq.P + j, head) + sub * VEC, a[u]);
+        Vec16<T>::load(fresh + head * g.head_dim + sub * VEC, b[u]);
+      }
     }
-    for (int o = lph >> 1; o > 0; o >>= 1) {
-      dot += __shfl_xor(dot, o, 64);
-      na += __shfl_xor(na, o, 64);
-      nb += __shfl_xor(nb, o, 64);
-    }
-    const float la = sqrtf(na), lb = sqrtf(nb);
-    const bool floored = la * lb < 1e-12f;
-    const float ra = floored ? 0.f : 1.0f / la, rb = floored ? 0.f : 1.0f / lb;
-    float dd = 0.f;
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-      const float t = a[e] * ra - b[e] * rb;
-      dd += t * t;
+    for (int u = 0; u < 2; ++u) {
+      const int head = h0 + u * hpp + hslot;
+      float dot = 0.f, na = 0.f, nb = 0.f;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        dot += a[u][e] * b[u][e];
+        na += a[u][e] * a[u][e];
+        nb += b[u][e] * b[u][e];
+      }
+      for (int o = lph >> 1; o > 0; o >>= 1) {
+        dot += __shfl_xor(dot, o, 64);
+        na += __shfl_xor(na, o, 64);
+        nb += __shfl_xor(nb, o, 64);
+      }
+      const float la = sqrtf(na), lb = sqrtf(nb);
+      const bool floored = la * lb < 1e-12f;
+      const float ra = floored ? 0.f : 1.0f / la, rb = floored ? 0.f : 1.0f / lb;
+      float dd = 0.f;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        const float t = a[u][e] * ra - b[u][e] * rb;
+        dd += t * t;
+      }
+      for (int o = lph >> 1; o > 0; o >>= 1) dd += __shfl_xor(dd, o, 64);
+      if (sub == 0 && head < g.n_kv_heads) dev_sum += floored ? 1.0f - dot / 1e-12f : 0.5f * dd;
     }
-    for (int o = lph >> 1; o > 0; o >>= 1) dd += __shfl_xor(dd, o, 64);
-    if (sub == 0 && head < g.n_kv_heads) dev_sum += floored ? 1.0f - dot / 1e-12f : 0.5f * dd;
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) dev_sum += __shfl_xor(dev_sum, o, 64);
