@@ -33,6 +33,7 @@ static constexpr int BKV = 64;   // keys per tile
 static constexpr int DH = 128;
 static constexpr int KROW = DH * 2 + 16;   // bytes between K rows in LDS
 static constexpr int VROW = BKV * 2 + 16;  // bytes between V^T rows in LDS
+static constexpr int kFragAhead = 4;       // LDS operand fragments in flight ahead of the MFMA that uses them
 
 // SCORES: additionally write every visible score q.k / sqrt(dh) of every valid row to
 // scores[(row * n_q_heads + head) * scores_len + key] (the decode-side influence accumulation reads them).
@@ -53,9 +54,12 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   // late tiles see the most keys: start them first.  With sp.n_chunks > 1 the KV range of a long query
   // tile is cut into chunks of sp.chunk_tiles tiles, one workgroup each, whose partial results are merged
   // by attn_merge_kernel; short tiles are done whole by their chunk-0 workgroup.
-  const int tile = total_tiles - 1 - (int)blockIdx.x / sp.n_chunks;
-  const int chunk = (int)blockIdx.x % sp.n_chunks;
-  const int kvh = blockIdx.y;
+  // The KV head varies fastest: workgroups are then dispatched in order of decreasing KV range over the whole
+  // grid (a longest-first schedule), and with 8 KV heads every XCD (workgroup id mod 8) keeps to one head's K/V.
+  const int kvh = (int)blockIdx.x % g.n_kv_heads;
+  const int item = (int)blockIdx.x / g.n_kv_heads;
+  const int tile = total_tiles - 1 - item / sp.n_chunks;
+  const int chunk = item % sp.n_chunks;
   const int n_q_heads = g.n_kv_heads * G;
   int r0, n_valid, seq, split_tile = tile, part_base = 0;   // split_tile < 0: this tile is never split
   if (table) {
@@ -196,18 +200,35 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
     __syncthreads();
     if (t + 2 < t_end) fetch(kv0 + 2 * BKV, set);
 
-    // S^T = K Q^T : two blocks of 32 keys
+    // S^T = K Q^T : two blocks of 32 keys.  The two accumulator chains alternate and the K fragments are read
+    // kFragAhead MFMAs ahead of their use, so that neither the LDS latency nor the MFMA dependency is exposed.
     f32x16 acc_s[2];
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc_s[b][e] = 0.f;
+    {
+      auto k_frag = [&](int i) {   // step i: key block i & 1, head-dim step i >> 1
+        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(k_rd + (i & 1) * 32 * KROW + (i >> 1) * 32));
+      };
+      bf16x8 kf[kFragAhead];
 #pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(k_rd + b * 32 * KROW + s * 32));
-        acc_s[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], acc_s[b], 0, 0, 0);
+      for (int i = 0; i < kFragAhead; ++i) kf[i] = k_frag(i);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        acc_s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % kFragAhead], qf[i >> 1], acc_s[i & 1], 0, 0, 0);
+        if (i + kFragAhead < 16) kf[i % kFragAhead] = k_frag(i + kFragAhead);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
+    // the first V^T fragments do not depend on the softmax: their LDS reads run under it
+    auto v_frag = [&](int i) {     // step i: head-dim block i & 3, key step i >> 2
+      return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(v_rd + (i & 3) * 32 * VROW + (i >> 2) * 32));
+    };
+    bf16x8 vf[kFragAhead];
+#pragma unroll
+    for (int i = 0; i < kFragAhead; ++i) vf[i] = v_frag(i);
     // running softmax on raw scores; the 1/sqrt(dh) * log2(e) factor is folded into the exponent.
     // Element e of block b is key kv0 + 32 b + 8 (e/4) + 4 half + e%4.  Only tiles that reach above the
     // tile's first query position need the causal mask.
@@ -268,14 +289,11 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
         pf[2 * b + u] = __builtin_convertvector(p, bf16x8);
       }
     l_run += psum;
-    // O^T += V^T P
+    // O^T += V^T P : four accumulator chains alternate, fragments read kFragAhead MFMAs ahead
 #pragma unroll
-    for (int db = 0; db < 4; ++db) {
-#pragma unroll
-      for (int tt = 0; tt < 4; ++tt) {
-        const bf16x8 vf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(v_rd + db * 32 * VROW + tt * 32));
-        acc_o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[tt], acc_o[db], 0, 0, 0);
-      }
+    for (int i = 0; i < 16; ++i) {
+      acc_o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % kFragAhead], pf[i >> 2], acc_o[i & 3], 0, 0, 0);
+      if (i + kFragAhead < 16) vf[i % kFragAhead] = v_frag(i + kFragAhead);
     }
   };
   for (int t = t_begin; t < t_end; t += 2) {
@@ -373,7 +391,7 @@ template <int G>
 static hipError_t launch_g(const bf16* q, const int* row_pos, const ReqTable* table, int fixed_seq, int total_rows,
                            int total_tiles, const bf16* k_pool, const bf16* v_pool, KvGeom g, bf16* out,
                            AttnSplit sp, float* part, float* scores, int scores_len, hipStream_t st) {
-  dim3 grid((unsigned)(total_tiles * sp.n_chunks), (unsigned)g.n_kv_heads);
+  dim3 grid((unsigned)(total_tiles * sp.n_chunks * g.n_kv_heads));
   float* part_o = part;
   float2* part_ml = reinterpret_cast<float2*>(part + (size_t)sp.total_slots * g.n_kv_heads * G * BQ * DH);
   if (scores)
