@@ -34,6 +34,7 @@ static constexpr int DH = 128;
 static constexpr int KROW = DH * 2 + 16;   // bytes between K rows in LDS
 static constexpr int VROW = BKV * 2 + 16;  // bytes between V^T rows in LDS
 static constexpr int kFragAhead = 4;       // LDS operand fragments in flight ahead of the MFMA that uses them
+static constexpr float kRescaleSlack = 8.f;   // log2 units the running maximum may lead the reference exponent
 
 // SCORES: additionally write every visible score q.k / sqrt(dh) of every valid row to
 // scores[(row * n_q_heads + head) * scores_len + key] (the decode-side influence accumulation reads them).
@@ -261,12 +262,16 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
 #pragma unroll
       for (int e = 0; e < 16; ++e) mx = fmaxf(mx, acc_s[b][e]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    // m_run is kept in the scaled (log2) domain.  A row that has not seen a visible key yet keeps
-    // m_run = -inf; m_use avoids inf - inf in that case (all its p are then 0).
+    // m_run is the reference exponent of the running sums, in the scaled (log2) domain.  It follows the
+    // running maximum lazily: the sums are rescaled (64 multiplies per lane) only when some row's maximum has
+    // grown by more than kRescaleSlack since its last rescale, so p stays below 2^kRescaleSlack instead of 1.
+    // Any reference gives the same quotient O / l; bf16 keeps p's relative precision at every magnitude.
+    // A row that has not seen a visible key yet keeps m_run = -inf; m_use avoids inf - inf in that case
+    // (all its p are then 0).
     const float m_new = fmaxf(m_run, mx * c_scale);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    if (__any(m_new > m_run)) {          // wave-uniform: rescale only when some row's maximum moved
-      const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
+    if (__any(m_new > m_run + kRescaleSlack)) {   // wave-uniform
+      const float m_to = (m_new == -INFINITY) ? 0.f : m_new;
+      const float corr = __builtin_amdgcn_exp2f(m_run - m_to);
       l_run *= corr;
 #pragma unroll
       for (int i = 0; i < 4; ++i)
@@ -274,6 +279,7 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
         for (int e = 0; e < 16; ++e) acc_o[i][e] *= corr;
       m_run = m_new;
     }
+    const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
     float psum = 0.f;
     bf16x8 pf[4];
 #pragma unroll
