@@ -33,6 +33,9 @@ static constexpr int BKV = 64;   // keys per tile
 static constexpr int DH = 128;
 static constexpr int KROW = DH * 2 + 16;   // bytes between K rows in LDS
 static constexpr int VROW = BKV * 2 + 16;  // bytes between V^T rows in LDS
+static constexpr int K_TILE_BYTES = BKV * KROW;
+static constexpr int V_TILE_BYTES = DH * VROW;
+static constexpr int ATTN_LDS_BYTES = 2 * (K_TILE_BYTES + V_TILE_BYTES);
 static constexpr int kFragAhead = 4;       // LDS operand fragments in flight ahead of the MFMA that uses them
 static constexpr float kRescaleSlack = 8.f;   // log2 units the running maximum may lead the reference exponent
 
@@ -49,8 +52,11 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   // K rows are 256 + 16 bytes, V^T rows 128 + 16 bytes apart.  With 64 banks of 4 bytes, the 16 lanes
   // that fetch the same 16-byte chunk of 16 consecutive rows then hit every bank exactly once, and every
   // LDS address in the main loop is a per-thread base plus a compile-time constant.
-  __shared__ __attribute__((aligned(16))) unsigned char lds_k[BKV * KROW];
-  __shared__ __attribute__((aligned(16))) unsigned char lds_vt[DH * VROW];
+  // Two K and two V^T buffers: tile t lives in buffer t % 2 and tile t + 1 is staged while tile t is multiplied,
+  // so one barrier per tile suffices.
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_attn[];
+  unsigned char* const lds_k = lds_attn;                         // [2][BKV * KROW]
+  unsigned char* const lds_vt = lds_attn + 2 * K_TILE_BYTES;     // [2][DH * VROW]
 
   // late tiles see the most keys: start them first.  With sp.n_chunks > 1 the KV range of a long query
   // tile is cut into chunks of sp.chunk_tiles tiles, one workgroup each, whose partial results are merged
@@ -122,20 +128,18 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
     kbase = k_pool + o + kch * 8;
     vbase = v_pool + o;
   }
-  // two register sets: the tile fetched at step t is staged at step t + 2, so a fetch has two multiply phases
-  // to arrive
-  uint4 rk[2][KPER], rv[2][VPER][4];
-  auto fetch = [&](int kv0, auto set) {
-    constexpr int SET = decltype(set)::value;
+  // the tile fetched during step t is staged during step t + 1 and multiplied in step t + 2
+  uint4 rk[KPER], rv[VPER][4];
+  auto fetch = [&](int kv0) {
     const bool full = kv0 + BKV - 1 <= last_pos;   // uniform: only a query tile's last KV tile can be ragged
 #pragma unroll
     for (int i = 0; i < KPER; ++i) {
       const int row = krow0 + i * KSTEP;
       const int pos = kv0 + row;
-      rk[SET][i] = make_uint4(0, 0, 0, 0);
+      rk[i] = make_uint4(0, 0, 0, 0);
       if (row < BKV && (full || pos <= last_pos)) {
         const bf16* src = contig ? kbase + (size_t)pos * DH : k_pool + kv_row_offset(g, seq, pos, kvh) + kch * 8;
-        rk[SET][i] = *reinterpret_cast<const uint4*>(src);
+        rk[i] = *reinterpret_cast<const uint4*>(src);
       }
     }
 #pragma unroll
@@ -144,10 +148,10 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         const int pos = kv0 + vquad * 4 + kk;
-        rv[SET][i][kk] = make_uint4(0, 0, 0, 0);
+        rv[i][kk] = make_uint4(0, 0, 0, 0);
         if (dch < 16 && (full || pos <= last_pos)) {
           const bf16* src = contig ? vbase + (size_t)pos * DH + dch * 8 : v_pool + kv_row_offset(g, seq, pos, kvh) + dch * 8;
-          rv[SET][i][kk] = *reinterpret_cast<const uint4*>(src);
+          rv[i][kk] = *reinterpret_cast<const uint4*>(src);
         }
       }
     }
@@ -157,18 +161,18 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   const int vcol = (vkey0 & ~15) + 8 * ((vkey0 >> 2) & 1) + 4 * ((vkey0 >> 3) & 1);
   unsigned char* const k_wr = lds_k + krow0 * KROW + kch * 16;
   unsigned char* const v_wr = lds_vt + vdch0 * 8 * VROW + vcol * 2;
-  auto stage = [&](auto set) {
-    constexpr int SET = decltype(set)::value;
+  auto stage = [&](auto buf) {
+    constexpr int KOFF = decltype(buf)::value * K_TILE_BYTES, VOFF = decltype(buf)::value * V_TILE_BYTES;
 #pragma unroll
     for (int i = 0; i < KPER; ++i)
-      if (krow0 + i * KSTEP < BKV) *reinterpret_cast<uint4*>(k_wr + i * KSTEP * KROW) = rk[SET][i];
+      if (krow0 + i * KSTEP < BKV) *reinterpret_cast<uint4*>(k_wr + KOFF + i * KSTEP * KROW) = rk[i];
 #pragma unroll
     for (int i = 0; i < VPER; ++i) {
       if (vdch0 + i * KSTEP >= 16) continue;
-      const uint32_t w[4][4] = {{rv[SET][i][0].x, rv[SET][i][0].y, rv[SET][i][0].z, rv[SET][i][0].w},
-                                {rv[SET][i][1].x, rv[SET][i][1].y, rv[SET][i][1].z, rv[SET][i][1].w},
-                                {rv[SET][i][2].x, rv[SET][i][2].y, rv[SET][i][2].z, rv[SET][i][2].w},
-                                {rv[SET][i][3].x, rv[SET][i][3].y, rv[SET][i][3].z, rv[SET][i][3].w}};
+      const uint32_t w[4][4] = {{rv[i][0].x, rv[i][0].y, rv[i][0].z, rv[i][0].w},
+                                {rv[i][1].x, rv[i][1].y, rv[i][1].z, rv[i][1].w},
+                                {rv[i][2].x, rv[i][2].y, rv[i][2].z, rv[i][2].w},
+                                {rv[i][3].x, rv[i][3].y, rv[i][3].z, rv[i][3].w}};
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int wi = e >> 1;
@@ -177,7 +181,7 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
         uint2 pk;
         pk.x = __builtin_amdgcn_perm(w[1][wi], w[0][wi], sel);
         pk.y = __builtin_amdgcn_perm(w[3][wi], w[2][wi], sel);
-        *reinterpret_cast<uint2*>(v_wr + (i * KSTEP * 8 + e) * VROW) = pk;
+        *reinterpret_cast<uint2*>(v_wr + VOFF + (i * KSTEP * 8 + e) * VROW) = pk;
       }
     }
   };
@@ -190,16 +194,22 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   const int t_begin = is_split ? chunk * sp.chunk_tiles : 0;
   const int t_end = is_split ? min(n_kv_tiles, t_begin + sp.chunk_tiles) : n_kv_tiles;
   if (t_begin >= t_end || (!is_split && chunk != 0)) return;   // nothing for this workgroup (uniform)
-  const std::integral_constant<int, 0> set0;
-  const std::integral_constant<int, 1> set1;
-  fetch(t_begin * BKV, set0);
-  if (t_begin + 1 < t_end) fetch((t_begin + 1) * BKV, set1);
-  auto tile_step = [&](int t, auto set) {
+  const std::integral_constant<int, 0> buf0;
+  const std::integral_constant<int, 1> buf1;
+  // prologue: the first tile goes to buffer 0, the second one is on its way in registers
+  fetch(t_begin * BKV);
+  stage(buf0);
+  if (t_begin + 1 < t_end) fetch((t_begin + 1) * BKV);
+  __syncthreads();
+  // step i (tile t = t_begin + i) multiplies buffer i % 2; before that it stages tile t + 1 into the other buffer
+  // (free since the barrier that ended step i - 1) and starts the loads of tile t + 2
+  auto tile_step = [&](int t, auto buf) {
+    constexpr int KOFF = decltype(buf)::value * K_TILE_BYTES, VOFF = decltype(buf)::value * V_TILE_BYTES;
     const int kv0 = t * BKV;
-    __syncthreads();   // previous tile fully consumed
-    stage(set);
-    __syncthreads();
-    if (t + 2 < t_end) fetch(kv0 + 2 * BKV, set);
+    if (t + 1 < t_end) {
+      stage(std::integral_constant<int, 1 - decltype(buf)::value>());
+      if (t + 2 < t_end) fetch(kv0 + 2 * BKV);
+    }
 
     // S^T = K Q^T : two blocks of 32 keys.  The two accumulator chains alternate and the K fragments are read
     // kFragAhead MFMAs ahead of their use, so that neither the LDS latency nor the MFMA dependency is exposed.
@@ -210,7 +220,7 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
       for (int e = 0; e < 16; ++e) acc_s[b][e] = 0.f;
     {
       auto k_frag = [&](int i) {   // step i: key block i & 1, head-dim step i >> 1
-        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(k_rd + (i & 1) * 32 * KROW + (i >> 1) * 32));
+        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(k_rd + KOFF + (i & 1) * 32 * KROW + (i >> 1) * 32));
       };
       bf16x8 kf[kFragAhead];
 #pragma unroll
@@ -225,7 +235,7 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
     }
     // the first V^T fragments do not depend on the softmax: their LDS reads run under it
     auto v_frag = [&](int i) {     // step i: head-dim block i & 3, key step i >> 2
-      return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(v_rd + (i & 3) * 32 * VROW + (i >> 2) * 32));
+      return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(v_rd + VOFF + (i & 3) * 32 * VROW + (i >> 2) * 32));
     };
     bf16x8 vf[kFragAhead];
 #pragma unroll
@@ -301,10 +311,11 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
       acc_o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % kFragAhead], pf[i >> 2], acc_o[i & 3], 0, 0, 0);
       if (i + kFragAhead < 16) vf[i % kFragAhead] = v_frag(i + kFragAhead);
     }
+    __syncthreads();   // tile t fully consumed, tile t + 1 fully staged
   };
   for (int t = t_begin; t < t_end; t += 2) {
-    tile_step(t, set0);
-    if (t + 1 < t_end) tile_step(t + 1, set1);
+    tile_step(t, buf0);
+    if (t + 1 < t_end) tile_step(t + 1, buf1);
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -400,12 +411,21 @@ static hipError_t launch_g(const bf16* q, const int* row_pos, const ReqTable* ta
   dim3 grid((unsigned)(total_tiles * sp.n_chunks * g.n_kv_heads));
   float* part_o = part;
   float2* part_ml = reinterpret_cast<float2*>(part + (size_t)sp.total_slots * g.n_kv_heads * G * BQ * DH);
+  // more than the 64 KB a kernel gets without asking
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<G, true>, hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_LDS_BYTES);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void*)attn_mfma_kernel<G, false>, hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
   if (scores)
-    attn_mfma_kernel<G, true><<<grid, 64 * G, 0, st>>>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool,
-                                                       v_pool, g, out, sp, part_o, part_ml, scores, scores_len);
+    attn_mfma_kernel<G, true><<<grid, 64 * G, ATTN_LDS_BYTES, st>>>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool,
+                                                                    v_pool, g, out, sp, part_o, part_ml, scores, scores_len);
   else
-    attn_mfma_kernel<G, false><<<grid, 64 * G, 0, st>>>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool,
-                                                        v_pool, g, out, sp, part_o, part_ml, nullptr, 0);
+    attn_mfma_kernel<G, false><<<grid, 64 * G, ATTN_LDS_BYTES, st>>>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool,
+                                                                     v_pool, g, out, sp, part_o, part_ml, nullptr, 0);
   return hipGetLastError();
 }
 
