@@ -39,6 +39,15 @@ static constexpr int ATTN_LDS_BYTES = 2 * (K_TILE_BYTES + V_TILE_BYTES);
 static constexpr int kFragAhead = 4;       // LDS operand fragments in flight ahead of the MFMA that uses them
 static constexpr float kRescaleSlack = 8.f;   // log2 units the running maximum may lead the reference exponent
 
+// Maximum over the lane pair (l, l ^ 32).  v_permlane32_swap exchanges the upper half of its first operand with
+// the lower half of its second; fed the same value twice it returns (lower half, lower half) and (upper half,
+// upper half), so the maximum of the two results is the pair's maximum in every lane, without an LDS round trip.
+__device__ inline float pair_max32(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 // SCORES: additionally write every visible score q.k / sqrt(dh) of every valid row to
 // scores[(row * n_q_heads + head) * scores_len + key] (the decode-side influence accumulation reads them).
 template <int G, bool SCORES>
@@ -271,7 +280,7 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int e = 0; e < 16; ++e) mx = fmaxf(mx, acc_s[b][e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    mx = pair_max32(mx);
     // m_run is the reference exponent of the running sums, in the scaled (log2) domain.  It follows the
     // running maximum lazily: the sums are rescaled (64 multiplies per lane) only when some row's maximum has
     // grown by more than kRescaleSlack since its last rescale, so p stays below 2^kRescaleSlack instead of 1.
