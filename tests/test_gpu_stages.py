@@ -210,6 +210,53 @@ def test_sparse_attention(dtype, hq, hkv, dh, block_size, split):
     assert rel_err(to_np(out)[0, 0], vs[1][0, 0]) <= (1e-6 if dtype == "f32" else 4e-3)
 
 
+@pytest.mark.parametrize("case", ["growing", "shrinking", "flat", "spiky"])
+@pytest.mark.parametrize("split", [False, True])
+def test_sparse_attention_wide_score_range(case, split):
+    """Scores whose running maximum moves by far more (or less) than the slack the bf16 kernel allows before it
+    rescales its running sums: logits that grow or fall along the context, identical scores, rare spikes."""
+    rc = _rc()
+    hq, hkv, dh, T = 8, 2, 128, 1500
+    g = stream_rng("stage", f"att_range_{case}")
+    k = g.standard_normal((T, hkv, dh), dtype=np.float32)
+    v = g.standard_normal((T, hkv, dh), dtype=np.float32)
+    ramp = np.linspace(0.05, 3.0, T, dtype=np.float32)[:, None, None]
+    if case == "growing":
+        k = np.abs(k) * ramp               # against an all-positive query: logits rise along the context
+    elif case == "shrinking":
+        k = np.abs(k) * ramp[::-1]
+    elif case == "flat":
+        k[:] = 0.0                         # every visible key gets the same weight: output = mean of V
+    else:
+        k *= 0.1
+        k[g.choice(T, size=12, replace=False)] *= 60.0
+    k, v = round_to_bf16(k), round_to_bf16(v)
+    kv = rc.PagedKV.contiguous(1, 1, T, hkv, dh, rc.RC_BF16)
+    kv.write("k", 0, 0, _up(k, "bf16"))
+    kv.write("v", 0, 0, _up(v, "bf16"))
+    pos = np.sort(np.concatenate([np.arange(0, 40), g.choice(np.arange(40, T), size=85, replace=False), [T - 1]]))
+    n = len(pos)
+    q = round_to_bf16(np.abs(g.standard_normal((n, hq, dh), dtype=np.float32)) * (1.5 if case != "spiky" else 1.0))
+    out = torch.zeros((n, hq, dh), dtype=torch.bfloat16, device="cuda")
+    ws = None
+    if split:
+        rc.rc_tune_set(rc.RC_TUNE_ATTN_CHUNK_TILES, 4)
+        ws = rc.alloc_workspace(rc.rc_sparse_attention_workspace_bytes(n, hq, kv.layer(0)))
+    try:
+        rc.rc_sparse_attention(_up(q, "bf16"), torch.from_numpy(pos.astype(np.int32)).cuda(), n, hq, kv.layer(0), 0,
+                               out, ws)
+        torch.cuda.synchronize()
+    finally:
+        rc.rc_tune_set(rc.RC_TUNE_ATTN_CHUNK_TILES, 0)
+    got = to_np(out)
+    assert np.isfinite(got).all()
+    want = R.causal_gqa_attention(q.astype(np.float64), pos, k.astype(np.float64), v.astype(np.float64))
+    assert rel_err(got, want) <= 1e-2
+    if case == "flat":
+        want_mean = np.stack([v[: p + 1].astype(np.float64).mean(axis=0) for p in pos])      # [n][hkv][dh]
+        assert rel_err(got, np.repeat(want_mean, hq // hkv, axis=1)) <= 1e-2
+
+
 # ------------------------------------------------------------------ K3
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("m,n,k", [(1, 64, 64), (51, 192, 256), (129, 1000, 688), (300, 257, 1408), (1639, 512, 1024),
