@@ -269,7 +269,7 @@ RC_API rc_status rc_profile_read(float* ms, int32_t* launches);
 
 /* Tuning knobs (process-global).  RC_TUNE_GEMM_TILE: kernel / workgroup tile of the bf16 projection GEMM,
  * 0 = chosen per shape (default); register-staged tiles 1 = 128x256, 2 = 256x256, 3 = 128x128;
- * direct-to-LDS tiles 5 = 256x256 (with the K-split tail), 6 = 128x128. */
+ * direct-to-LDS tiles 5 = 256x256 (with the K-split tail), 6 = 128x128, 7 = 256x192 (K-split tail). */
 #define RC_TUNE_GEMM_TILE 1
 /* RC_TUNE_ATTN_CHUNK_TILES: KV tiles (of 64 keys) per attention workgroup when a query tile's KV range is
  * split; 0 = chosen per shape (default), a value beyond the context length disables the split. */

@@ -493,23 +493,23 @@ gemm_fixup_kernel(void* __restrict__ c, int m, int n, int ldc, int epi, TileOrde
 }
 
 // Rough time model (microseconds, measured on MI355X) used to choose the tile and the K-split of the tail:
-// one K step of a full round costs kStep256 with 256x256 tiles (one workgroup per CU) and kStep128 with
-// 128x128 tiles (two per CU); summing one 256x256 tile part in the fix-up costs kFixPart.
-static constexpr float kStep256 = 1.9f, kStep128 = 1.2f, kFixPart = 0.1f, kFixLaunch = 6.f;
+// one K step of a full round costs kStep256 with 256x256 tiles, kStep192 with 256x192 tiles (one workgroup per
+// CU each) and kStep128 with 128x128 tiles (two per CU); summing one tile part in the fix-up costs kFixPart.
+static constexpr float kStep256 = 1.9f, kStep192 = 1.55f, kStep128 = 1.2f, kFixPart = 0.1f, kFixLaunch = 6.f;
 
 struct SplitPlan { int rem, split; float cost; };
 // total tiles over `slots` workgroup slots: full rounds, then `rem` tiles cut into `split` K parts each
-static SplitPlan plan_tail_split(int total, int slots, int ksteps) {
+static SplitPlan plan_tail_split(int total, int slots, int ksteps, float step = kStep256) {
   SplitPlan best;
   best.rem = total % slots;
   best.split = 1;
   const int full_rounds = total / slots;
-  best.cost = (full_rounds + (best.rem > 0 ? 1 : 0)) * ksteps * kStep256;
+  best.cost = (full_rounds + (best.rem > 0 ? 1 : 0)) * ksteps * step;
   if (best.rem == 0) return best;
   const int gmax = std::min(std::min(slots / best.rem, 16), ksteps);
   for (int g = 2; g <= gmax; ++g) {
     if (best.rem * g > 256) break;
-    const float c = full_rounds * ksteps * kStep256 + ((ksteps + g - 1) / g) * kStep256 + best.rem * g * kFixPart + kFixLaunch;
+    const float c = full_rounds * ksteps * step + ((ksteps + g - 1) / g) * step + best.rem * g * kFixPart + kFixLaunch;
     if (c < best.cost) { best.cost = c; best.split = g; }
   }
   return best;
@@ -541,7 +541,7 @@ static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const 
   const int ksteps = k / BK;
   int full_tiles = total, split = 1, kpp = ksteps;
   if (partial && OCC == 1) {
-    const SplitPlan sp = plan_tail_split(total, slots, ksteps);
+    const SplitPlan sp = plan_tail_split(total, slots, ksteps, BN == 192 ? kStep192 : kStep256);
     if (sp.split > 1) {
       full_tiles = total - sp.rem;
       kpp = (ksteps + sp.split - 1) / sp.split;
@@ -580,7 +580,7 @@ static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const 
   return hipGetLastError();
 }
 
-static int g_gemm_tile = 0;   // 0: by shape; 1-3: register-staged 128x256 / 256x256 / 128x128; 5, 6: direct-to-LDS 256x256 / 128x128
+static int g_gemm_tile = 0;   // 0: by shape; 1-3: register-staged 128x256 / 256x256 / 128x128; 5-7: direct-to-LDS 256x256 / 128x128 / 256x192
 void set_gemm_tile(int t) { g_gemm_tile = t; }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int OCC>
@@ -625,12 +625,21 @@ static hipError_t dispatch(const bf16* a, const bf16* w, const bf16* w2, const b
       const float cost6 = (t6 / slots6) * ksteps * kStep128 +
                           (last6 == 0 ? 0.f : (last6 * 2 <= slots6 ? 0.65f : 1.f) * ksteps * kStep128);
       tile = cost5 <= cost6 ? 5 : 6;
+      // 256x192 tiles where they cover N exactly (the fused q|k|v projection: 6144 = 32 x 192): a launch of a
+      // few hundred rows then has a third more tiles to spread over the CUs
+      if (!dual && n % 192 == 0) {
+        const int t7 = ((m + 255) / 256) * (n / 192);
+        const float cost7 = partial ? plan_tail_split(t7, num_cus(), ksteps, kStep192).cost
+                                    : ((t7 + num_cus() - 1) / num_cus()) * ksteps * kStep192;
+        if (cost7 < std::min(cost5, cost6)) tile = 7;
+      }
     }
   }
   if (tile >= 5 && (k % BK) != 0) tile = 3;   // the direct-load kernels need whole K steps
   switch (tile) {
     case 5: return launch_dl<256, 256, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st);
     case 6: return launch_dl<128, 128, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, nullptr, st);
+    case 7: return launch_dl<256, 192, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st);
     case 2: return launch_cfg<256, 256, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);
     case 3: return launch_cfg<128, 128, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);
     default: return launch_cfg<128, 256, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);

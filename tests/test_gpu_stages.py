@@ -280,6 +280,40 @@ def test_gemm_rows(dtype, m, n, k, tail_split):
     assert rel_err(to_np(c), want) <= 2e-6 * np.sqrt(k)
 
 
+@pytest.mark.parametrize("tile", [5, 6, 7])
+@pytest.mark.parametrize("epilogue", ["store", "add", "swiglu"])
+@pytest.mark.parametrize("m,n,k", [(300, 258, 1408), (1639, 576, 1024), (700, 2100, 512), (2049, 6144, 256)])
+def test_gemm_forced_tile_shapes(tile, epilogue, m, n, k):
+    """Every direct-to-LDS tile shape of the bf16 GEMM (normally chosen per launch by a time model), with the
+    K-split tail where the shape has one."""
+    rc = _rc()
+    a = _rand((m, k), "bf16", f"ta{m}{k}")
+    w = _rand((n, k), "bf16", f"tw{n}{k}", 0.05)
+    w2 = _rand((n, k), "bf16", f"tu{n}{k}", 0.05)
+    ws = rc.alloc_workspace(rc.rc_gemm_workspace_bytes())
+    prod = R.linear(a.astype(np.float64), w.astype(np.float64))
+    rc.rc_tune_set(rc.RC_TUNE_GEMM_TILE, tile)
+    try:
+        if epilogue == "store":
+            c = torch.zeros((m, n), dtype=torch.float32, device="cuda")
+            rc.rc_gemm_rows(rc.RC_BF16, _up(a, "bf16"), _up(w, "bf16"), c, m, n, k, ws)
+            want, tol = prod, 2e-6 * np.sqrt(k)
+        elif epilogue == "add":
+            c0 = _rand((m, n), "f32", f"tc{m}{n}")
+            c = torch.from_numpy(c0).cuda()
+            rc.rc_gemm_rows_fused(rc.RC_BF16, rc.RC_GEMM_ADD, _up(a, "bf16"), _up(w, "bf16"), None, c, m, n, k, ws)
+            want, tol = c0.astype(np.float64) + prod, 2e-6 * np.sqrt(k)
+        else:
+            c = torch.zeros((m, n), dtype=torch.bfloat16, device="cuda")
+            rc.rc_gemm_rows_fused(rc.RC_BF16, rc.RC_GEMM_SWIGLU, _up(a, "bf16"), _up(w, "bf16"), _up(w2, "bf16"), c,
+                                  m, n, k, ws)
+            want, tol = R.silu(prod) * R.linear(a.astype(np.float64), w2.astype(np.float64)), 4e-3
+        torch.cuda.synchronize()
+    finally:
+        rc.rc_tune_set(rc.RC_TUNE_GEMM_TILE, 0)
+    assert rel_err(to_np(c), want) <= tol
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("epilogue", ["store_t", "add", "swiglu"])
 @pytest.mark.parametrize("m,n,k", [(51, 192, 256), (129, 1000, 688), (300, 258, 1408), (1639, 512, 1024),
