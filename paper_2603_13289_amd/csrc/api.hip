@@ -535,7 +535,7 @@ rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
                                  scores_from_attention ? w.inf_scratch : nullptr, job.max_pos));
     if (job.any_inf)
       RC_LAUNCH(PC_INFLUENCE, launch_influence_finish(w.row_pos, w.row_req, rows, d.n_q_heads, job.max_pos, job.inf,
-                                                      w.inf_scratch, st));
+                                                      w.inf_scratch, scores_from_attention, st));
     RC_LAUNCH(PC_GEMM_O, gemm_any<T>((const T*)w.o, (const T*)lw.wo, nullptr, h, rows, D, nq, D, EPI_ADD_F32, w.gemm_part, st));
     RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(h, (const T*)lw.g_ffn, (T*)w.a, rows, D, d.rms_eps, st));
     RC_LAUNCH(PC_GEMM_GATE_UP, gemm_any<T>((const T*)w.a, (const T*)lw.w_gate, (const T*)lw.w_up, w.act, rows, F, D, F, EPI_SWIGLU_T, w.gemm_part, st));

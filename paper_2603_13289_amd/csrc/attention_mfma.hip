@@ -49,14 +49,16 @@ __device__ inline float pair_max32(float x) {
 }
 
 // SCORES: additionally write every visible score q.k / sqrt(dh) of every valid row to
-// scores[(row * n_q_heads + head) * scores_len + key] (the decode-side influence accumulation reads them).
+// scores[(row * n_q_heads + head) * scores_len + key] (the decode-side influence accumulation reads them), and
+// the row's reference exponent and sum, score_ml[row * n_q_heads + head], unless the tile's KV range is split
+// (then attn_merge_kernel writes the merged pair).
 template <int G, bool SCORES>
 __global__ void __launch_bounds__(64 * G, (G <= 4 ? 2 : 1))
 attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, const ReqTable* __restrict__ table,
                  int fixed_seq, int total_rows, int total_tiles, const bf16* __restrict__ k_pool,
                  const bf16* __restrict__ v_pool, KvGeom g, bf16* __restrict__ out, AttnSplit sp,
                  float* __restrict__ part_o, float2* __restrict__ part_ml, float* __restrict__ scores,
-                 int scores_len) {
+                 int scores_len, float2* __restrict__ score_ml) {
   constexpr int NT = 64 * G;
   // K rows are 256 + 16 bytes, V^T rows 128 + 16 bytes apart.  With 64 banks of 4 bytes, the 16 lanes
   // that fetch the same 16-byte chunk of 16 consecutive rows then hit every bank exactly once, and every
@@ -344,6 +346,7 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
     return;
   }
   if (q_ok) {
+    if (SCORES && half == 0) score_ml[(size_t)my_row * n_q_heads + head] = make_float2(m_run, l_tot);
     const float inv = 1.0f / l_tot;
     bf16* orow = out + ((size_t)my_row * n_q_heads + head) * DH;
 #pragma unroll
@@ -365,7 +368,7 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
 __global__ void __launch_bounds__(256)
 attn_merge_kernel(const int* __restrict__ row_pos, const int* __restrict__ row_req, const ReqTable* __restrict__ table,
                   int total_rows, int n_q_heads, AttnSplit sp, const float* __restrict__ part_o,
-                  const float2* __restrict__ part_ml, bf16* __restrict__ out) {
+                  const float2* __restrict__ part_ml, bf16* __restrict__ out, float2* __restrict__ score_ml) {
   const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (item >= total_rows * n_q_heads) return;
@@ -400,6 +403,7 @@ attn_merge_kernel(const int* __restrict__ row_pos, const int* __restrict__ row_r
     o0 += o.x * wgt;
     o1 += o.y * wgt;
   }
+  if (score_ml && lane == 0) score_ml[(size_t)r * n_q_heads + head] = make_float2(m, l);
   const float inv = 1.0f / l;
   const uint32_t pk = (uint32_t)f32_to_bf16(o0 * inv).v | ((uint32_t)f32_to_bf16(o1 * inv).v << 16);
   *reinterpret_cast<uint32_t*>(out + ((size_t)r * n_q_heads + head) * DH + 2 * lane) = pk;
@@ -431,10 +435,11 @@ static hipError_t launch_g(const bf16* q, const int* row_pos, const ReqTable* ta
   }
   if (scores)
     attn_mfma_kernel<G, true><<<grid, 64 * G, ATTN_LDS_BYTES, st>>>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool,
-                                                                    v_pool, g, out, sp, part_o, part_ml, scores, scores_len);
+                                                                    v_pool, g, out, sp, part_o, part_ml, scores, scores_len,
+                                                                    influence_pairs(scores, total_rows, g.n_kv_heads * G, scores_len));
   else
     attn_mfma_kernel<G, false><<<grid, 64 * G, ATTN_LDS_BYTES, st>>>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool,
-                                                                     v_pool, g, out, sp, part_o, part_ml, nullptr, 0);
+                                                                     v_pool, g, out, sp, part_o, part_ml, nullptr, 0, nullptr);
   return hipGetLastError();
 }
 
@@ -461,7 +466,7 @@ hipError_t launch_attention_bf16(const bf16* q, const int* row_pos, const int* r
   const float2* part_ml = reinterpret_cast<const float2*>(part + (size_t)sp.total_slots * n_q_heads * BQ * DH);
   const int items = total_rows * n_q_heads;
   attn_merge_kernel<<<(items + 3) / 4, 256, 0, st>>>(row_pos, row_req, table, total_rows, n_q_heads, sp, part, part_ml,
-                                                     out);
+                                                     out, scores ? influence_pairs(scores, total_rows, n_q_heads, scores_len) : nullptr);
   return hipGetLastError();
 }
 

@@ -232,14 +232,21 @@ hipError_t launch_threshold_select(const float* score, int n, float tau, int* id
 // per-request influence vectors (Eq. 6), passed to the accumulation kernel by value; nullptr: not tracked
 struct InfluencePtrs { float* s_inf[RC_MAX_REQ]; };
 size_t influence_scratch_floats(int n_rows, int n_q_heads, int max_len);
-// scratch holds the scores [rows][Hq][max_len]; they are either written by launch_influence_scores or by the
-// bf16 attention kernel's score output, then turned into weights and added by launch_influence_finish
+// scratch holds the scores [rows][Hq][max_len] (q.k / sqrt(dh)) followed by one (reference exponent in log2 units,
+// sum of exp2(score * log2(e) - reference)) pair per (row, head).  The scores are written by launch_influence_scores
+// or by the bf16 attention kernel, which also writes the pairs (have_pairs); launch_influence_finish computes the
+// pairs if they are missing, turns the scores into weights and adds them to the requests' vectors.
+inline float2* influence_pairs(float* scratch, int n_rows, int n_q_heads, int max_len) {
+  size_t off = (size_t)n_rows * n_q_heads * max_len;
+  off = (off + 1) & ~(size_t)1;   // 8-byte aligned
+  return reinterpret_cast<float2*>(scratch + off);
+}
 template <typename T>
 hipError_t launch_influence_scores(const T* q, const int* row_pos, const int* row_req, const ReqTable* table,
                                    int n_rows, const T* k_pool, KvGeom g, int n_q_heads, int max_len, float* scratch,
                                    hipStream_t st);
 hipError_t launch_influence_finish(const int* row_pos, const int* row_req, int n_rows, int n_q_heads, int max_len,
-                                   const InfluencePtrs& out, float* scratch, hipStream_t st);
+                                   const InfluencePtrs& out, float* scratch, bool have_pairs, hipStream_t st);
 hipError_t launch_final_select(const float* s_dev, const float* s_inf, int n, float tau_dev, float tau_inf, int k_suf,
                                int* idx_out, int* count_out, hipStream_t st);
 hipError_t launch_copy_i32(const int* src, int* dst, int n, hipStream_t st);

@@ -5,8 +5,10 @@
 //
 // Three small memory-bound kernels per layer (K is read once; no float atomics, fixed summation order):
 //   scores   s[row][h][j] = q[row][h] . k[j][h / G] / sqrt(dh)          for j <= pos(row)
-//   norm     m[row][h] = max_j s,  l[row][h] = sum_j exp(s - m)
-//   add      s_inf[req][j] += sum_h exp(s[row][h][j] - m[row][h]) / l[row][h]   (h ascending)
+//   norm     m[row][h] = log2(e) max_j s,  l[row][h] = sum_j exp2(log2(e) s - m)     (skipped when the attention
+//            kernel, which computes the same pair for its own softmax, has written it)
+//   add      s_inf[req][j] += sum_h exp2(log2(e) s[row][h][j] - m[row][h]) / l[row][h]   (h ascending)
+// m is only a reference exponent: any value gives the same weights as long as l was summed against it.
 #include "common.h"
 
 namespace rc {
@@ -86,8 +88,9 @@ influence_norm_kernel(const float* __restrict__ scores, const int* __restrict__ 
   const int h = blockIdx.x, row = blockIdx.y;
   const int n = row_pos[row] + 1;
   const float* s = scores + ((size_t)row * n_q_heads + h) * max_len;
+  constexpr float kLog2e = 1.4426950408889634f;
   float m = -INFINITY;
-  for (int j = threadIdx.x; j < n; j += kInfThreads) m = fmaxf(m, s[j]);
+  for (int j = threadIdx.x; j < n; j += kInfThreads) m = fmaxf(m, s[j] * kLog2e);
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
@@ -95,7 +98,7 @@ influence_norm_kernel(const float* __restrict__ scores, const int* __restrict__ 
   m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
   __syncthreads();
   float l = 0.f;
-  for (int j = threadIdx.x; j < n; j += kInfThreads) l += __expf(s[j] - m);
+  for (int j = threadIdx.x; j < n; j += kInfThreads) l += __builtin_amdgcn_exp2f(s[j] * kLog2e - m);
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o, 64);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = l;
@@ -115,7 +118,7 @@ influence_add_kernel(const float* __restrict__ scores, const float2* __restrict_
   float acc = 0.f;
   for (int h = 0; h < n_q_heads; ++h) {
     const float2 t = ml[(size_t)row * n_q_heads + h];
-    acc += __expf(scores[((size_t)row * n_q_heads + h) * max_len + j] - t.x) / t.y;
+    acc += __builtin_amdgcn_exp2f(scores[((size_t)row * n_q_heads + h) * max_len + j] * 1.4426950408889634f - t.x) / t.y;
   }
   dst[j] += acc;
 }
@@ -142,15 +145,13 @@ template hipError_t launch_influence_scores<bf16>(const bf16*, const int*, const
                                                   const bf16*, KvGeom, int, int, float*, hipStream_t);
 
 hipError_t launch_influence_finish(const int* row_pos, const int* row_req, int n_rows, int n_q_heads, int max_len,
-                                   const InfluencePtrs& out, float* scratch, hipStream_t st) {
+                                   const InfluencePtrs& out, float* scratch, bool have_pairs, hipStream_t st) {
   if (n_rows <= 0 || max_len <= 0) return hipSuccess;
-  // 8-byte aligned (m, l) pair array behind the scores
-  size_t off = (size_t)n_rows * n_q_heads * max_len;
-  off = (off + 1) & ~(size_t)1;
-  float2* ml = reinterpret_cast<float2*>(scratch + off);
+  float2* ml = influence_pairs(scratch, n_rows, n_q_heads, max_len);
   const unsigned chunks = (unsigned)((max_len + kInfThreads - 1) / kInfThreads);
-  influence_norm_kernel<<<dim3((unsigned)n_q_heads, (unsigned)n_rows), kInfThreads, 0, st>>>(scratch, row_pos, n_q_heads,
-                                                                                           max_len, ml);
+  if (!have_pairs)
+    influence_norm_kernel<<<dim3((unsigned)n_q_heads, (unsigned)n_rows), kInfThreads, 0, st>>>(scratch, row_pos, n_q_heads,
+                                                                                             max_len, ml);
   influence_add_kernel<<<dim3(chunks, (unsigned)n_rows), kInfThreads, 0, st>>>(scratch, ml, row_pos, row_req, out,
                                                                                n_q_heads, max_len);
   return hipGetLastError();
