@@ -14,10 +14,12 @@
 // so each operand is one 16-byte LDS read.
 //
 // LDS rows are padded by 16 bytes (K: 272, V^T: 144 bytes apart) so that operand fetches are free of
-// bank conflicts and all LDS addresses are constants off a per-thread base.  K/V rows come from the paged cache through the block table.
+// bank conflicts and all LDS addresses are constants off a per-thread base.  K/V rows come from the paged
+// cache through the block table, one tile ahead in registers and one tile ahead in a second pair of LDS
+// buffers, so a tile costs one barrier.
 // KV tiles entirely above the tile's last query position are skipped; the causal mask is applied
 // only in tiles that reach above the tile's first query position.  Workgroups are issued longest
-// first.
+// first over the whole launch (KV head fastest, query tiles by decreasing KV range).
 #include <type_traits>
 
 #include "common.h"

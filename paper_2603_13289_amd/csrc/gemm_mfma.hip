@@ -10,7 +10,8 @@
 // 4 bytes a 128-byte row covers half the banks, so 16 lanes reading the same chunk of 16 consecutive
 // rows (one MFMA operand fetch) touch 16 different (row parity, slot) pairs = all 64 banks once, and
 // the row-contiguous fill is conflict free as well.  No padding is needed.
-// The next K step is fetched into registers while the current one is multiplied.
+// The register-staged kernel fetches the next K step into registers while the current one is multiplied;
+// the direct-to-LDS kernel keeps two K steps in flight in two LDS buffers.
 // Each wavefront owns a (BM/WAVES_M) x (BN/WAVES_N) sub-tile, built from 32x32x16 MFMA blocks in the
 // register-staged kernel (any K) and from 16x16x32 blocks in the direct-to-LDS kernel (K a multiple of 64).
 //
