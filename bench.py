@@ -89,6 +89,38 @@ def device_model(rc, torch, w, seed):
     return model, g
 
 
+def machine_ceilings():
+    """What this board sustains: a 16-byte stream copy (HBM) and a register-only bf16 MFMA loop (matrix cores under
+    the chip's power limit), both kernels of the library, timed with events."""
+    import torch
+    from paper_2603_13289_amd import binding as rc
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(7)
+    dst = torch.empty_like(src)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    rc.rc_ceiling_stream_copy(src, dst, n)
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(5):
+        rc.rc_ceiling_stream_copy(src, dst, n)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * n / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del src, dst
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    out = torch.empty(rc.rc_ceiling_mfma_loop_out_bytes(n_cu) // 4, dtype=torch.float32, device="cuda")
+    rc.rc_ceiling_mfma_loop(out, n_cu, 2000)
+    torch.cuda.synchronize()
+    ev0.record()
+    flops = rc.rc_ceiling_mfma_loop(out, n_cu, 20000)        # about 10 ms
+    ev1.record()
+    torch.cuda.synchronize()
+    mfma_tf = flops / (ev0.elapsed_time(ev1) * 1e-3) / 1e12
+    return {"stream_copy_gb_s": copy_gbs, "mfma_loop_bf16_tflop_s": mfma_tf,
+            "note": "this board: 1 GiB copy with 16-byte accesses; 16x16x32 bf16 MFMAs on register operands, "
+                    "8 wavefronts per CU, pseudo-random operands"}
+
+
 def cpu_baseline(w, budget_s=20.0):
     """The CPU oracle timed on a bounded sample of the same workload: same widths and token counts,
     3 layers with triple (0, 1, 2) (one dense detect layer, two sparse layers), random segment record.
@@ -133,6 +165,7 @@ def main() -> int:
     ap.add_argument("--workload", default="mistral7b_4k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-prefill", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the stream-copy and MFMA-loop micro-benchmarks")
     ap.add_argument("--seed", type=int, default=20260313)
     ap.add_argument("--decode-steps", type=int, default=0,
                     help="after the prefill measurement, also time this many decoding steps (one token per request) on "
@@ -200,7 +233,7 @@ def main() -> int:
         rc.rc_reuse(model, reqs, plan, record, dst, logits, sel, None, ws)
 
     if args.counter_pass:
-        args.no_cpu_baseline = args.no_full_prefill = True
+        args.no_cpu_baseline = args.no_full_prefill = args.no_ceilings = True
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -391,6 +424,9 @@ def main() -> int:
     }
     if decode is not None:
         out["decode"] = decode
+    if not args.no_ceilings:
+        out["ceilings"] = machine_ceilings()
+        out["roofline"]["frac_of_sustained_mfma"] = achieved / out["ceilings"]["mfma_loop_bf16_tflop_s"]
     if not args.no_cpu_baseline and n_req == 1:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

@@ -278,6 +278,18 @@ RC_API rc_status rc_profile_read(float* ms, int32_t* launches);
 #define RC_TUNE_GEMM_XCD_REMAP 3
 RC_API rc_status rc_tune_set(int32_t key, int32_t value);
 
+/* ------------------------------------------------------------ machine ceilings
+ * Two micro-benchmarks for the benchmark report (boards differ, and the chip lowers its clock under matrix load);
+ * the caller times them with events on `stream`.
+ * rc_ceiling_stream_copy: dst[0, bytes) = src[0, bytes) with 16-byte accesses (bytes a multiple of 16; device
+ *   buffers, not overlapping): 2 * bytes of HBM traffic.
+ * rc_ceiling_mfma_loop: n_workgroups workgroups of 8 wavefronts issue `iters` rounds of 32 back-to-back 16x16x32
+ *   bf16 MFMAs on register operands; *flops receives the floating-point operations of the launch (host pointer).
+ *   out: device scratch of rc_ceiling_mfma_loop_out_bytes(n_workgroups) bytes (keeps the loop observable). */
+RC_API rc_status rc_ceiling_stream_copy(const void* src, void* dst, size_t bytes, void* stream);
+RC_API size_t rc_ceiling_mfma_loop_out_bytes(int32_t n_workgroups);
+RC_API rc_status rc_ceiling_mfma_loop(float* out, int32_t n_workgroups, int32_t iters, double* flops, void* stream);
+
 /* ------------------------------------------------------------ stage calls
  * One kernel (family) each, for unit tests and for profiling a stage in isolation. */
 

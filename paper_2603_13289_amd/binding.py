@@ -25,7 +25,8 @@ RC_SELECT_BUDGET, RC_SELECT_THRESHOLD = 0, 1
 EXPORTS = [
     "rc_status_str", "rc_build_info", "rc_model_create", "rc_model_destroy", "rc_reuse_workspace_bytes",
     "rc_reuse", "rc_prefill_workspace_bytes", "rc_prefill", "rc_decode_workspace_bytes", "rc_decode_step", "rc_layer_profile", "rc_stage_workspace_bytes", "rc_rope_rerotate",
-    "rc_vdev_score", "rc_topk", "rc_threshold_select", "rc_final_select", "rc_sparse_attention", "rc_gemm_rows", "rc_gemm_rows_fused",
+    "rc_vdev_score", "rc_topk", "rc_threshold_select", "rc_final_select", "rc_sparse_attention", "rc_gemm_rows", "rc_gemm_rows_fused", "rc_ceiling_stream_copy",
+    "rc_ceiling_mfma_loop_out_bytes", "rc_ceiling_mfma_loop",
     "rc_scatter_paged", "rc_profile_enable", "rc_profile_class_count", "rc_profile_class_name", "rc_profile_read",
     "rc_tune_set", "rc_sparse_attention_workspace_bytes",
     "rc_gemm_workspace_bytes",
@@ -136,6 +137,12 @@ def _load() -> C.CDLL:
     lib.rc_sparse_attention_workspace_bytes.argtypes = [i32, i32, C.POINTER(rc_kv_layer)]
     lib.rc_gemm_rows.restype = C.c_int
     lib.rc_gemm_rows.argtypes = [i32, vp, vp, vp, i32, i32, i32, vp, sz, vp]
+    lib.rc_ceiling_stream_copy.restype = C.c_int
+    lib.rc_ceiling_stream_copy.argtypes = [vp, vp, sz, vp]
+    lib.rc_ceiling_mfma_loop_out_bytes.restype = sz
+    lib.rc_ceiling_mfma_loop_out_bytes.argtypes = [i32]
+    lib.rc_ceiling_mfma_loop.restype = C.c_int
+    lib.rc_ceiling_mfma_loop.argtypes = [vp, i32, i32, C.POINTER(C.c_double), vp]
     lib.rc_gemm_rows_fused.restype = C.c_int
     lib.rc_gemm_rows_fused.argtypes = [i32, i32, vp, vp, vp, vp, i32, i32, i32, vp, sz, vp]
     lib.rc_gemm_workspace_bytes.restype = sz
@@ -490,6 +497,22 @@ def rc_gemm_rows(dtype: int, a: torch.Tensor, w: torch.Tensor, c: torch.Tensor, 
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.rc_gemm_rows(dtype, _ptr(a), _ptr(w), _ptr(c), m, n, k, _ptr(workspace), nbytes, _stream(stream)),
            "rc_gemm_rows")
+
+
+def rc_ceiling_stream_copy(src: torch.Tensor, dst: torch.Tensor, nbytes: int, stream=None) -> None:
+    _check(lib.rc_ceiling_stream_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "rc_ceiling_stream_copy")
+
+
+def rc_ceiling_mfma_loop_out_bytes(n_workgroups: int) -> int:
+    return int(lib.rc_ceiling_mfma_loop_out_bytes(n_workgroups))
+
+
+def rc_ceiling_mfma_loop(out: torch.Tensor, n_workgroups: int, iters: int, stream=None) -> float:
+    """Launches the register-only MFMA loop; returns the floating-point operations it performs."""
+    flops = C.c_double(0.0)
+    _check(lib.rc_ceiling_mfma_loop(_ptr(out), n_workgroups, iters, C.byref(flops), _stream(stream)),
+           "rc_ceiling_mfma_loop")
+    return float(flops.value)
 
 
 RC_GEMM_STORE, RC_GEMM_STORE_T, RC_GEMM_ADD, RC_GEMM_SWIGLU = 0, 1, 2, 3

@@ -1067,6 +1067,24 @@ rc_status rc_sparse_attention(const void* q, const int32_t* q_pos, int32_t n, in
   return RC_OK;
 }
 
+rc_status rc_ceiling_stream_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  if (!src || !dst || (bytes % 16) != 0) return RC_E_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) return RC_E_INVALID_ARG;
+  RC_HIP(launch_stream_copy(src, dst, bytes, reinterpret_cast<hipStream_t>(stream)));
+  return RC_OK;
+}
+
+size_t rc_ceiling_mfma_loop_out_bytes(int32_t n_workgroups) {
+  return n_workgroups > 0 ? mfma_loop_out_floats(n_workgroups) * sizeof(float) : 0;
+}
+
+rc_status rc_ceiling_mfma_loop(float* out, int32_t n_workgroups, int32_t iters, double* flops, void* stream) {
+  if (!out || n_workgroups < 1 || n_workgroups > 65536 || iters < 1 || iters > (1 << 24)) return RC_E_INVALID_ARG;
+  if (flops) *flops = mfma_loop_flops(n_workgroups, iters);
+  RC_HIP(launch_mfma_loop(out, n_workgroups, iters, reinterpret_cast<hipStream_t>(stream)));
+  return RC_OK;
+}
+
 size_t rc_gemm_workspace_bytes(void) { return align_up(gemm_partial_bytes()); }
 
 rc_status rc_gemm_rows(int32_t dtype, const void* a, const void* w, float* c, int32_t m, int32_t n, int32_t k,

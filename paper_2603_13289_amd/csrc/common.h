@@ -251,6 +251,12 @@ hipError_t launch_final_select(const float* s_dev, const float* s_inf, int n, fl
                                int* idx_out, int* count_out, hipStream_t st);
 hipError_t launch_copy_i32(const int* src, int* dst, int n, hipStream_t st);
 
+// machine ceilings (ceilings.hip)
+hipError_t launch_stream_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+size_t mfma_loop_out_floats(int n_workgroups);
+double mfma_loop_flops(int n_workgroups, int iters);
+hipError_t launch_mfma_loop(float* out, int n_workgroups, int iters, hipStream_t st);
+
 template <typename T>
 hipError_t launch_scatter_rows(const T* k_rows, const T* v_rows, const int* pos, int n, T* k_pool,
                                T* v_pool, KvGeom g, int seq, hipStream_t st);

@@ -119,6 +119,9 @@ def test_stage_argument_errors():
     assert status(lambda: rc.rc_gemm_rows_fused(rc.RC_F32, rc.RC_GEMM_SWIGLU, s, s, None, s, 1, 1, 8)) == rc.RC_E_INVALID_ARG
     assert status(lambda: rc.rc_gemm_rows_fused(rc.RC_F32, rc.RC_GEMM_ADD, s, s, s, s, 1, 1, 8)) == rc.RC_E_INVALID_ARG
     assert rc.rc_stage_workspace_bytes(10, 64) > 0
+    assert status(lambda: rc.rc_ceiling_stream_copy(s, s, 24)) == rc.RC_E_INVALID_ARG                      # not 16-byte units
+    assert status(lambda: rc.rc_ceiling_mfma_loop(s, 0, 10)) == rc.RC_E_INVALID_ARG
+    assert rc.rc_ceiling_mfma_loop_out_bytes(2) == 2 * 512 * 4
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -363,3 +363,20 @@ def test_scatter_paged(dtype, hkv, dh, block_size):
     assert np.array_equal(to_np(cache.read("k", 0, 0, T)), want_k)
     assert np.array_equal(to_np(cache.read("v", 0, 0, T)), want_v)
     assert np.array_equal(to_np(cache.read("k", 0, 1, 33)), ks[1])     # other sequences untouched
+
+
+# ------------------------------------------------------------------ machine ceilings (benchmark report helpers)
+def test_ceiling_kernels_run_and_copy_is_exact():
+    rc = _rc()
+    g = stream_rng("stage", "ceil")
+    n = (1 << 22) + 16 * 37
+    src = torch.from_numpy(g.integers(0, 256, size=n, dtype=np.uint8)).cuda()
+    dst = torch.zeros_like(src)
+    rc.rc_ceiling_stream_copy(src, dst, n)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    out = torch.zeros(rc.rc_ceiling_mfma_loop_out_bytes(4) // 4, dtype=torch.float32, device="cuda")
+    flops = rc.rc_ceiling_mfma_loop(out, 4, 10)
+    torch.cuda.synchronize()
+    assert flops == 4 * 8 * 10 * 32 * 2 * 16 * 16 * 32
+    assert torch.isfinite(out).all() and float(out.abs().max()) > 0.0
