@@ -427,14 +427,10 @@ static hipError_t launch_g(const bf16* q, const int* row_pos, const ReqTable* ta
   float* part_o = part;
   float2* part_ml = reinterpret_cast<float2*>(part + (size_t)sp.total_slots * g.n_kv_heads * G * BQ * DH);
   // more than the 64 KB a kernel gets without asking
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<G, true>, hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_LDS_BYTES);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void*)attn_mfma_kernel<G, false>, hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<unsigned long long> told_scores{0}, told_plain{0};
+  hipError_t e = scores ? allow_dynamic_lds((const void*)attn_mfma_kernel<G, true>, ATTN_LDS_BYTES, told_scores)
+                        : allow_dynamic_lds((const void*)attn_mfma_kernel<G, false>, ATTN_LDS_BYTES, told_plain);
+  if (e != hipSuccess) return e;
   if (scores)
     attn_mfma_kernel<G, true><<<grid, 64 * G, ATTN_LDS_BYTES, st>>>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool,
                                                                     v_pool, g, out, sp, part_o, part_ml, scores, scores_len,

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/relaycache.h"
 
 namespace rc {
@@ -250,6 +252,19 @@ hipError_t launch_influence_finish(const int* row_pos, const int* row_req, int n
 hipError_t launch_final_select(const float* s_dev, const float* s_inf, int n, float tau_dev, float tau_inf, int k_suf,
                                int* idx_out, int* count_out, hipStream_t st);
 hipError_t launch_copy_i32(const int* src, int* dst, int n, hipStream_t st);
+
+// Kernels that use more dynamic LDS than a kernel gets without asking must say so once per device.  `done` is a
+// per-kernel bit mask of the devices that have been told (one static per call site).
+inline hipError_t allow_dynamic_lds(const void* kernel, int bytes, std::atomic<unsigned long long>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const unsigned long long bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
 
 // machine ceilings (ceilings.hip)
 hipError_t launch_stream_copy(const void* src, void* dst, size_t bytes, hipStream_t st);

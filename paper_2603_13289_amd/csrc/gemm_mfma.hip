@@ -516,15 +516,18 @@ static SplitPlan plan_tail_split(int total, int slots, int ksteps, float step = 
   return best;
 }
 
-static int g_num_cus = 0;
+// compute units of the current device (asked once per device)
 static int num_cus() {
-  if (g_num_cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-      n = 256;
-    g_num_cus = n;
+  static std::atomic<int> cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  std::atomic<int>& slot = cached[dev & 63];
+  int n = slot.load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    slot.store(n, std::memory_order_relaxed);
   }
-  return g_num_cus;
+  return n;
 }
 
 size_t gemm_partial_bytes() { return (size_t)256 * 256 * 256 * sizeof(float) + 4096; }   // 256 tile parts
@@ -559,8 +562,8 @@ static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const 
   hipError_t e = hipSuccess;
   if (dual) {
     auto kern = gemm_mfma_dl_kernel<BM, BN, WAVES_M, WAVES_N, true, OCC>;
-    static bool attr_set = false;
-    if (!attr_set) { e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes); attr_set = true; }
+    static std::atomic<unsigned long long> told{0};
+    e = allow_dynamic_lds((const void*)kern, (int)lds_bytes, told);
     if (e != hipSuccess) return e;
     kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, make_tile_order(tiles_m, tiles_n), full_tiles, per_xcd,
                                       n_full_wgs, split, kpp, partial);
@@ -569,8 +572,8 @@ static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const 
           c, m, n, ldc, (int)epi, make_tile_order(tiles_m, tiles_n), full_tiles, split, partial);
   } else {
     auto kern = gemm_mfma_dl_kernel<BM, BN, WAVES_M, WAVES_N, false, OCC>;
-    static bool attr_set = false;
-    if (!attr_set) { e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes); attr_set = true; }
+    static std::atomic<unsigned long long> told{0};
+    e = allow_dynamic_lds((const void*)kern, (int)lds_bytes, told);
     if (e != hipSuccess) return e;
     kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, make_tile_order(tiles_m, tiles_n), full_tiles, per_xcd,
                                       n_full_wgs, split, kpp, partial);
