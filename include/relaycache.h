@@ -276,6 +276,9 @@ RC_API rc_status rc_profile_read(float* ms, int32_t* launches);
 #define RC_TUNE_ATTN_CHUNK_TILES 2
 /* RC_TUNE_GEMM_XCD_REMAP: 1 (default) = GEMM workgroup ids are regrouped per XCD, 0 = launch order. */
 #define RC_TUNE_GEMM_XCD_REMAP 3
+/* RC_TUNE_GEMM_THIN_TILES: 1 (default) = a last row of 256-row GEMM tiles with at most 64 live rows is multiplied
+ * by a tile body laid out for 64 rows, 0 = by the full tile body. */
+#define RC_TUNE_GEMM_THIN_TILES 4
 RC_API rc_status rc_tune_set(int32_t key, int32_t value);
 
 /* ------------------------------------------------------------ machine ceilings

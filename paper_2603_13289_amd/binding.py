@@ -549,6 +549,7 @@ def rc_profile_read() -> dict:
 RC_TUNE_GEMM_TILE = 1
 RC_TUNE_ATTN_CHUNK_TILES = 2
 RC_TUNE_GEMM_XCD_REMAP = 3
+RC_TUNE_GEMM_THIN_TILES = 4
 
 
 def rc_tune_set(key: int, value: int) -> None:

@@ -694,6 +694,10 @@ rc_status rc_tune_set(int32_t key, int32_t value) {
     set_gemm_xcd_remap(value);
     return RC_OK;
   }
+  if (key == RC_TUNE_GEMM_THIN_TILES && (value == 0 || value == 1)) {
+    set_gemm_thin_tiles(value);
+    return RC_OK;
+  }
   if (key == RC_TUNE_ATTN_CHUNK_TILES && value >= 0) {
     set_attention_chunk_tiles(value);
     return RC_OK;

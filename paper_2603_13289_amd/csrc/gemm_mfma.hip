@@ -286,42 +286,21 @@ __device__ inline void store_tile16(const f32x4 (&acc)[FM][FN], void* __restrict
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool DUAL, int OCC>
-__global__ void __launch_bounds__(WAVES_M * WAVES_N * 64, OCC)
-gemm_mfma_dl_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const bf16* __restrict__ w2,
-                      const bf16* __restrict__ w3, int ns1, int ns2, void* __restrict__ c, int m, int n, int k, int ldc,
-                      int epi, TileOrder order, int full_tiles, int per_xcd, int n_full_wgs, int split, int ksteps_per_part,
-                      float* __restrict__ partial) {
+// One output tile (or one K part of it): the work of a workgroup once it knows its tile.
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool DUAL>
+__device__ __forceinline__ void gemm_tile_body(const bf16* __restrict__ a, const bf16* __restrict__ w,
+                                               const bf16* __restrict__ w2, const bf16* __restrict__ w3, int ns1, int ns2,
+                                               void* __restrict__ c, int m, int n, int k, int ldc, int epi, int m0, int n0,
+                                               int k_begin, int k_end, int part_slot, float* __restrict__ partial) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   constexpr int FM = WTM / 16, FN = WTN / 16, FH = FN / 2;
-  constexpr int BN_OUT = DUAL ? BN / 2 : BN;
   constexpr int A_BLK = BM / 8, B_BLK = BN / 8;
   constexpr int A_PER = A_BLK / NW, B_PER = B_BLK / NW;
   static_assert(A_PER * NW == A_BLK && B_PER * NW == B_BLK, "tile/waves mismatch");
   static_assert(FN % 2 == 0 && BK == 64, "two sub-steps of 32, two halves of the column blocks");
   constexpr int TILE_BYTES = (BM + BN) * 128;
-
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];   // 2 x [A tile | B tile]
-
-  // Workgroups [0, n_full_wgs) each own one of the first full_tiles output tiles (whole K range).
-  // The remaining tiles, too few to fill the chip, are each cut along K into `split` parts: workgroup
-  // n_full_wgs + j takes part j % split of tile full_tiles + j / split and leaves its raw accumulators
-  // in `partial`; gemm_fixup_kernel adds the parts in a fixed order and applies the epilogue.
-  int logical, k_begin = 0, k_end = k, part_slot = -1;
-  if ((int)blockIdx.x < n_full_wgs) {
-    logical = per_xcd > 0 ? (int)(blockIdx.x % XCDS) * per_xcd + (int)(blockIdx.x / XCDS) : (int)blockIdx.x;
-    if (logical >= full_tiles) return;
-  } else {
-    const int j = (int)blockIdx.x - n_full_wgs;
-    logical = full_tiles + j / split;
-    part_slot = j;
-    k_begin = (j % split) * ksteps_per_part * BK;
-    k_end = min(k, k_begin + ksteps_per_part * BK);
-  }
-  int tile_m, tile_n;
-  tile_of(order, logical, &tile_m, &tile_n);
-  const int m0 = tile_m * BM, n0 = tile_n * BN_OUT;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -455,13 +434,69 @@ gemm_mfma_dl_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, cons
   store_tile16<FM, FN, WTM, WTN, DUAL>(acc, c, m, n, ldc, epi, m0, n0, wm, wn, lane);
 }
 
+// Workgroups [0, n_full_wgs) each own one of the first full_tiles output tiles (whole K range).
+// The remaining tiles, too few to fill the chip, are each cut along K into `split` parts: workgroup
+// n_full_wgs + j takes part j % split of tile full_tiles + j / split and leaves its raw accumulators
+// in `partial`; gemm_fixup_kernel adds the parts in a fixed order and applies the epilogue.
+//
+// THIN: when the last tile row has at most 64 live rows (a prompt whose live rows are a multiple of the tile height
+// plus a few: the last reused token, a short suffix), its n_thin tiles are multiplied by a 64-row body whose eight
+// wavefronts sit side by side, which costs about a third of a full tile; `order` then describes the tile rows
+// above it only.  The thin tiles are always whole-K tiles and are dealt out evenly over the XCDs' queues, at
+// the tail of each, where they fill the last round.  (A 128-row body for up to 128 live rows was measured
+// as well: no gain.)
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool DUAL, int OCC, bool THIN>
+__global__ void __launch_bounds__(WAVES_M * WAVES_N * 64, OCC)
+gemm_mfma_dl_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const bf16* __restrict__ w2,
+                    const bf16* __restrict__ w3, int ns1, int ns2, void* __restrict__ c, int m, int n, int k, int ldc,
+                    int epi, TileOrder order, int full_tiles, int per_xcd, int n_full_wgs, int split, int ksteps_per_part,
+                    float* __restrict__ partial, int n_thin) {
+  constexpr int BN_OUT = DUAL ? BN / 2 : BN;
+  const int n_normal_full = full_tiles - n_thin;
+  int u = 0, thin_tile = -1, k_begin = 0, k_end = k, part_slot = -1;   // u: index among the normal tiles
+  if ((int)blockIdx.x < n_full_wgs) {
+    if (per_xcd > 0) {
+      const int x = (int)(blockIdx.x % XCDS), j = (int)(blockIdx.x / XCDS);
+      const int cnt = THIN ? n_thin / XCDS + (x < n_thin % XCDS ? 1 : 0) : 0;          // thin tiles of this XCD
+      const int before = THIN ? x * (n_thin / XCDS) + min(x, n_thin % XCDS) : 0;      // ... of the XCDs before it
+      if (j >= per_xcd - cnt) thin_tile = (j - (per_xcd - cnt)) * XCDS + x;
+      else u = x * per_xcd - before + j;
+    } else {
+      if (THIN && (int)blockIdx.x >= n_normal_full) {
+        thin_tile = (int)blockIdx.x - n_normal_full;
+        if (thin_tile >= n_thin) return;
+      } else {
+        u = (int)blockIdx.x;
+      }
+    }
+    if (thin_tile < 0 && u >= n_normal_full) return;
+  } else {
+    const int j = (int)blockIdx.x - n_full_wgs;
+    u = n_normal_full + j / split;
+    part_slot = j;
+    k_begin = (j % split) * ksteps_per_part * BK;
+    k_end = min(k, k_begin + ksteps_per_part * BK);
+  }
+  if constexpr (THIN) {
+    if (thin_tile >= 0) {
+      const int m0 = order.tiles_m * BM, n0 = thin_tile * BN_OUT;
+      gemm_tile_body<64, BN, 1, 8, DUAL>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, m0, n0, 0, k, -1, partial);
+      return;
+    }
+  }
+  int tile_m, tile_n;
+  tile_of(order, u, &tile_m, &tile_n);
+  gemm_tile_body<BM, BN, WAVES_M, WAVES_N, DUAL>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, tile_m * BM, tile_n * BN_OUT,
+                                                 k_begin, k_end, part_slot, partial);
+}
+
 // Sum of the K-split parts of the tail tiles (fixed order: part 0, 1, ...) followed by the epilogue.  One
 // workgroup per (tile, accumulator (i, j)); thread t owns the same (wavefront, lane) as thread t of the GEMM
 // kernel, so all reads of a part are coalesced.
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool DUAL>
 __global__ void __launch_bounds__(WAVES_M * WAVES_N * 64)
-gemm_fixup_kernel(void* __restrict__ c, int m, int n, int ldc, int epi, TileOrder order, int full_tiles, int split,
-                    const float* __restrict__ partial) {
+gemm_fixup_kernel(void* __restrict__ c, int m, int n, int ldc, int epi, TileOrder order, int full_tiles /* of `order` */,
+                  int split, const float* __restrict__ partial) {
   constexpr int NW = WAVES_M * WAVES_N, NT = NW * 64;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   constexpr int FM = WTM / 16, FN = WTN / 16;
@@ -532,27 +567,78 @@ static int num_cus() {
 
 size_t gemm_partial_bytes() { return (size_t)256 * 256 * 256 * sizeof(float) + 4096; }   // 256 tile parts
 
+// Schedule of a launch of 256-row tiles: which tiles run whole, which are cut along K, and whether the ragged
+// last tile row goes to the thin body.  A thin tile is priced at kThinCost of a full one.
+static constexpr float kThinCost = 0.4f;
+static constexpr int kThinRows = 64;
+static int g_thin_tiles = 1;
+void set_gemm_thin_tiles(int on) { g_thin_tiles = on; }
+
+struct LaunchPlan {
+  int n_thin;                 // tiles of the ragged last tile row handled by the thin body (0: none)
+  int n_normal;               // tiles of the other rows
+  int rem, split, kpp;        // the last `rem` normal tiles are cut into `split` parts of `kpp` K steps
+  float cost;
+};
+
+// thin: price and schedule the launch with the ragged last tile row on the thin body; cost < 0 if that is not possible
+static LaunchPlan plan_one(int m, int tiles_n, int bm, int ksteps, int slots, float step, bool may_split, bool thin) {
+  const int tiles_m = (m + bm - 1) / bm;
+  LaunchPlan p = {};
+  p.cost = -1.f;
+  if (thin) {
+    const int ragged = m - (tiles_m - 1) * bm;   // live rows of the last tile row
+    if (tiles_m < 2 || ragged > kThinRows) return p;
+    p.n_thin = tiles_n;
+  }
+  p.n_normal = tiles_m * tiles_n - p.n_thin;
+  const int equiv = p.n_normal + (int)(p.n_thin * kThinCost + 0.999f);
+  p.split = 1;
+  p.kpp = ksteps;
+  float cost;
+  if (may_split) {
+    const SplitPlan sp = plan_tail_split(equiv, slots, ksteps, step);
+    cost = sp.cost;
+    if (sp.split > 1) {
+      p.rem = sp.rem;
+      p.kpp = (ksteps + sp.split - 1) / sp.split;
+      p.split = (ksteps + p.kpp - 1) / p.kpp;
+    }
+  } else {
+    cost = ((equiv + slots - 1) / slots) * ksteps * step;
+  }
+  // thin tiles only among the whole tiles of a launch that has at least one full round
+  if (thin && (equiv < slots || p.rem > p.n_normal)) return p;
+  p.cost = cost;
+  return p;
+}
+
+static LaunchPlan plan_launch(int m, int tiles_n, int bm, int ksteps, int slots, float step, bool may_split, bool may_thin) {
+  const LaunchPlan plain = plan_one(m, tiles_n, bm, ksteps, slots, step, may_split, false);
+  if (may_thin && g_thin_tiles) {
+    const LaunchPlan thin = plan_one(m, tiles_n, bm, ksteps, slots, step, may_split, true);
+    if (thin.cost >= 0.f && thin.cost < plain.cost) return thin;
+  }
+  return plain;
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int OCC>
 static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const bf16* w3, int ns1, int ns2, void* c,
                             int m, int n, int k, int ldc, GemmEpilogue epi, float* partial, hipStream_t st) {
   const bool dual = epi == EPI_SWIGLU_T;
   const int bn_out = dual ? BN / 2 : BN;
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + bn_out - 1) / bn_out;
-  const int total = tiles_m * tiles_n;
   // Full rounds of one tile per workgroup slot; the remainder (less than one round) is cut along K so
-  // that it also fills the chip.  Only with a partial buffer, and only for the one-workgroup-per-CU tile.
+  // that it also fills the chip.  Only with a partial buffer, and only for the one-workgroup-per-CU tiles.
+  constexpr bool THIN = BM == 256 && BN == 256 && OCC == 1;
   const int slots = num_cus() * OCC;
   const int ksteps = k / BK;
-  int full_tiles = total, split = 1, kpp = ksteps;
-  if (partial && OCC == 1) {
-    const SplitPlan sp = plan_tail_split(total, slots, ksteps, BN == 192 ? kStep192 : kStep256);
-    if (sp.split > 1) {
-      full_tiles = total - sp.rem;
-      kpp = (ksteps + sp.split - 1) / sp.split;
-      split = (ksteps + kpp - 1) / kpp;
-    }
-  }
-  const int rem_tiles = total - full_tiles;
+  const LaunchPlan lp = plan_launch(m, tiles_n, BM, ksteps, slots, BN == 192 ? kStep192 : kStep256,
+                                    partial != nullptr && OCC == 1, THIN);
+  const int full_tiles = lp.n_thin + lp.n_normal - lp.rem;     // whole-K tiles
+  const int normal_full = lp.n_normal - lp.rem;
+  const int rem_tiles = lp.rem, split = lp.split, kpp = lp.kpp;
+  const TileOrder order = make_tile_order(lp.n_thin > 0 ? tiles_m - 1 : tiles_m, tiles_n);
   int per_xcd = (full_tiles + XCDS - 1) / XCDS;
   const int n_full_wgs = per_xcd * XCDS;
   const dim3 grid((unsigned)(n_full_wgs + rem_tiles * split));
@@ -561,25 +647,25 @@ static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const 
   constexpr size_t lds_bytes = 2 * (size_t)(BM + BN) * 128;
   hipError_t e = hipSuccess;
   if (dual) {
-    auto kern = gemm_mfma_dl_kernel<BM, BN, WAVES_M, WAVES_N, true, OCC>;
+    auto kern = gemm_mfma_dl_kernel<BM, BN, WAVES_M, WAVES_N, true, OCC, THIN>;
     static std::atomic<unsigned long long> told{0};
     e = allow_dynamic_lds((const void*)kern, (int)lds_bytes, told);
     if (e != hipSuccess) return e;
-    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, make_tile_order(tiles_m, tiles_n), full_tiles, per_xcd,
-                                      n_full_wgs, split, kpp, partial);
+    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, order, full_tiles, per_xcd,
+                                      n_full_wgs, split, kpp, partial, lp.n_thin);
     if (rem_tiles > 0)
       gemm_fixup_kernel<BM, BN, WAVES_M, WAVES_N, true><<<rem_tiles * (BM / WAVES_M / 16) * (BN / WAVES_N / 32), NT, 0, st>>>(
-          c, m, n, ldc, (int)epi, make_tile_order(tiles_m, tiles_n), full_tiles, split, partial);
+          c, m, n, ldc, (int)epi, order, normal_full, split, partial);
   } else {
-    auto kern = gemm_mfma_dl_kernel<BM, BN, WAVES_M, WAVES_N, false, OCC>;
+    auto kern = gemm_mfma_dl_kernel<BM, BN, WAVES_M, WAVES_N, false, OCC, THIN>;
     static std::atomic<unsigned long long> told{0};
     e = allow_dynamic_lds((const void*)kern, (int)lds_bytes, told);
     if (e != hipSuccess) return e;
-    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, make_tile_order(tiles_m, tiles_n), full_tiles, per_xcd,
-                                      n_full_wgs, split, kpp, partial);
+    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, order, full_tiles, per_xcd,
+                                      n_full_wgs, split, kpp, partial, lp.n_thin);
     if (rem_tiles > 0)
       gemm_fixup_kernel<BM, BN, WAVES_M, WAVES_N, false><<<rem_tiles * (BM / WAVES_M / 16) * (BN / WAVES_N / 16), NT, 0, st>>>(
-          c, m, n, ldc, (int)epi, make_tile_order(tiles_m, tiles_n), full_tiles, split, partial);
+          c, m, n, ldc, (int)epi, order, normal_full, split, partial);
   }
   return hipGetLastError();
 }
@@ -620,11 +706,10 @@ static hipError_t dispatch(const bf16* a, const bf16* w, const bf16* w2, const b
       // 256x256 tiles (one workgroup per CU, K-split tail) against 128x128 tiles (two per CU), by the time model
       const bool dual = epi == EPI_SWIGLU_T;
       const int ksteps = k / BK;
-      const int t5 = ((m + 255) / 256) * ((n + (dual ? 127 : 255)) / (dual ? 128 : 256));
       const long t6 = (long)((m + 127) / 128) * ((n + (dual ? 63 : 127)) / (dual ? 64 : 128));
       const int slots6 = 2 * num_cus();
-      const float cost5 = partial ? plan_tail_split(t5, num_cus(), ksteps).cost
-                                  : ((t5 + num_cus() - 1) / num_cus()) * ksteps * kStep256;
+      const float cost5 = plan_launch(m, (n + (dual ? 127 : 255)) / (dual ? 128 : 256), 256, ksteps, num_cus(), kStep256,
+                                      partial != nullptr, true).cost;
       const long last6 = t6 % slots6;
       const float cost6 = (t6 / slots6) * ksteps * kStep128 +
                           (last6 == 0 ? 0.f : (last6 * 2 <= slots6 ? 0.65f : 1.f) * ksteps * kStep128);
@@ -632,9 +717,7 @@ static hipError_t dispatch(const bf16* a, const bf16* w, const bf16* w2, const b
       // 256x192 tiles where they cover N exactly (the fused q|k|v projection: 6144 = 32 x 192): a launch of a
       // few hundred rows then has a third more tiles to spread over the CUs
       if (!dual && n % 192 == 0) {
-        const int t7 = ((m + 255) / 256) * (n / 192);
-        const float cost7 = partial ? plan_tail_split(t7, num_cus(), ksteps, kStep192).cost
-                                    : ((t7 + num_cus() - 1) / num_cus()) * ksteps * kStep192;
+        const float cost7 = plan_launch(m, n / 192, 256, ksteps, num_cus(), kStep192, partial != nullptr, false).cost;
         if (cost7 < std::min(cost5, cost6)) tile = 7;
       }
     }

@@ -314,6 +314,54 @@ def test_gemm_forced_tile_shapes(tile, epilogue, m, n, k):
     assert rel_err(to_np(c), want) <= tol
 
 
+@pytest.mark.parametrize("epilogue", ["store", "add", "swiglu"])
+@pytest.mark.parametrize("m", [1025, 1057, 1088, 1089, 1153, 1639])
+def test_gemm_ragged_last_tile_row(epilogue, m):
+    """Launches with at least one full round of 256x256 tiles whose last tile row has 1 ... 129 live rows: up to
+    64 of them are multiplied by the thin tile body, more by the full body."""
+    rc = _rc()
+    k = 256
+    n = 8192 if epilogue == "swiglu" else 16384
+    a = _rand((m, k), "bf16", f"ra{m}")
+    w = _rand((n, k), "bf16", f"rw{n}", 0.05)
+    ws = rc.alloc_workspace(rc.rc_gemm_workspace_bytes())
+    prod = R.linear(a.astype(np.float64), w.astype(np.float64))
+    if epilogue == "store":
+        c = torch.full((m, n), 7.0, dtype=torch.float32, device="cuda")
+        rc.rc_gemm_rows(rc.RC_BF16, _up(a, "bf16"), _up(w, "bf16"), c, m, n, k, ws)
+        want, tol = prod, 2e-6 * np.sqrt(k)
+    elif epilogue == "add":
+        c0 = _rand((m, n), "f32", f"rc{m}")
+        c = torch.from_numpy(c0).cuda()
+        rc.rc_gemm_rows_fused(rc.RC_BF16, rc.RC_GEMM_ADD, _up(a, "bf16"), _up(w, "bf16"), None, c, m, n, k, ws)
+        want, tol = c0.astype(np.float64) + prod, 2e-6 * np.sqrt(k)
+    else:
+        w2 = _rand((n, k), "bf16", f"ru{n}", 0.05)
+        c = torch.zeros((m, n), dtype=torch.bfloat16, device="cuda")
+        rc.rc_gemm_rows_fused(rc.RC_BF16, rc.RC_GEMM_SWIGLU, _up(a, "bf16"), _up(w, "bf16"), _up(w2, "bf16"), c, m, n, k,
+                              ws)
+        want, tol = R.silu(prod) * R.linear(a.astype(np.float64), w2.astype(np.float64)), 4e-3
+    torch.cuda.synchronize()
+    assert rel_err(to_np(c), want) <= tol
+    # the same launch with the thin bodies switched off (only the K-split tail may fall on other tiles)
+    rc.rc_tune_set(rc.RC_TUNE_GEMM_THIN_TILES, 0)
+    try:
+        if epilogue == "store":
+            c2 = torch.zeros_like(c)
+            rc.rc_gemm_rows(rc.RC_BF16, _up(a, "bf16"), _up(w, "bf16"), c2, m, n, k, ws)
+        elif epilogue == "add":
+            c2 = torch.from_numpy(c0).cuda()
+            rc.rc_gemm_rows_fused(rc.RC_BF16, rc.RC_GEMM_ADD, _up(a, "bf16"), _up(w, "bf16"), None, c2, m, n, k, ws)
+        else:
+            c2 = torch.zeros_like(c)
+            rc.rc_gemm_rows_fused(rc.RC_BF16, rc.RC_GEMM_SWIGLU, _up(a, "bf16"), _up(w, "bf16"), _up(w2, "bf16"), c2, m, n,
+                                  k, ws)
+        torch.cuda.synchronize()
+    finally:
+        rc.rc_tune_set(rc.RC_TUNE_GEMM_THIN_TILES, 1)
+    assert rel_err(to_np(c), to_np(c2)) <= (1e-6 if epilogue != "swiglu" else 8e-3)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("epilogue", ["store_t", "add", "swiglu"])
 @pytest.mark.parametrize("m,n,k", [(51, 192, 256), (129, 1000, 688), (300, 258, 1408), (1639, 512, 1024),
