@@ -281,6 +281,15 @@ RC_API rc_status rc_profile_read(float* ms, int32_t* launches);
 #define RC_TUNE_GEMM_THIN_TILES 4
 RC_API rc_status rc_tune_set(int32_t key, int32_t value);
 
+/* Host-only self-check of the bf16 GEMM's launch schedule (no GPU needed): builds the grid the library would launch
+ * for C[m][n] = A[m][k] W^T with direct-to-LDS tile `tile` (5, 6 or 7, see RC_TUNE_GEMM_TILE) on a device of n_cus
+ * compute units, walks every workgroup id and counts violations of "every output tile is covered exactly once, by
+ * one workgroup over the whole K range or by K parts that partition it in order".  swiglu != 0: the gate/up
+ * epilogue (half as many output columns per tile); with_workspace != 0: the K-split tail is allowed.
+ * *n_blocks (optional) receives the grid size.  Returns the number of violations, or -1 for bad arguments. */
+RC_API int32_t rc_gemm_plan_check(int32_t m, int32_t n, int32_t k, int32_t swiglu, int32_t tile, int32_t n_cus,
+                                  int32_t with_workspace, int32_t* n_blocks);
+
 /* ------------------------------------------------------------ machine ceilings
  * Two micro-benchmarks for the benchmark report (boards differ, and the chip lowers its clock under matrix load);
  * the caller times them with events on `stream`.

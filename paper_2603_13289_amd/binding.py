@@ -26,7 +26,7 @@ EXPORTS = [
     "rc_status_str", "rc_build_info", "rc_model_create", "rc_model_destroy", "rc_reuse_workspace_bytes",
     "rc_reuse", "rc_prefill_workspace_bytes", "rc_prefill", "rc_decode_workspace_bytes", "rc_decode_step", "rc_layer_profile", "rc_stage_workspace_bytes", "rc_rope_rerotate",
     "rc_vdev_score", "rc_topk", "rc_threshold_select", "rc_final_select", "rc_sparse_attention", "rc_gemm_rows", "rc_gemm_rows_fused", "rc_ceiling_stream_copy",
-    "rc_ceiling_mfma_loop_out_bytes", "rc_ceiling_mfma_loop",
+    "rc_ceiling_mfma_loop_out_bytes", "rc_ceiling_mfma_loop", "rc_gemm_plan_check",
     "rc_scatter_paged", "rc_profile_enable", "rc_profile_class_count", "rc_profile_class_name", "rc_profile_read",
     "rc_tune_set", "rc_sparse_attention_workspace_bytes",
     "rc_gemm_workspace_bytes",
@@ -137,6 +137,8 @@ def _load() -> C.CDLL:
     lib.rc_sparse_attention_workspace_bytes.argtypes = [i32, i32, C.POINTER(rc_kv_layer)]
     lib.rc_gemm_rows.restype = C.c_int
     lib.rc_gemm_rows.argtypes = [i32, vp, vp, vp, i32, i32, i32, vp, sz, vp]
+    lib.rc_gemm_plan_check.restype = i32
+    lib.rc_gemm_plan_check.argtypes = [i32, i32, i32, i32, i32, i32, i32, C.POINTER(i32)]
     lib.rc_ceiling_stream_copy.restype = C.c_int
     lib.rc_ceiling_stream_copy.argtypes = [vp, vp, sz, vp]
     lib.rc_ceiling_mfma_loop_out_bytes.restype = sz
@@ -497,6 +499,13 @@ def rc_gemm_rows(dtype: int, a: torch.Tensor, w: torch.Tensor, c: torch.Tensor, 
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.rc_gemm_rows(dtype, _ptr(a), _ptr(w), _ptr(c), m, n, k, _ptr(workspace), nbytes, _stream(stream)),
            "rc_gemm_rows")
+
+
+def rc_gemm_plan_check(m: int, n: int, k: int, swiglu: bool, tile: int, n_cus: int = 256, with_workspace: bool = True):
+    """(violations, grid size) of the launch schedule of one bf16 GEMM; host only."""
+    nb = C.c_int32(0)
+    err = int(lib.rc_gemm_plan_check(m, n, k, 1 if swiglu else 0, tile, n_cus, 1 if with_workspace else 0, C.byref(nb)))
+    return err, int(nb.value)
 
 
 def rc_ceiling_stream_copy(src: torch.Tensor, dst: torch.Tensor, nbytes: int, stream=None) -> None:

@@ -1071,6 +1071,12 @@ rc_status rc_sparse_attention(const void* q, const int32_t* q_pos, int32_t n, in
   return RC_OK;
 }
 
+int32_t rc_gemm_plan_check(int32_t m, int32_t n, int32_t k, int32_t swiglu, int32_t tile, int32_t n_cus,
+                           int32_t with_workspace, int32_t* n_blocks) {
+  if (m < 1 || n < 1 || k < 64 || (k % 64) != 0 || n_cus < 1 || (tile != 5 && tile != 6 && tile != 7)) return -1;
+  return check_grid_plan(m, n, k, swiglu != 0, tile, n_cus, with_workspace != 0, n_blocks);
+}
+
 rc_status rc_ceiling_stream_copy(const void* src, void* dst, size_t bytes, void* stream) {
   if (!src || !dst || (bytes % 16) != 0) return RC_E_INVALID_ARG;
   if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) return RC_E_INVALID_ARG;

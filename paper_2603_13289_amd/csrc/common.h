@@ -189,6 +189,7 @@ hipError_t launch_gemm_bf16(const bf16* a, const bf16* w, const bf16* w2, void* 
 hipError_t launch_gemm_qkv_bf16(const bf16* a, const bf16* wq, int nq, const bf16* wk, const bf16* wv, int nkv, float* c,
                                 int m, int k, float* partial, hipStream_t st);
 void set_gemm_xcd_remap(int on);
+int check_grid_plan(int m, int n, int k, bool dual, int tile, int n_cus, bool with_partial, int* n_blocks_out);
 void set_gemm_thin_tiles(int on);   // 1: a ragged last tile row of at most 64 rows goes to the thin tile body
 void set_gemm_tile(int t);  // 0: by shape; 1-3 register-staged tiles; 5-7 direct-to-LDS tiles (bf16 MFMA GEMM)
 

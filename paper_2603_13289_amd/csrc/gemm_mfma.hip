@@ -22,6 +22,7 @@
 // all row tiles of the same few weight-column tiles: a weight tile is then fetched from HBM once
 // per XCD-L2 instead of once per row tile.
 #include <algorithm>
+#include <vector>
 
 #include "common.h"
 
@@ -434,60 +435,80 @@ __device__ __forceinline__ void gemm_tile_body(const bf16* __restrict__ a, const
   store_tile16<FM, FN, WTM, WTN, DUAL>(acc, c, m, n, ldc, epi, m0, n0, wm, wn, lane);
 }
 
-// Workgroups [0, n_full_wgs) each own one of the first full_tiles output tiles (whole K range).
-// The remaining tiles, too few to fill the chip, are each cut along K into `split` parts: workgroup
-// n_full_wgs + j takes part j % split of tile full_tiles + j / split and leaves its raw accumulators
-// in `partial`; gemm_fixup_kernel adds the parts in a fixed order and applies the epilogue.
+// What the launch's grid does.  Workgroups [0, n_full_wgs) each own one of the first full_tiles output tiles
+// (whole K range).  The remaining tiles, too few to fill the chip, are each cut along K into `split` parts:
+// workgroup n_full_wgs + j takes part j % split of the tile after the whole ones + j / split and leaves its raw
+// accumulators in `partial`; gemm_fixup_kernel adds the parts in a fixed order and applies the epilogue.
 //
-// THIN: when the last tile row has at most 64 live rows (a prompt whose live rows are a multiple of the tile height
-// plus a few: the last reused token, a short suffix), its n_thin tiles are multiplied by a 64-row body whose eight
-// wavefronts sit side by side, which costs about a third of a full tile; `order` then describes the tile rows
+// Thin tiles: when the last tile row has at most 64 live rows (a prompt whose live rows are a multiple of the tile
+// height plus a few: the last reused token, a short suffix), its n_thin tiles are multiplied by a 64-row body whose
+// eight wavefronts sit side by side, which costs about a third of a full tile; `order` then describes the tile rows
 // above it only.  The thin tiles are always whole-K tiles and are dealt out evenly over the XCDs' queues, at
 // the tail of each, where they fill the last round.  (A 128-row body for up to 128 live rows was measured
 // as well: no gain.)
+struct GridPlan {
+  TileOrder order;      // the normal tiles (all tile rows, or all but the ragged last one)
+  int full_tiles;       // whole-K tiles: normal ones first, then the n_thin thin ones
+  int per_xcd;          // > 0: workgroup ids are regrouped per XCD, this many queue slots each
+  int n_full_wgs;       // workgroups reserved for whole-K tiles (some may stay empty)
+  int split, kpp;       // K parts per remaining tile, K steps per part
+  int n_thin;
+};
+struct BlockWork { int kind /* 0: nothing, 1: normal tile, 2: thin tile */, tile_m, tile_n, k_begin, k_end, part_slot; };
+
+__device__ __host__ inline BlockWork block_work(const GridPlan& g, int bid, int k) {
+  BlockWork bw = {0, 0, 0, 0, k, -1};
+  const int n_normal_full = g.full_tiles - g.n_thin;
+  int u = 0, thin_tile = -1;   // u: index among the normal tiles
+  if (bid < g.n_full_wgs) {
+    if (g.per_xcd > 0) {
+      const int x = bid % XCDS, j = bid / XCDS;
+      const int cnt = g.n_thin / XCDS + (x < g.n_thin % XCDS ? 1 : 0);                          // thin tiles of this XCD
+      const int before = x * (g.n_thin / XCDS) + (x < g.n_thin % XCDS ? x : g.n_thin % XCDS);   // ... of the XCDs before it
+      if (j >= g.per_xcd - cnt) thin_tile = (j - (g.per_xcd - cnt)) * XCDS + x;
+      else u = x * g.per_xcd - before + j;
+    } else if (bid >= n_normal_full) {
+      thin_tile = bid - n_normal_full;
+      if (thin_tile >= g.n_thin) return bw;
+    } else {
+      u = bid;
+    }
+    if (thin_tile < 0 && u >= n_normal_full) return bw;
+  } else {
+    const int j = bid - g.n_full_wgs;
+    u = n_normal_full + j / g.split;
+    bw.part_slot = j;
+    bw.k_begin = (j % g.split) * g.kpp * BK;
+    bw.k_end = bw.k_begin + g.kpp * BK < k ? bw.k_begin + g.kpp * BK : k;
+  }
+  if (thin_tile >= 0) {
+    bw.kind = 2;
+    bw.tile_m = g.order.tiles_m;   // the row below the normal ones
+    bw.tile_n = thin_tile;
+  } else {
+    bw.kind = 1;
+    tile_of(g.order, u, &bw.tile_m, &bw.tile_n);
+  }
+  return bw;
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool DUAL, int OCC, bool THIN>
 __global__ void __launch_bounds__(WAVES_M * WAVES_N * 64, OCC)
 gemm_mfma_dl_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const bf16* __restrict__ w2,
                     const bf16* __restrict__ w3, int ns1, int ns2, void* __restrict__ c, int m, int n, int k, int ldc,
-                    int epi, TileOrder order, int full_tiles, int per_xcd, int n_full_wgs, int split, int ksteps_per_part,
-                    float* __restrict__ partial, int n_thin) {
+                    int epi, GridPlan plan, float* __restrict__ partial) {
   constexpr int BN_OUT = DUAL ? BN / 2 : BN;
-  const int n_normal_full = full_tiles - n_thin;
-  int u = 0, thin_tile = -1, k_begin = 0, k_end = k, part_slot = -1;   // u: index among the normal tiles
-  if ((int)blockIdx.x < n_full_wgs) {
-    if (per_xcd > 0) {
-      const int x = (int)(blockIdx.x % XCDS), j = (int)(blockIdx.x / XCDS);
-      const int cnt = THIN ? n_thin / XCDS + (x < n_thin % XCDS ? 1 : 0) : 0;          // thin tiles of this XCD
-      const int before = THIN ? x * (n_thin / XCDS) + min(x, n_thin % XCDS) : 0;      // ... of the XCDs before it
-      if (j >= per_xcd - cnt) thin_tile = (j - (per_xcd - cnt)) * XCDS + x;
-      else u = x * per_xcd - before + j;
-    } else {
-      if (THIN && (int)blockIdx.x >= n_normal_full) {
-        thin_tile = (int)blockIdx.x - n_normal_full;
-        if (thin_tile >= n_thin) return;
-      } else {
-        u = (int)blockIdx.x;
-      }
-    }
-    if (thin_tile < 0 && u >= n_normal_full) return;
-  } else {
-    const int j = (int)blockIdx.x - n_full_wgs;
-    u = n_normal_full + j / split;
-    part_slot = j;
-    k_begin = (j % split) * ksteps_per_part * BK;
-    k_end = min(k, k_begin + ksteps_per_part * BK);
-  }
+  const BlockWork bw = block_work(plan, (int)blockIdx.x, k);
+  if (bw.kind == 0) return;
   if constexpr (THIN) {
-    if (thin_tile >= 0) {
-      const int m0 = order.tiles_m * BM, n0 = thin_tile * BN_OUT;
-      gemm_tile_body<64, BN, 1, 8, DUAL>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, m0, n0, 0, k, -1, partial);
+    if (bw.kind == 2) {
+      gemm_tile_body<64, BN, 1, 8, DUAL>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, bw.tile_m * BM, bw.tile_n * BN_OUT, 0, k,
+                                         -1, partial);
       return;
     }
   }
-  int tile_m, tile_n;
-  tile_of(order, u, &tile_m, &tile_n);
-  gemm_tile_body<BM, BN, WAVES_M, WAVES_N, DUAL>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, tile_m * BM, tile_n * BN_OUT,
-                                                 k_begin, k_end, part_slot, partial);
+  gemm_tile_body<BM, BN, WAVES_M, WAVES_N, DUAL>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, bw.tile_m * BM,
+                                                 bw.tile_n * BN_OUT, bw.k_begin, bw.k_end, bw.part_slot, partial);
 }
 
 // Sum of the K-split parts of the tail tiles (fixed order: part 0, 1, ...) followed by the epilogue.  One
@@ -622,27 +643,39 @@ static LaunchPlan plan_launch(int m, int tiles_n, int bm, int ksteps, int slots,
   return plain;
 }
 
+// the grid of a direct-to-LDS launch: tiles of bm rows, tiles_n tile columns
+static GridPlan make_grid_plan(int m, int tiles_n, int bm, int ksteps, int slots, float step, bool may_split, bool may_thin,
+                               int* n_blocks, int* rem_tiles) {
+  const int tiles_m = (m + bm - 1) / bm;
+  const LaunchPlan lp = plan_launch(m, tiles_n, bm, ksteps, slots, step, may_split, may_thin);
+  GridPlan g;
+  g.order = make_tile_order(lp.n_thin > 0 ? tiles_m - 1 : tiles_m, tiles_n);
+  g.full_tiles = lp.n_thin + lp.n_normal - lp.rem;
+  g.per_xcd = (g.full_tiles + XCDS - 1) / XCDS;
+  g.n_full_wgs = g.per_xcd * XCDS;
+  g.split = lp.split;
+  g.kpp = lp.kpp;
+  g.n_thin = lp.n_thin;
+  *n_blocks = g.n_full_wgs + lp.rem * lp.split;
+  *rem_tiles = lp.rem;
+  if (!g_xcd_remap) g.per_xcd = 0;
+  return g;
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int OCC>
 static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const bf16* w3, int ns1, int ns2, void* c,
                             int m, int n, int k, int ldc, GemmEpilogue epi, float* partial, hipStream_t st) {
   const bool dual = epi == EPI_SWIGLU_T;
   const int bn_out = dual ? BN / 2 : BN;
-  const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + bn_out - 1) / bn_out;
+  const int tiles_n = (n + bn_out - 1) / bn_out;
   // Full rounds of one tile per workgroup slot; the remainder (less than one round) is cut along K so
   // that it also fills the chip.  Only with a partial buffer, and only for the one-workgroup-per-CU tiles.
   constexpr bool THIN = BM == 256 && BN == 256 && OCC == 1;
-  const int slots = num_cus() * OCC;
-  const int ksteps = k / BK;
-  const LaunchPlan lp = plan_launch(m, tiles_n, BM, ksteps, slots, BN == 192 ? kStep192 : kStep256,
-                                    partial != nullptr && OCC == 1, THIN);
-  const int full_tiles = lp.n_thin + lp.n_normal - lp.rem;     // whole-K tiles
-  const int normal_full = lp.n_normal - lp.rem;
-  const int rem_tiles = lp.rem, split = lp.split, kpp = lp.kpp;
-  const TileOrder order = make_tile_order(lp.n_thin > 0 ? tiles_m - 1 : tiles_m, tiles_n);
-  int per_xcd = (full_tiles + XCDS - 1) / XCDS;
-  const int n_full_wgs = per_xcd * XCDS;
-  const dim3 grid((unsigned)(n_full_wgs + rem_tiles * split));
-  if (!g_xcd_remap) per_xcd = 0;
+  int n_blocks = 0, rem_tiles = 0;
+  const GridPlan plan = make_grid_plan(m, tiles_n, BM, k / BK, num_cus() * OCC, BN == 192 ? kStep192 : kStep256,
+                                       partial != nullptr && OCC == 1, THIN, &n_blocks, &rem_tiles);
+  const int normal_full = plan.full_tiles - plan.n_thin;
+  const dim3 grid((unsigned)n_blocks);
   constexpr int NT = WAVES_M * WAVES_N * 64;
   constexpr size_t lds_bytes = 2 * (size_t)(BM + BN) * 128;
   hipError_t e = hipSuccess;
@@ -651,23 +684,61 @@ static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const 
     static std::atomic<unsigned long long> told{0};
     e = allow_dynamic_lds((const void*)kern, (int)lds_bytes, told);
     if (e != hipSuccess) return e;
-    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, order, full_tiles, per_xcd,
-                                      n_full_wgs, split, kpp, partial, lp.n_thin);
+    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, plan, partial);
     if (rem_tiles > 0)
       gemm_fixup_kernel<BM, BN, WAVES_M, WAVES_N, true><<<rem_tiles * (BM / WAVES_M / 16) * (BN / WAVES_N / 32), NT, 0, st>>>(
-          c, m, n, ldc, (int)epi, order, normal_full, split, partial);
+          c, m, n, ldc, (int)epi, plan.order, normal_full, plan.split, partial);
   } else {
     auto kern = gemm_mfma_dl_kernel<BM, BN, WAVES_M, WAVES_N, false, OCC, THIN>;
     static std::atomic<unsigned long long> told{0};
     e = allow_dynamic_lds((const void*)kern, (int)lds_bytes, told);
     if (e != hipSuccess) return e;
-    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, order, full_tiles, per_xcd,
-                                      n_full_wgs, split, kpp, partial, lp.n_thin);
+    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, plan, partial);
     if (rem_tiles > 0)
       gemm_fixup_kernel<BM, BN, WAVES_M, WAVES_N, false><<<rem_tiles * (BM / WAVES_M / 16) * (BN / WAVES_N / 16), NT, 0, st>>>(
-          c, m, n, ldc, (int)epi, order, normal_full, split, partial);
+          c, m, n, ldc, (int)epi, plan.order, normal_full, plan.split, partial);
   }
   return hipGetLastError();
+}
+
+// Host-side check of a launch's grid: every output tile must be covered exactly once, by one whole-K workgroup or by
+// K parts that partition [0, k) in part order; thin tiles only in the last tile row and only for at most 64 live rows.
+// Returns the number of violations; *n_blocks_out receives the grid size.  tile: 5, 6 or 7; n_cus: CUs to plan for.
+int check_grid_plan(int m, int n, int k, bool dual, int tile, int n_cus, bool with_partial, int* n_blocks_out) {
+  const int bm = tile == 6 ? 128 : 256, bn = tile == 6 ? 128 : (tile == 7 ? 192 : 256), occ = tile == 6 ? 2 : 1;
+  const int bn_out = dual ? bn / 2 : bn;
+  const int tiles_m = (m + bm - 1) / bm, tiles_n = (n + bn_out - 1) / bn_out;
+  int n_blocks = 0, rem_tiles = 0;
+  const GridPlan g = make_grid_plan(m, tiles_n, bm, k / BK, n_cus * occ, tile == 7 ? kStep192 : kStep256,
+                                    with_partial && occ == 1, tile == 5, &n_blocks, &rem_tiles);
+  if (n_blocks_out) *n_blocks_out = n_blocks;
+  int errors = 0;
+  std::vector<int> covered((size_t)tiles_m * tiles_n, 0), next_k((size_t)tiles_m * tiles_n, 0), slots;
+  for (int bid = 0; bid < n_blocks; ++bid) {
+    const BlockWork bw = block_work(g, bid, k);
+    if (bw.kind == 0) continue;
+    if (bw.tile_m < 0 || bw.tile_m >= tiles_m || bw.tile_n < 0 || bw.tile_n >= tiles_n) { ++errors; continue; }
+    const size_t t = (size_t)bw.tile_m * tiles_n + bw.tile_n;
+    if (bw.kind == 2 && (bw.tile_m != tiles_m - 1 || m - (tiles_m - 1) * bm > kThinRows || bw.part_slot >= 0)) ++errors;
+    if (bw.part_slot < 0) {
+      if (bw.k_begin != 0 || bw.k_end != k || covered[t] != 0) ++errors;
+      covered[t] = 1;
+      next_k[t] = k;
+    } else {
+      // parts arrive in block order = part order
+      if (covered[t] == 1 || bw.k_begin != next_k[t] || bw.k_end <= bw.k_begin || bw.k_end > k) ++errors;
+      covered[t] = 2;
+      next_k[t] = bw.k_end;
+      slots.push_back(bw.part_slot);
+    }
+  }
+  for (size_t t = 0; t < covered.size(); ++t)
+    if (covered[t] == 0 || next_k[t] != k) ++errors;
+  // part slots are 0, 1, ... without gaps and fit the partial buffer
+  for (size_t i = 0; i < slots.size(); ++i)
+    if (slots[i] != (int)i) ++errors;
+  if (slots.size() > 256) ++errors;
+  return errors;
 }
 
 static int g_gemm_tile = 0;   // 0: by shape; 1-3: register-staged 128x256 / 256x256 / 128x128; 5-7: direct-to-LDS 256x256 / 128x128 / 256x192
