@@ -393,10 +393,32 @@ attn_merge_kernel(const int* __restrict__ row_pos, const int* __restrict__ row_r
   const int nc = min(sp.n_chunks, row_pos[r] / (sp.chunk_tiles * BKV) + 1);
   const size_t slot0 = ((size_t)(part_base + split_tile * sp.n_chunks) * n_q_heads + head) * BQ + ql;
   const size_t cstride = (size_t)n_q_heads * BQ;
+  // Pass 1, one chunk per lane (64 at a time): the common reference exponent.  Pass 2: every lane needs every
+  // chunk's weight, so the (m, l) pairs are read again (they are cached) and the partial outputs of four chunks are
+  // requested before the first is used.  The sums run in chunk order.
   float m = -INFINITY;
-  for (int c = 0; c < nc; ++c) m = fmaxf(m, part_ml[slot0 + c * cstride].x);
+  for (int c = lane; c < nc; c += 64) m = fmaxf(m, part_ml[slot0 + c * cstride].x);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
   float l = 0.f, o0 = 0.f, o1 = 0.f;
-  for (int c = 0; c < nc; ++c) {
+  int c = 0;
+  for (; c + 4 <= nc; c += 4) {
+    float2 ml[4], o[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t slot = slot0 + (c + u) * cstride;
+      ml[u] = part_ml[slot];
+      o[u] = *reinterpret_cast<const float2*>(part_o + slot * DH + 2 * lane);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float wgt = (ml[u].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml[u].x - m);
+      l += ml[u].y * wgt;
+      o0 += o[u].x * wgt;
+      o1 += o[u].y * wgt;
+    }
+  }
+  for (; c < nc; ++c) {
     const size_t slot = slot0 + c * cstride;
     const float2 ml = part_ml[slot];
     const float wgt = (ml.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml.x - m);
