@@ -343,6 +343,11 @@ def test_gemm_ragged_last_tile_row(epilogue, m):
         want, tol = R.silu(prod) * R.linear(a.astype(np.float64), w2.astype(np.float64)), 4e-3
     torch.cuda.synchronize()
     assert rel_err(to_np(c), want) <= tol
+    if epilogue == "store":     # without a workspace: no K-split tail, every tile is done by one workgroup
+        c1 = torch.zeros_like(c)
+        rc.rc_gemm_rows(rc.RC_BF16, _up(a, "bf16"), _up(w, "bf16"), c1, m, n, k, None)
+        torch.cuda.synchronize()
+        assert rel_err(to_np(c1), want) <= tol
     # the same launch with the thin bodies switched off (only the K-split tail may fall on other tiles)
     rc.rc_tune_set(rc.RC_TUNE_GEMM_THIN_TILES, 0)
     try:
