@@ -56,15 +56,16 @@ def gemm_flops_batch(w, lens, ks):
     return fl, rows
 
 
-def recorded_gemm_traffic(workload: str):
-    """Bytes crossing the L2 boundary per GEMM launch, from the committed rocprofv3 counter summary of this
-    workload (profiles/), or None if there is none.  Counters cannot be read from inside the process."""
+def recorded_gemm_traffic(workload: str, gemm_launches: int):
+    """Bytes crossing the L2 boundary per GEMM launch (a fix-up kernel counted with its GEMM, as in the roofline's
+    launch count), from the committed rocprofv3 counter summary of this workload (profiles/), or None if there is
+    none.  Counters cannot be read from inside the process."""
     path = os.path.join(ROOT, "profiles", f"rc_reuse_{workload}_l2_traffic.txt")
     try:
         with open(path) as f:
             for line in f:
-                if line.startswith("gemm_hbm_bytes_per_launch"):
-                    return float(line.split()[1])
+                if line.startswith("gemm_hbm_bytes_per_call"):
+                    return float(line.split()[1]) / max(gemm_launches, 1)
     except OSError:
         pass
     return None
@@ -409,7 +410,7 @@ def main() -> int:
                    "kv_layout": "contiguous" if w.block_size == 0 else f"paged, {w.block_size}-token blocks, shuffled",
                    "batch": n_req},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": recorded_gemm_traffic(w.name),
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": recorded_gemm_traffic(w.name, gemm_launches),
                      "kernel": "projection GEMMs (all launches of one step)",
                      "algorithmic_gflop_per_step": fl / 1e9, "gemm_ms_per_step": gemm_ms,
                      "gemm_launches_per_step": gemm_launches,
