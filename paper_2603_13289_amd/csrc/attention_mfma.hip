@@ -143,7 +143,7 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   }
   // the tile fetched during step t is staged during step t + 1 and multiplied in step t + 2
   uint4 rk[KPER], rv[VPER][4];
-  auto fetch = [&](int kv0) {
+  auto fetch_k = [&](int kv0) {
     const bool full = kv0 + BKV - 1 <= last_pos;   // uniform: only a query tile's last KV tile can be ragged
 #pragma unroll
     for (int i = 0; i < KPER; ++i) {
@@ -155,6 +155,9 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
         rk[i] = *reinterpret_cast<const uint4*>(src);
       }
     }
+  };
+  auto fetch_v = [&](int kv0) {
+    const bool full = kv0 + BKV - 1 <= last_pos;
 #pragma unroll
     for (int i = 0; i < VPER; ++i) {
       const int dch = vdch0 + i * KSTEP;
@@ -174,11 +177,15 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   const int vcol = (vkey0 & ~15) + 8 * ((vkey0 >> 2) & 1) + 4 * ((vkey0 >> 3) & 1);
   unsigned char* const k_wr = lds_k + krow0 * KROW + kch * 16;
   unsigned char* const v_wr = lds_vt + vdch0 * 8 * VROW + vcol * 2;
-  auto stage = [&](auto buf) {
-    constexpr int KOFF = decltype(buf)::value * K_TILE_BYTES, VOFF = decltype(buf)::value * V_TILE_BYTES;
+  auto stage_k = [&](auto buf) {
+    constexpr int KOFF = decltype(buf)::value * K_TILE_BYTES;
 #pragma unroll
     for (int i = 0; i < KPER; ++i)
       if (krow0 + i * KSTEP < BKV) *reinterpret_cast<uint4*>(k_wr + KOFF + i * KSTEP * KROW) = rk[i];
+  };
+  // V^T rows e_begin .. e_end - 1 (of the 8 head-dim elements a thread's block covers)
+  auto stage_v = [&](auto buf, int e_begin, int e_end) {
+    constexpr int VOFF = decltype(buf)::value * V_TILE_BYTES;
 #pragma unroll
     for (int i = 0; i < VPER; ++i) {
       if (vdch0 + i * KSTEP >= 16) continue;
@@ -188,6 +195,7 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
                                 {rv[i][3].x, rv[i][3].y, rv[i][3].z, rv[i][3].w}};
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
+        if (e < e_begin || e >= e_end) continue;
         const int wi = e >> 1;
         // byte select: even e packs the low halves of two words, odd e the high halves
         const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
@@ -210,19 +218,28 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   const std::integral_constant<int, 0> buf0;
   const std::integral_constant<int, 1> buf1;
   // prologue: the first tile goes to buffer 0, the second one is on its way in registers
-  fetch(t_begin * BKV);
-  stage(buf0);
-  if (t_begin + 1 < t_end) fetch((t_begin + 1) * BKV);
+  fetch_k(t_begin * BKV);
+  fetch_v(t_begin * BKV);
+  stage_k(buf0);
+  stage_v(buf0, 0, 8);
+  if (t_begin + 1 < t_end) {
+    fetch_k((t_begin + 1) * BKV);
+    fetch_v((t_begin + 1) * BKV);
+  }
   __syncthreads();
-  // step i (tile t = t_begin + i) multiplies buffer i % 2; before that it stages tile t + 1 into the other buffer
-  // (free since the barrier that ended step i - 1) and starts the loads of tile t + 2
+  // step i (tile t = t_begin + i) multiplies buffer i % 2; meanwhile it stages tile t + 1 into the other buffer
+  // (free since the barrier that ended step i - 1) and starts the loads of tile t + 2.  That staging is vector-ALU
+  // and LDS-write work, which is dealt out between the MFMAs of S^T so that it runs while the matrix pipe is busy.
   auto tile_step = [&](int t, auto buf) {
     constexpr int KOFF = decltype(buf)::value * K_TILE_BYTES, VOFF = decltype(buf)::value * V_TILE_BYTES;
+    const std::integral_constant<int, 1 - decltype(buf)::value> other;
     const int kv0 = t * BKV;
-    if (t + 1 < t_end) {
-      stage(std::integral_constant<int, 1 - decltype(buf)::value>());
-      if (t + 2 < t_end) fetch(kv0 + 2 * BKV);
-    }
+    const bool has_next = t + 1 < t_end, has_next2 = t + 2 < t_end;
+    auto staging_slice = [&](int i) {   // i-th of the 16 gaps between the MFMAs of S^T
+      if (!has_next) return;
+      if (i == 0) stage_k(other);
+      else if (i >= 1 && i <= 4) stage_v(other, 2 * (i - 1), 2 * i);
+    };
 
     // S^T = K Q^T : two blocks of 32 keys.  The two accumulator chains alternate and the K fragments are read
     // kFragAhead MFMAs ahead of their use, so that neither the LDS latency nor the MFMA dependency is exposed.
@@ -243,8 +260,13 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
       for (int i = 0; i < 16; ++i) {
         acc_s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % kFragAhead], qf[i >> 1], acc_s[i & 1], 0, 0, 0);
         if (i + kFragAhead < 16) kf[i % kFragAhead] = k_frag(i + kFragAhead);
+        staging_slice(i);
         __builtin_amdgcn_sched_barrier(0);
       }
+    }
+    if (has_next2) {
+      fetch_k(kv0 + 2 * BKV);
+      fetch_v(kv0 + 2 * BKV);
     }
     // the first V^T fragments do not depend on the softmax: their LDS reads run under it
     auto v_frag = [&](int i) {     // step i: head-dim block i & 3, key step i >> 2
