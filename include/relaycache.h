@@ -318,6 +318,24 @@ RC_API rc_status rc_rope_rerotate(const rc_kv_layer* src, int32_t src_seq, int32
                            int32_t n_tokens, int32_t k_is_pre_rope, int32_t old_start_pos,
                            float rope_base, void* workspace, size_t workspace_bytes, void* stream);
 
+/* rc_rope_rerotate for callers that cannot allocate or hand over device scratch: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bit-identical results, but the stage's scratch (request table, rotary table) is a fixed device array
+ * inside the library: rc_rope_rerotate_static_scratch_bytes() bytes (about 16 MiB) that every GPU the
+ * library runs on holds until the process ends.  The call allocates and frees nothing.
+ *   limit   dst_offset + n_tokens <= RC_REROTATE_STATIC_MAX_POSITIONS, else RC_E_CAPACITY (nothing is
+ *           launched).
+ *   sharing all calls on one GPU use that GPU's one array: calls that overlap in time on the same GPU
+ *           (different streams or threads) race; serialise them.  The array keeps the last call's tables;
+ *           nothing in it has to start at zero, every table entry a call reads it has written itself.
+ * Other errors as rc_rope_rerotate; RC_E_HIP if the array's address cannot be obtained. */
+#define RC_REROTATE_STATIC_MAX_POSITIONS 32768
+RC_API size_t rc_rope_rerotate_static_scratch_bytes(void);
+RC_API rc_status rc_rope_rerotate_static(const rc_kv_layer* src, int32_t src_seq, int32_t src_offset,
+                                  const rc_kv_layer* dst, int32_t dst_seq, int32_t dst_offset,
+                                  int32_t n_tokens, int32_t k_is_pre_rope, int32_t old_start_pos,
+                                  float rope_base, void* stream);
+
 /* Eq. (1): score[j] = 1 - mean_h cos(cache V row (offset + j, h), v_fresh[j][h]); H = KV heads;
  * cos = dot / max(|a||b|, 1e-12).  Accumulated in float; above the floor 1 - cos is evaluated in the
  * equivalent cancellation-free form 0.5 |a/|a| - b/|b||^2.  v_fresh [n_tokens][Hkv][dh] of T.

@@ -29,7 +29,7 @@ EXPORTS = [
     "rc_ceiling_mfma_loop_out_bytes", "rc_ceiling_mfma_loop", "rc_gemm_plan_check",
     "rc_scatter_paged", "rc_profile_enable", "rc_profile_class_count", "rc_profile_class_name", "rc_profile_read",
     "rc_tune_set", "rc_sparse_attention_workspace_bytes",
-    "rc_gemm_workspace_bytes",
+    "rc_gemm_workspace_bytes", "rc_rope_rerotate_static", "rc_rope_rerotate_static_scratch_bytes",
 ]
 
 
@@ -123,6 +123,11 @@ def _load() -> C.CDLL:
     lib.rc_rope_rerotate.restype = C.c_int
     lib.rc_rope_rerotate.argtypes = [C.POINTER(rc_kv_layer), i32, i32, C.POINTER(rc_kv_layer), i32, i32, i32, i32,
                                      i32, C.c_float, vp, sz, vp]
+    lib.rc_rope_rerotate_static.restype = C.c_int
+    lib.rc_rope_rerotate_static.argtypes = [C.POINTER(rc_kv_layer), i32, i32, C.POINTER(rc_kv_layer), i32, i32, i32,
+                                            i32, i32, C.c_float, vp]
+    lib.rc_rope_rerotate_static_scratch_bytes.restype = sz
+    lib.rc_rope_rerotate_static_scratch_bytes.argtypes = []
     lib.rc_vdev_score.restype = C.c_int
     lib.rc_vdev_score.argtypes = [vp, C.POINTER(rc_kv_layer), i32, i32, i32, vp, vp, sz, vp]
     lib.rc_topk.restype = C.c_int
@@ -455,6 +460,21 @@ def rc_rope_rerotate(src: rc_kv_layer, src_seq: int, src_offset: int, dst: rc_kv
     _check(lib.rc_rope_rerotate(C.byref(src), src_seq, src_offset, C.byref(dst), dst_seq, dst_offset, n_tokens,
                                 1 if k_is_pre_rope else 0, old_start_pos, rope_base, _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream(stream)), "rc_rope_rerotate")
+
+
+RC_REROTATE_STATIC_MAX_POSITIONS = 32768
+
+
+def rc_rope_rerotate_static_scratch_bytes() -> int:
+    return int(lib.rc_rope_rerotate_static_scratch_bytes())
+
+
+def rc_rope_rerotate_static(src: rc_kv_layer, src_seq: int, src_offset: int, dst: rc_kv_layer, dst_seq: int,
+                            dst_offset: int, n_tokens: int, k_is_pre_rope: bool, old_start_pos: int,
+                            rope_base: float, stream=None) -> None:
+    _check(lib.rc_rope_rerotate_static(C.byref(src), src_seq, src_offset, C.byref(dst), dst_seq, dst_offset,
+                                       n_tokens, 1 if k_is_pre_rope else 0, old_start_pos, rope_base,
+                                       _stream(stream)), "rc_rope_rerotate_static")
 
 
 def rc_vdev_score(v_fresh: torch.Tensor, cache: rc_kv_layer, seq: int, offset: int, n_tokens: int,

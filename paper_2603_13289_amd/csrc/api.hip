@@ -921,10 +921,10 @@ size_t rc_stage_workspace_bytes(int32_t n_positions, int32_t head_dim) {
          align_up(sizeof(float2) * (size_t)(head_dim / 2));
 }
 
-rc_status rc_rope_rerotate(const rc_kv_layer* src, int32_t src_seq, int32_t src_offset, const rc_kv_layer* dst,
-                           int32_t dst_seq, int32_t dst_offset, int32_t n_tokens, int32_t k_is_pre_rope,
-                           int32_t old_start_pos, float rope_base, void* workspace, size_t workspace_bytes,
-                           void* stream) {
+// Argument checks shared by rc_rope_rerotate and its allocation-free twin (everything but the scratch).
+static rc_status check_rerotate(const rc_kv_layer* src, int32_t src_seq, int32_t src_offset, const rc_kv_layer* dst,
+                                int32_t dst_seq, int32_t dst_offset, int32_t n_tokens, int32_t old_start_pos,
+                                float rope_base) {
   RC_TRY(check_kv_layer(src));
   RC_TRY(check_kv_layer(dst));
   if (src->n_kv_heads != dst->n_kv_heads || src->head_dim != dst->head_dim || src->dtype != dst->dtype)
@@ -935,12 +935,16 @@ rc_status rc_rope_rerotate(const rc_kv_layer* src, int32_t src_seq, int32_t src_
   if ((long)src_offset + n_tokens > (long)src->max_blocks_per_seq * src->block_size ||
       (long)dst_offset + n_tokens > (long)dst->max_blocks_per_seq * dst->block_size)
     return RC_E_CAPACITY;
-  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RC_E_WORKSPACE;
+  return RC_OK;
+}
+
+// The launches of the re-rotation stage; `scratch` holds rc_stage_workspace_bytes(dst_offset + n_tokens, head_dim)
+// bytes of device memory: the request table, then the rotary table, then the delta table.
+static rc_status enqueue_rerotate(const rc_kv_layer* src, int32_t src_seq, int32_t src_offset, const rc_kv_layer* dst,
+                                  int32_t dst_seq, int32_t dst_offset, int32_t n_tokens, int32_t k_is_pre_rope,
+                                  int32_t old_start_pos, float rope_base, void* scratch, hipStream_t st) {
   const int n_pos = dst_offset + n_tokens;
-  if (rc_stage_workspace_bytes(n_pos, src->head_dim) > workspace_bytes) return RC_E_WORKSPACE;
-  if (n_tokens == 0) return RC_OK;
-  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  char* p = reinterpret_cast<char*>(workspace);
+  char* p = reinterpret_cast<char*>(scratch);
   ReqTable* dt = reinterpret_cast<ReqTable*>(p);
   float2* rope_tab = reinterpret_cast<float2*>(p + align_up(sizeof(ReqTable)));
   float2* delta_tab = reinterpret_cast<float2*>(p + align_up(sizeof(ReqTable)) +
@@ -962,6 +966,63 @@ rc_status rc_rope_rerotate(const rc_kv_layer* src, int32_t src_seq, int32_t src_
   else
     RC_HIP(launch_rerotate<float>(ptrs, 1, geom_of(*src), geom_of(*dst), dt, 1, n_tokens, rope_tab, delta_tab, st));
   return RC_OK;
+}
+
+rc_status rc_rope_rerotate(const rc_kv_layer* src, int32_t src_seq, int32_t src_offset, const rc_kv_layer* dst,
+                           int32_t dst_seq, int32_t dst_offset, int32_t n_tokens, int32_t k_is_pre_rope,
+                           int32_t old_start_pos, float rope_base, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+  RC_TRY(check_rerotate(src, src_seq, src_offset, dst, dst_seq, dst_offset, n_tokens, old_start_pos, rope_base));
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RC_E_WORKSPACE;
+  if (rc_stage_workspace_bytes(dst_offset + n_tokens, src->head_dim) > workspace_bytes) return RC_E_WORKSPACE;
+  if (n_tokens == 0) return RC_OK;
+  return enqueue_rerotate(src, src_seq, src_offset, dst, dst_seq, dst_offset, n_tokens, k_is_pre_rope, old_start_pos,
+                          rope_base, workspace, reinterpret_cast<hipStream_t>(stream));
+}
+
+// ------------------------------------------------------------------ the same stage without any allocation
+// The scratch of the re-rotation stage (request table, rotary table, delta table) lives in a device array of the
+// library instead of a caller's workspace.  Every GPU holds its own copy of the array at its own address; host code
+// never uses the array's name as an address, only what hipGetSymbolAddress returned for the current device.
+static constexpr int kStaticMaxPositions = RC_REROTATE_STATIC_MAX_POSITIONS;
+static constexpr size_t kStaticScratchBytes =
+    ((sizeof(ReqTable) + 255) / 256 * 256) + (size_t)(kStaticMaxPositions + 1) * 64 * sizeof(float2) + 256 +
+    64 * sizeof(float2) + 256;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// device address of `scratch` on the current device, looked up once per device
+static rc_status static_scratch(void** out) {
+  int dev = 0;
+  RC_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return RC_E_CAPACITY;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    RC_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return RC_E_HIP;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return RC_OK;
+}
+
+size_t rc_rope_rerotate_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+rc_status rc_rope_rerotate_static(const rc_kv_layer* src, int32_t src_seq, int32_t src_offset, const rc_kv_layer* dst,
+                                  int32_t dst_seq, int32_t dst_offset, int32_t n_tokens, int32_t k_is_pre_rope,
+                                  int32_t old_start_pos, float rope_base, void* stream) {
+  RC_TRY(check_rerotate(src, src_seq, src_offset, dst, dst_seq, dst_offset, n_tokens, old_start_pos, rope_base));
+  if ((long)dst_offset + n_tokens > kStaticMaxPositions) return RC_E_CAPACITY;
+  if (rc_stage_workspace_bytes(dst_offset + n_tokens, src->head_dim) > kStaticScratchBytes) return RC_E_CAPACITY;
+  if (n_tokens == 0) return RC_OK;
+  void* ptr = nullptr;
+  RC_TRY(static_scratch(&ptr));
+  // every byte of the scratch that the kernels read is written earlier in the same call (tables), so nothing
+  // has to be cleared between calls
+  return enqueue_rerotate(src, src_seq, src_offset, dst, dst_seq, dst_offset, n_tokens, k_is_pre_rope, old_start_pos,
+                          rope_base, ptr, reinterpret_cast<hipStream_t>(stream));
 }
 
 rc_status rc_vdev_score(const void* v_fresh, const rc_kv_layer* cache, int32_t seq, int32_t offset,
