@@ -53,9 +53,16 @@ Readings taken where the paper is silent (all restated in the design notes):
     of equal deviations are averaged; rho_l compares layers l-1 and l; the
     "min rise samples" hyper-parameter is listed but never used by the text.
 
+    l* is the first layer whose second difference alpha is negative directly
+    after a positive one, and l_det = l* + 1.
+
 Pins: tests/test_oracle_pins.py.  No function here is unpinned, except that
 nothing fixes the numeric values of scores on trained models (the paper prints
-none): that part is "parity unpinned" by necessity.
+none): that part is "parity unpinned" by necessity; and the index base of
+rho / alpha in the profiler's detection rule, which the rule's hand-worked
+example fixes for this reading only: the table "Model-specific layer
+configurations" lists detection layers 3 and 4, which this reading reaches
+only through its l_start + 1 fallback ("parity unpinned").
 """
 from __future__ import annotations
 

@@ -35,6 +35,17 @@ def test_layer_profile_matches_oracle(idx, params):
     assert 0 <= l_start and l_start <= l_end < d.shape[1] and l_det <= l_end
 
 
+def test_layer_profile_hand_worked_detection_layer():
+    """The library's profiler on rankings written out by hand: rho, the first positive-to-negative change of the
+    second difference at l* = 5 and l_det = l* + 1 = 6 are typed-in numbers (tests/hand_profiles.py)."""
+    from tests import hand_profiles as H
+    (l_start, l_det, l_end), s, rho = rc.rc_layer_profile(H.deviations().T.astype(np.float32))
+    assert (l_start, l_det, l_end) == H.TRIPLE == (2, 6, 8)
+    assert np.allclose(rho, H.RHO, atol=1e-12) and np.allclose(s, H.S, atol=1e-6)
+    flat = rc.rc_layer_profile(H.deviations(ranks=[H.RANKS[0]] + [H.RANKS[5]] * 11).T.astype(np.float32))[0]
+    assert flat == (2, 3, 8)
+
+
 def test_layer_profile_argument_errors():
     d = np.zeros((3, 4), np.float32)
     for bad in (dict(tail=0), dict(consecutive=0), dict(lam=-1.0)):

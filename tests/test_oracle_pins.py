@@ -475,6 +475,28 @@ def test_profiler_start_and_end_layer_hand_example():
     assert R.profile_layers(_deviations_with_profile(s), tau_st=1.5).l_start == 0
 
 
+def test_profiler_detection_layer_hand_example():
+    """Eq. (4) and the choice of l* on rankings written out by hand (tests/hand_profiles.py): rho, alpha and the
+    triple are typed-in numbers, not recomputed by any rule."""
+    from tests import hand_profiles as H
+    prof = R.profile_layers(H.deviations())
+    assert np.allclose(prof.s, H.S, atol=1e-12)
+    assert np.allclose(prof.rho, H.RHO, atol=1e-12)
+    assert np.allclose(prof.alpha, H.ALPHA, atol=1e-12)
+    assert (prof.l_start, prof.l_det, prof.l_end) == H.TRIPLE == (2, 6, 8)
+    # rankings that never change from layer 1 on: rho = 1, alpha = 0, no sign change -> l_start + 1
+    flat = R.profile_layers(H.deviations(ranks=[H.RANKS[0]] + [H.RANKS[5]] * 11))
+    assert (flat.l_start, flat.l_det, flat.l_end) == (2, 3, 8)
+    # another similarity profile under the same rankings (start and end move, l* does not), worked by hand:
+    #   minimum at layer 4; tau_st 0.96: deepest layer <= 4 with s >= 0.96 is 3.
+    #   last five layers 0.952 0.951 0.952 0.951 0.952: mean 0.9516, population std 0.00049, b = 0.95111.
+    #   l = 4: s5 = 0.950 < b.  l = 5: s6 = 0.951 < b.  l = 6: s7 ok, s8 = 0.951 < b.  l = 7: s8 < b.
+    #   l = 8: s9 ok, s10 < b.  l = 9: s10 < b.  No layer qualifies: l_end = 11, and 6 lies inside (3, 11].
+    s_short = [0.999, 0.995, 0.992, 0.97, 0.90, 0.95, 0.951, 0.952, 0.951, 0.952, 0.951, 0.952]
+    short = R.profile_layers(H.deviations(s=s_short), tau_st=0.96, lam=50.0)
+    assert (short.l_start, short.l_det, short.l_end) == (3, 6, 11)
+
+
 def test_profiler_rank_correlation_against_library_and_sign_change():
     import scipy.stats
     rng = np.random.default_rng(5)
