@@ -153,9 +153,34 @@ def cpu_baseline(w, budget_s=20.0):
     _, full_rows = gemm_flops(w, P, S, k)
     est_ttft = dt * full_rows / sample_rows
     return {"value": (P + S) / est_ttft, "unit": "context tokens/s", "cores": int(threads), "kind": "oracle",
+            "extrapolated": True, "sample_seconds": dt, "tiny_f32_one_thread": tiny_one_thread(),
             "sample": f"oracle relay_prefill (numpy float64) on a 3-layer instance of the workload's widths, "
                       f"P={P}, S={S}, k={k}, triple (0,1,2): {sample_rows} row-layers in {dt:.1f} s, scaled to the "
                       f"workload's {full_rows} row-layers (estimated TTFT {est_ttft:.0f} s)"}
+
+
+def tiny_one_thread():
+    """The oracle on the small float configuration (2 layers, 128 new + 256 reused tokens, 20 %), timed directly
+    (no scaling) with numpy's BLAS held to one thread."""
+    import numpy as np
+    from oracle import relay_oracle as R
+    from synth import WORKLOADS, make_hidden, make_weights, budget_to_k
+    try:
+        from threadpoolctl import threadpool_limits
+    except Exception:
+        return None
+    w = WORKLOADS["tiny_f32"]
+    om = R.OracleModel.from_shape(w.shape, make_weights(w))
+    xp, xa, xs = (make_hidden(w, n, c) for n, c in (("x_prefix", w.n_prefix), ("x_alt", w.n_alt), ("x_seg", w.n_seg)))
+    with threadpool_limits(limits=1):
+        seg = R.decode_record(om, xa, xs, w.l_start)
+        best = 1e30
+        for _ in range(3):
+            t0 = time.perf_counter()
+            R.relay_prefill(om, xp, seg, w.l_start, w.l_det, w.l_end, budget_to_k(w.n_seg, w.budget_pct))
+            best = min(best, time.perf_counter() - t0)
+    return {"value": (w.n_prefix + w.n_seg) / best, "unit": "context tokens/s", "cores": 1, "ttft_ms": best * 1e3,
+            "workload": "tiny_f32", "extrapolated": False}
 
 
 def main() -> int:
@@ -256,6 +281,18 @@ def main() -> int:
     torch.cuda.synchronize()
     ms_per_step = ev0.elapsed_time(ev1) / args.steps
 
+    # TTFT as a caller sees it: every call timed on its own (enqueue to logits ready), median of at least 10
+    singles = []
+    for _ in range(max(args.steps, 10)):
+        torch.cuda.synchronize()
+        ev0.record()
+        step()
+        ev1.record()
+        torch.cuda.synchronize()
+        singles.append(ev0.elapsed_time(ev1))
+    singles.sort()
+    ttft_median = singles[len(singles) // 2] if len(singles) % 2 else 0.5 * (singles[len(singles) // 2 - 1] + singles[len(singles) // 2])
+
     # per-stage split of the same steps, with HIP events around every launch on the same stream
     rc.rc_profile_enable(True)
     torch.cuda.synchronize()
@@ -271,7 +308,7 @@ def main() -> int:
               for name, (ms, n) in prof.items() if n}
     gemm_ms = sum(v["ms_per_step"] for n, v in stages.items() if n.startswith("gemm"))
     gemm_launches = sum(v["launches_per_step"] for n, v in stages.items() if n.startswith("gemm"))
-    fl, rows = gemm_flops_batch(w, lens, ks)
+    fl, row_layers = gemm_flops_batch(w, lens, ks)
     achieved = fl / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
 
     # bandwidth-bound stages and attention against their own rooflines (algorithmic bytes / FLOPs only)
@@ -393,7 +430,9 @@ def main() -> int:
         "metric": METRIC,
         "value": ctx_tokens / (ms_per_step * 1e-3),
         "unit": "context tokens/s",
-        "ttft_ms": ms_per_step,
+        "ttft_ms": ttft_median,
+        "ttft_ms_min_max": [singles[0], singles[-1]],
+        "ttft_calls": len(singles),
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
@@ -411,10 +450,12 @@ def main() -> int:
                    "batch": n_req},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": recorded_gemm_traffic(w.name, gemm_launches),
+                     "traffic_source": f"profiles/rc_reuse_{w.name}_l2_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                                       "runs of `bench.py --counter-pass`; counters cannot be read inside this process)",
                      "kernel": "projection GEMMs (all launches of one step)",
                      "algorithmic_gflop_per_step": fl / 1e9, "gemm_ms_per_step": gemm_ms,
                      "gemm_launches_per_step": gemm_launches,
-                     "avg_launch_us": 1e3 * gemm_ms / max(gemm_launches, 1), "row_layers": rows},
+                     "avg_launch_us": 1e3 * gemm_ms / max(gemm_launches, 1), "row_layers": row_layers},
         "stages_ms": {n: round(v["ms_per_step"], 4) for n, v in stages.items()},
         "stage_rooflines": stage_rooflines,
         "ms_per_step_with_stage_events": ms_per_step_profiled,

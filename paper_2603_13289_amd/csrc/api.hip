@@ -686,7 +686,7 @@ rc_status rc_model_create(const rc_model_desc* desc, const rc_layer_w* layers, c
 }
 
 rc_status rc_tune_set(int32_t key, int32_t value) {
-  if (key == RC_TUNE_GEMM_TILE && (value == 0 || value == 1 || value == 2 || value == 3 || value == 5 || value == 6 || value == 7)) {
+  if (key == RC_TUNE_GEMM_TILE && (value == 0 || value == 1 || value == 2 || value == 3 || value == 5 || value == 6 || value == 7 || value == 8)) {
     set_gemm_tile(value);
     return RC_OK;
   }

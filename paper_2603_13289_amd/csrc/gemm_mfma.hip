@@ -502,8 +502,8 @@ gemm_mfma_dl_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, cons
   if (bw.kind == 0) return;
   if constexpr (THIN) {
     if (bw.kind == 2) {
-      gemm_tile_body<64, BN, 1, 8, DUAL>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, bw.tile_m * BM, bw.tile_n * BN_OUT, 0, k,
-                                         -1, partial);
+      gemm_tile_body<64, BN, 1, WAVES_M * WAVES_N, DUAL>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, bw.tile_m * BM,
+                                                         bw.tile_n * BN_OUT, 0, k, -1, partial);
       return;
     }
   }
@@ -798,6 +798,7 @@ static hipError_t dispatch(const bf16* a, const bf16* w, const bf16* w2, const b
     case 5: return launch_dl<256, 256, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st);
     case 6: return launch_dl<128, 128, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, nullptr, st);
     case 7: return launch_dl<256, 192, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st);
+    case 8: return launch_dl<256, 256, 2, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st);
     case 2: return launch_cfg<256, 256, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);
     case 3: return launch_cfg<128, 128, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);
     default: return launch_cfg<128, 256, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);

@@ -108,6 +108,12 @@ _add(Workload("small_bf16_ragged", ModelShape(4, 512, 8, 2, 128, 1408, 2048, 1.0
               block_size=16, n_req=3, prefix_range=(40, 200), seg_range=(100, 400)))
 _add(Workload("mistral7b_trunc", replace(_MISTRAL, n_layers=4, vocab=4096), 192, 640, 96, 0, 1, 2, 15,
               note="Mistral-7B widths, 4 layers, triple (0,1,2)"))
+_add(Workload("mistral7b_4k_trunc", replace(_MISTRAL, n_layers=4, vocab=4096), 1024, 4096, 512, 0, 1, 2, 15,
+              note="the headline token counts (1024 new + 4096 reused, k = 614) at Mistral-7B widths, 4 layers, "
+                   "triple (0,1,2): dense, two sparse and one tail layer; the oracle finishes it in about a minute"))
+_add(Workload("mistral7b_pair_trunc", replace(_MISTRAL, n_layers=3, vocab=4096), 0, 0, 0, 0, 1, 2, 15, block_size=16,
+              n_req=2, prefix_range=(256, 1024), seg_range=(1024, 2560),
+              note="two ragged requests, paged with 16-token blocks, Mistral-7B widths, 3 layers"))
 _add(Workload("qwen32b_trunc", replace(_QWEN32, n_layers=3, vocab=4096), 130, 330, 64, 0, 1, 2, 10,
               note="32B widths (group 5), 3 layers"))
 
@@ -177,7 +183,8 @@ def make_influence(w: Workload, n_tokens: int, req: int = 0, seed: int = MASTER_
 
 
 def ragged_lengths(w: Workload, seed: int = MASTER_SEED) -> List[Tuple[int, int, int]]:
-    """(P_i, S_i, alt_i) per request; fixed sizes for single-request workloads."""
+    """(P_i, S_i, alt_i) per request; fixed sizes for single-request workloads.  The earlier agent's prefix is half
+    as long as the new one, and at least one token."""
     if w.n_req == 1 and w.prefix_range == (0, 0):
         return [(w.n_prefix, w.n_seg, w.n_alt)]
     g = stream_rng(w.name, "lengths", -1, seed)
@@ -185,7 +192,7 @@ def ragged_lengths(w: Workload, seed: int = MASTER_SEED) -> List[Tuple[int, int,
     for _ in range(w.n_req):
         p = int(g.integers(w.prefix_range[0], w.prefix_range[1] + 1))
         s = int(g.integers(w.seg_range[0], w.seg_range[1] + 1))
-        out.append((p, s, p // 2))
+        out.append((p, s, max(p // 2, 1)))     # never the same (empty) prefix on both sides: scores would all be 0
     return out
 
 

@@ -25,6 +25,17 @@ def rel_err(got, want) -> float:
     return float(np.max(np.abs(got - want)) / max(np.max(np.abs(want)), 1e-30))
 
 
+def row_rel_err(got, want, floor_frac: float = 0.05) -> float:
+    """Worst row of max|x - y| over a row divided by that row's own max|y|, rows being the vectors along the
+    last axis (one token and head of a cache, one logits vector).  The divisor is at least floor_frac of the
+    tensor's max|y|, so a row that is small against the rest of the tensor is still held to an absolute bound."""
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    err = np.max(np.abs(got - want), axis=-1)
+    ref = np.maximum(np.max(np.abs(want), axis=-1), floor_frac * max(np.max(np.abs(want)), 1e-30))
+    return float(np.max(err / ref))
+
+
 def to_np(t: torch.Tensor) -> np.ndarray:
     return t.detach().float().cpu().numpy()
 
@@ -56,7 +67,9 @@ class Case:
 
 
 def build_case(name: str, k_override: Optional[int] = None, pre_rope: bool = True, n_suffix: int = 0,
-               l_triple=None, max_req: Optional[int] = None) -> Case:
+               l_triple=None, max_req: Optional[int] = None, seed: Optional[int] = None) -> Case:
+    """seed: master seed of the token hidden states, one for all requests or a list with one per request (weights
+    keep the default seed); None = the default."""
     w = WORKLOADS[name]
     if l_triple is not None:
         from dataclasses import replace
@@ -68,10 +81,11 @@ def build_case(name: str, k_override: Optional[int] = None, pre_rope: bool = Tru
     if max_req is not None:
         lens = lens[:max_req]
     for b, (P, S, A) in enumerate(lens):
-        xp = make_hidden(w, "x_prefix", P, b)
-        xa = make_hidden(w, "x_alt", A, b)
-        xs = make_hidden(w, "x_seg", S, b)
-        xsuf = make_hidden(w, "x_suffix", n_suffix, b) if n_suffix else None
+        hs = {} if seed is None else {"seed": seed[b] if isinstance(seed, (list, tuple)) else seed}
+        xp = make_hidden(w, "x_prefix", P, b, **hs)
+        xa = make_hidden(w, "x_alt", A, b, **hs)
+        xs = make_hidden(w, "x_seg", S, b, **hs)
+        xsuf = make_hidden(w, "x_suffix", n_suffix, b, **hs) if n_suffix else None
         seg = R.decode_record(om, xa, xs, w.l_start, k_is_pre_rope=pre_rope)
         dt = w.shape.dtype
         seg = R.SegmentRecord(round_store(seg.k, dt).astype(np.float64), round_store(seg.v, dt).astype(np.float64),
@@ -86,6 +100,37 @@ def oracle_relay(case: Case, b: int = 0, forced_idx=None, thresholds=None, s_inf
     w = case.w
     return R.relay_prefill(case.om, rq.xp, rq.seg, w.l_start, w.l_det, w.l_end, rq.k, x_suffix=rq.xsuf,
                            forced_idx=forced_idx, thresholds=thresholds, s_inf=s_inf)
+
+
+def build_case_with_margin(name: str, margin: float, **kw):
+    """A case whose oracle selection is safe to compare bit for bit across precisions: every request's input seed
+    is bumped until the oracle's k-th and (k+1)-th largest scores of that request are further apart (relatively)
+    than `margin` (requests are independent, so each is bumped on its own; k = 0 and k = S always qualify).
+    Returns (case, [oracle result per request], [seed per request])."""
+    from dataclasses import replace
+    from synth.workloads import MASTER_SEED
+    def safe(case, b, want):
+        kb = case.reqs[b].k
+        # scores that are rounding noise around zero (identical prefixes) have no meaningful ranking
+        real = kb in (0, case.reqs[b].S) or np.sort(want.score)[::-1][kb - 1] > 1e-9
+        return real and selection_margin(want.score, kb) > margin
+
+    case = build_case(name, **kw)
+    n_req = len(case.reqs)
+    seeds = [MASTER_SEED] * n_req
+    reqs = list(case.reqs)
+    wants = [oracle_relay(case, b) for b in range(n_req)]
+    for b in range(n_req):
+        bump = 0
+        while not safe(case, b, wants[b]):
+            bump += 1
+            if bump >= 64:
+                raise AssertionError(f"{name} request {b}: no seed in 64 gives a selection margin above {margin}")
+            seeds[b] = MASTER_SEED + bump
+            case = build_case(name, seed=list(seeds), **kw)
+            wants[b] = oracle_relay(case, b)
+            reqs[b] = case.reqs[b]
+    return replace(case, reqs=reqs), wants, seeds
 
 
 def threshold_margin(score: np.ndarray, tau: float) -> float:

@@ -4,23 +4,23 @@ import pytest
 
 from oracle import relay_oracle as R
 from synth import make_influence
-from tests.harness import (TOL, build_case, hip_full_prefill, hip_relay, oracle_relay, rel_err, selection_margin,
-                           threshold_margin)
+from tests.harness import (TOL, build_case, build_case_with_margin, hip_full_prefill, hip_relay, oracle_relay, rel_err,
+                           selection_margin, threshold_margin)
 
 pytestmark = pytest.mark.gpu
 
-# Index parity is asserted bit-exactly when the oracle's k-th and (k+1)-th scores are further apart
+# Index parity is asserted bit-exactly; for that the oracle's k-th and (k+1)-th scores must be further apart
 # (relatively) than float arithmetic can move them: the float path carries ~3e-4 relative error on a
-# deviation of 1e-5 (hidden states and fresh values are float products of ~256 terms).
+# deviation of 1e-5 (hidden states and fresh values are float products of ~256 terms).  Cases whose default
+# inputs do not have that gap take the next input seed that has it (build_case_with_margin).
 MARGIN = 2e-3
 
 
-def _check_against_oracle(case, run, want_list, tol, check_sel=True):
+def _check_against_oracle(case, run, want_list, tol):
     L = case.w.shape.n_layers
     for b, want in enumerate(want_list):
         T = want.k_cache.shape[1]
-        if check_sel:
-            assert np.array_equal(run.sel[b], want.sel_idx), f"req {b}: selected indices differ"
+        assert np.array_equal(run.sel[b], want.sel_idx), f"req {b}: selected indices differ"
         for l in range(L):
             ek = rel_err(run.k_cache[b][l][:T], want.k_cache[l])
             ev = rel_err(run.v_cache[b][l][:T], want.v_cache[l])
@@ -46,20 +46,16 @@ def test_tiny_f32_matches_oracle_exact_indices():
 
 @pytest.mark.parametrize("k", [0, 1, 203])
 def test_tiny_f32_paged_budgets(k):
-    case = build_case("tiny_f32_paged", k_override=k)
-    want = oracle_relay(case)
+    case, wants, _ = build_case_with_margin("tiny_f32_paged", MARGIN, k_override=k)
     run = hip_relay(case)
-    _check_against_oracle(case, run, [want], TOL["f32"], check_sel=(k in (0, 203)) or
-                          selection_margin(want.score, k) > MARGIN)
+    _check_against_oracle(case, run, wants, TOL["f32"])
 
 
 @pytest.mark.parametrize("pre_rope", [True, False])
 def test_tiny_f32_suffix_and_rotated_keys(pre_rope):
-    case = build_case("tiny_f32_paged", pre_rope=pre_rope, n_suffix=5)
-    want = oracle_relay(case)
+    case, wants, _ = build_case_with_margin("tiny_f32_paged", MARGIN, pre_rope=pre_rope, n_suffix=5)
     run = hip_relay(case)
-    ok = selection_margin(want.score, case.reqs[0].k) > MARGIN
-    _check_against_oracle(case, run, [want], TOL["f32"], check_sel=ok)
+    _check_against_oracle(case, run, wants, TOL["f32"])
 
 
 def test_zero_budget_is_pure_reuse_bit_exact():
@@ -108,12 +104,9 @@ def test_prefill_matches_oracle_full_prefill_f32():
 def test_f32_all_phases_and_edge_shapes(name, k, n_suffix):
     """Five layers with triple (1, 2, 3): layers before l_start, a dense layer, sparse layers and a tail layer
     all exist; plus no prefix at all, a one-token segment, zero and full budgets, with and without a suffix."""
-    case = build_case(name, k_override=k, n_suffix=n_suffix)
-    want = oracle_relay(case)
+    case, wants, _ = build_case_with_margin(name, MARGIN, k_override=k, n_suffix=n_suffix)
     run = hip_relay(case)
-    kk = case.reqs[0].k
-    exact = kk in (0, case.reqs[0].S) or selection_margin(want.score, kk) > MARGIN
-    _check_against_oracle(case, run, [want], TOL["f32"], check_sel=exact)
+    _check_against_oracle(case, run, wants, TOL["f32"])
 
 
 # ------------------------------------------------------------------ the paper's own selector, Eq. (5)-(10)
@@ -165,31 +158,16 @@ def test_bf16_threshold_selector_ragged_batch():
         assert 10 <= len(sel) < r.S
         r.k = len(sel)
         wants.append(oracle_relay(case, b, forced_idx=sel))
-    _check_against_oracle(case, run, wants, TOL["bf16"], check_sel=False)
+    _check_against_oracle(case, run, wants, TOL["bf16"])
 
 
 def test_f32_largest_batch_of_ragged_requests():
     """32 requests in one call (the limit), lengths from 1 token up, some without a new prefix, some whose
     budget rounds down to nothing (pure reuse inside the same batch)."""
-    case = build_case("tiny5_f32_batch32")
+    case, wants, seeds = build_case_with_margin("tiny5_f32_batch32", MARGIN)
     assert len(case.reqs) == 32 and any(r.k == 0 for r in case.reqs) and any(r.k > 0 for r in case.reqs)
-    wants = [oracle_relay(case, b) for b in range(32)]
     run = hip_relay(case)
-    for b, want in enumerate(wants):
-        k = case.reqs[b].k
-        ok = k == 0 or k == case.reqs[b].S or selection_margin(want.score, k) > MARGIN
-        if not ok:                                  # too close to call across precisions: compare on the oracle's rows
-            continue
-        assert np.array_equal(run.sel[b], want.sel_idx), b
-    exact = [b for b, want in enumerate(wants)
-             if case.reqs[b].k in (0, case.reqs[b].S) or selection_margin(want.score, case.reqs[b].k) > MARGIN]
-    assert len(exact) >= 24
-    T = lambda b: wants[b].k_cache.shape[1]
-    for b in exact:
-        for l in range(case.w.shape.n_layers):
-            assert rel_err(run.k_cache[b][l][:T(b)], wants[b].k_cache[l]) <= TOL["f32"], (b, l)
-            assert rel_err(run.v_cache[b][l][:T(b)], wants[b].v_cache[l]) <= TOL["f32"], (b, l)
-        assert rel_err(run.logits[b], wants[b].logits) <= TOL["f32"], b
+    _check_against_oracle(case, run, wants, TOL["f32"])
 
 
 # ------------------------------------------------------------------ bf16 configurations
@@ -272,20 +250,27 @@ def test_multi_segment_prompt_by_chained_calls(name, ends_with_segment):
     model = rc.rc_model_create(sh, weights)
     l_start, l_det, l_end = (1, 2, 3) if sh.n_layers >= 5 else (0, 1, 2)
     sizes = dict(a=37, s1=101, b=20, s2=64, c=0 if ends_with_segment else 9, alt1=29, alt2=50)
-    x = {k: make_hidden(w, "multi_" + k, n) for k, n in sizes.items()}
     up = lambda t: torch.from_numpy(np.ascontiguousarray(t, np.float32)).cuda().to(td).contiguous()
+    bf16 = sh.dtype == "bf16"
 
     def record(alt, seg, pre_rope):
         r = R.decode_record(om, alt, seg, l_start, k_is_pre_rope=pre_rope)
         return R.SegmentRecord(round_store(r.k, sh.dtype).astype(np.float64), round_store(r.v, sh.dtype).astype(np.float64),
                                round_store(r.h_start, sh.dtype).astype(np.float64), pre_rope, alt.shape[0])
 
-    rec1, rec2 = record(x["alt1"], x["s1"], True), record(x["alt2"], x["s2"], False)
     k1, k2 = 15, 9
-    pieces = [("new", x["a"]), ("seg", rec1, k1), ("new", x["b"]), ("seg", rec2, k2)]
-    if not ends_with_segment:
-        pieces.append(("new", x["c"]))
-    want = R.relay_prefill_multi(om, pieces, l_start, l_det, l_end)
+    from synth.workloads import MASTER_SEED
+    for bump in range(64):    # float: the first input seed whose two selections are safe to compare bit for bit
+        x = {k: make_hidden(w, "multi_" + k, n, seed=MASTER_SEED + bump) for k, n in sizes.items()}
+        rec1, rec2 = record(x["alt1"], x["s1"], True), record(x["alt2"], x["s2"], False)
+        pieces = [("new", x["a"]), ("seg", rec1, k1), ("new", x["b"]), ("seg", rec2, k2)]
+        if not ends_with_segment:
+            pieces.append(("new", x["c"]))
+        want = R.relay_prefill_multi(om, pieces, l_start, l_det, l_end)
+        if bf16 or all(selection_margin(want.score[i], (k1, k2)[i]) > MARGIN for i in range(2)):
+            break
+    else:
+        raise AssertionError("no input seed with safe selection margins")
     T = want.k_cache.shape[1]
     # the earlier agents' caches
     src = rc.PagedKV.contiguous(sh.n_layers, 2, max(sizes["alt1"] + sizes["s1"], sizes["alt2"] + sizes["s2"]),
@@ -296,7 +281,6 @@ def test_multi_segment_prompt_by_chained_calls(name, ends_with_segment):
             src.write("v", l, b, up(rec.v[l]), start=rec.old_start_pos)
     dst = rc.PagedKV.contiguous(sh.n_layers, 1, T, sh.n_kv_heads, sh.head_dim, dt, fill=5.0)
     logits = torch.zeros((1, sh.vocab), dtype=torch.float32, device="cuda")
-    bf16 = sh.dtype == "bf16"
     sels = []
     at = 0
     calls = [(x["a"], rec1, 0, k1, None, False), (x["b"], rec2, 1, k2, None if ends_with_segment else x["c"], True)]
@@ -315,8 +299,7 @@ def test_multi_segment_prompt_by_chained_calls(name, ends_with_segment):
         at += xn.shape[0] + S
     tol = TOL[sh.dtype]
     for i in range(2):
-        if not bf16 and selection_margin(want.score[i], (k1, k2)[i]) > MARGIN:
-            assert np.array_equal(sels[i], want.sel_idx[i])
+        assert np.array_equal(sels[i], want.sel_idx[i])       # bf16: forced onto the oracle's rows
     for l in range(sh.n_layers):
         assert rel_err(to_np(dst.read("k", l, 0, T)), want.k_cache[l]) <= tol, l
         assert rel_err(to_np(dst.read("v", l, 0, T)), want.v_cache[l]) <= tol, l

@@ -176,6 +176,41 @@ def test_dense_layer_rows_and_scores_sampled(run):
                 assert rel_err(to_np(run["dst"].read("v", l1, b, 1, start=P + j))[0], v_fresh[0]) <= TOL["bf16"]
 
 
+def test_sparse_layer_attention_of_a_selected_token_sampled(run):
+    """A selected token followed through the first sparse layer by the oracle: its hidden state leaving the dense
+    layer (oracle, from the cached h_start row) enters layer l_det, where the oracle attends with that one query over
+    the library's real layer-l_det cache (thousands of rows, among them the other selected tokens' fresh rows; the
+    library ran this layer with the KV-split plan it picks by itself), finishes the layer and projects the token's
+    K/V rows of layer l_det + 1.  Those must be the rows the library wrote there."""
+    w = run["w"]
+    sh = w.shape
+    l0, l1, l2 = w.l_start, w.l_det, w.l_det + 1
+    assert l1 == l0 + 1 and l2 <= w.l_end
+    lw0, lw1 = _layer_np(run["model"], l0), _layer_np(run["model"], l1)
+    lw2 = {k: v for k, v in _layer_np(run["model"], l2).items() if k in ("g_attn", "wk", "wv")}
+    om1 = _OneLayer(sh, {l1: lw1})
+    for b in run["probe"]:
+        P, S, A = run["lens"][b]
+        sel = run["sel"][b]
+        for j in (int(sel[len(sel) // 3]), int(sel[-1])):
+            pos = P + j
+            h1, _, _, _, _ = _dense_layer_token(run, lw0, b, j)
+            kc = to_np(run["dst"].read("k", l1, b, pos + 1)).astype(np.float64)
+            vc = to_np(run["dst"].read("v", l1, b, pos + 1)).astype(np.float64)
+            h2 = R.decoder_layer(om1, l1, h1, np.array([pos]), kc, vc)
+            a2 = R.rmsnorm(h2, lw2["g_attn"], sh.rms_eps)
+            k_want = R.rope_rotate(R.linear(a2, lw2["wk"]).reshape(1, sh.n_kv_heads, sh.head_dim), np.array([pos]),
+                                   sh.rope_base)[0]
+            v_want = R.linear(a2, lw2["wv"]).reshape(sh.n_kv_heads, sh.head_dim)
+            k_got = to_np(run["dst"].read("k", l2, b, 1, start=pos))[0]
+            v_got = to_np(run["dst"].read("v", l2, b, 1, start=pos))[0]
+            assert rel_err(k_got, k_want) <= TOL["bf16"], (b, j, rel_err(k_got, k_want))
+            assert rel_err(v_got, v_want) <= TOL["bf16"], (b, j, rel_err(v_got, v_want))
+            # and the row differs from what the earlier agent had stored there: it was really recomputed
+            v_old = to_np(run["record"].read("v", l2, b, 1, start=A + j))[0]
+            assert rel_err(v_got, v_old) > 1e-3
+
+
 def test_same_prefix_reproduces_full_prefill_at_full_size(run):
     """If the earlier agent saw the same prefix, the record is already right: scores vanish and the corrected
     cache and logits equal a full prefill of [prefix ; segment] (both computed by the library)."""
