@@ -193,6 +193,10 @@ def main() -> int:
     ap.add_argument("--no-full-prefill", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the stream-copy and MFMA-loop micro-benchmarks")
     ap.add_argument("--seed", type=int, default=20260313)
+    ap.add_argument("--selector", choices=["budget", "threshold"], default="budget",
+                    help="budget: the workload's fixed recompute budget (the headline metric); threshold: the paper's "
+                         "selector, Eq. (5)-(10) with its default cuts (1.5, no influence scores, last 10 tokens); the "
+                         "number of recomputed tokens is then whatever the scores give and is reported under config.k")
     ap.add_argument("--decode-steps", type=int, default=0,
                     help="after the prefill measurement, also time this many decoding steps (one token per request) on "
                          "the corrected cache, with the cache manager's bookkeeping on; reported under \"decode\"")
@@ -250,19 +254,35 @@ def main() -> int:
     dst = cache(new_lens, 2)
     reqs = [rc.Request(x_prefix[b], h_start[b], None, src_seq=b, src_offset=lens[b][2], k_is_pre_rope=True,
                        seg_old_start_pos=lens[b][2], dst_seq=b) for b in range(n_req)]
-    plan = rc.Plan(w.l_start, w.l_det, w.l_end, ks)
+    by_threshold = args.selector == "threshold"
+    sel_cnt = None
+    if by_threshold:
+        plan = rc.Plan(w.l_start, w.l_det, w.l_end, None, None, rc.RC_SELECT_THRESHOLD, 1.5, 1.45, 10)
+        sel = torch.zeros(sum(s_ for _, s_, _ in lens), dtype=torch.int32, device="cuda")
+        sel_cnt = torch.zeros(n_req, dtype=torch.int32, device="cuda")
+    else:
+        plan = rc.Plan(w.l_start, w.l_det, w.l_end, ks)
+        sel = torch.zeros(max(sum(ks), 1), dtype=torch.int32, device="cuda")
     ws = rc.alloc_workspace(rc.rc_reuse_workspace_bytes(model, reqs, plan))
     logits = torch.zeros((n_req, sh.vocab), dtype=torch.float32, device="cuda")
-    sel = torch.zeros(max(sum(ks), 1), dtype=torch.int32, device="cuda")
 
     def step():
-        rc.rc_reuse(model, reqs, plan, record, dst, logits, sel, None, ws)
+        rc.rc_reuse(model, reqs, plan, record, dst, logits, sel, None, ws, sel_cnt=sel_cnt)
 
     if args.counter_pass:
         args.no_cpu_baseline = args.no_full_prefill = args.no_ceilings = True
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if by_threshold:
+        # the selection is data dependent: the counts of the warm-up call (every call selects the same rows) feed the
+        # work accounting below; the selected indices of request b start at the sum of the earlier segments' lengths
+        if args.warmup < 1:
+            step()
+            torch.cuda.synchronize()
+        ks = [int(c) for c in sel_cnt.cpu().numpy()]
+        k = ks[0]
+        args.no_full_prefill = True      # the side measurements below are made for the budget selector only
     if args.counter_pass:
         for _ in range(args.steps):
             step()
@@ -319,10 +339,11 @@ def main() -> int:
     attn_pairs = 0.0
     ko = 0
     for (P_, S_, _), k_ in zip(lens, ks):
+        stride = S_ if by_threshold else k_
         b_rerotate += sh.n_layers * 2 * (2 * S_ * nkv * es)                       # K and V, read + write
         b_score += 2 * S_ * nkv * es + 4 * S_
         sel_pos = P_ + sel_host[ko:ko + k_].astype("float64")
-        ko += k_
+        ko += stride
         pre_pairs = P_ * (P_ + 1) / 2.0
         seg_pairs_all = S_ * P_ + S_ * (S_ + 1) / 2.0
         last_pairs = float(P_ + S_)
@@ -447,7 +468,7 @@ def main() -> int:
                    "k": k if n_req == 1 else ks, "context_tokens": ctx_tokens,
                    "layers": [w.l_start, w.l_det, w.l_end], "n_layers": sh.n_layers, "d_model": sh.d_model,
                    "kv_layout": "contiguous" if w.block_size == 0 else f"paged, {w.block_size}-token blocks, shuffled",
-                   "batch": n_req},
+                   "batch": n_req, "selector": args.selector},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": recorded_gemm_traffic(w.name, gemm_launches),
                      "traffic_source": f"profiles/rc_reuse_{w.name}_l2_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "

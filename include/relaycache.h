@@ -163,8 +163,12 @@ RC_API size_t rc_reuse_workspace_bytes(const rc_model* m, const rc_request* reqs
 
 /* The selective-recompute prefill (Section 4.2, paragraph after Eq. 4; Eq. 1; Figure "Overview", item 3).
  *
- *   src      the earlier agent's cache (read only).  May share pools with dst only if no
- *            destination row overlaps a source row that is still to be read (not checked).
+ *   src      the earlier agent's cache (read only).  It may share pools with dst (a take-over in place) only
+ *            if both have the same block size and every segment moves by a whole number of blocks,
+ *            (n_cached + n_prefix - src_offset) % block_size == 0, so that each row lands on the slot it came
+ *            from; otherwise RC_E_UNSUPPORTED (checked on the host, last of the argument checks).  Whether the
+ *            two block tables then name the same blocks (rows rotated in place) or different ones (a copy
+ *            inside one pool) is up to the caller; partial overlaps of the two are the caller's error.
  *   dst      in/out: on return rows 0..P+S+n_suffix-1 of every layer of sequence dst_seq hold
  *            the corrected cache: new tokens' K/V, re-rotated reused K/V, recomputed rows.
  *   logits   [n_req][vocab] float: logits of the last position of each request.
@@ -172,11 +176,12 @@ RC_API size_t rc_reuse_workspace_bytes(const rc_model* m, const rc_request* reqs
  *            largest deviation at l_det, equal scores resolved to the lower index.
  *            threshold selector: [sum n_seg] int32; request b's selection starts at the sum of the
  *            earlier requests' n_seg, ascending, sel_cnt[b] entries.
- *   sel_cnt  threshold selector: [n_req] int32 (device), number of selected tokens per request;
- *            may be NULL for the budget selector.
- *            The threshold selector's row counts are only known after scoring: the call copies
- *            sel_cnt to the host and waits for the stream once, at l_det, before it enqueues the
- *            remaining layers.
+ *   sel_cnt  threshold selector: [n_req] int32 (device), number of selected tokens per request
+ *            (requests without a segment are left untouched); may be NULL for the budget selector.
+ *            The threshold selector's row counts are only known after scoring, and they stay on the
+ *            device: from l_det on every launch is sized for the bound "all tokens selected" and the
+ *            kernels read the live counts from device memory, so the call enqueues and returns like
+ *            the budget path (it can be captured in a HIP graph); the workspace is sized for the bound.
  *   scores   optional [sum n_seg] float: Eq. (1) at l_det for every segment token of every
  *            request with k > 0 (others untouched); NULL to skip.
  *   With n_suffix == 0 the last segment token is recomputed from l_start to the last layer in
@@ -185,7 +190,8 @@ RC_API size_t rc_reuse_workspace_bytes(const rc_model* m, const rc_request* reqs
  *
  * Errors: RC_E_INVALID_ARG (nulls, triple, k out of range, n_seg == 0 with no new token),
  * RC_E_CAPACITY (n_req > RC_MAX_REQ, sequence longer than max_blocks_per_seq * block_size,
- * seq index out of range), RC_E_UNSUPPORTED (dtype/head_dim), RC_E_WORKSPACE. */
+ * seq index out of range), RC_E_UNSUPPORTED (dtype/head_dim; src and dst sharing pools with a segment
+ * that does not move by whole blocks), RC_E_WORKSPACE. */
 RC_API rc_status rc_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req, const rc_plan* plan,
                    const rc_paged_kv* src, const rc_paged_kv* dst, float* logits, int32_t* sel_idx,
                    int32_t* sel_cnt, float* scores, void* workspace, size_t workspace_bytes, void* stream);
@@ -344,8 +350,10 @@ RC_API rc_status rc_vdev_score(const void* v_fresh, const rc_kv_layer* cache, in
                         int32_t n_tokens, float* score, void* workspace, size_t workspace_bytes,
                         void* stream);
 
-/* Budget selection: indices of the k largest of score[0..n), equal scores to the lower index,
- * written ascending to idx_out[k].  n <= 2^20.  NaN scores order above +inf. */
+/* Budget selection: a fixed recompute budget of k tokens in place of the paper's thresholds (Eq. 5), the way its
+ * budgeted comparison system is configured (Appendix "Baseline Descriptions": a fixed recompute ratio, rounded
+ * down): indices of the k largest of score[0..n), equal scores to the lower index, written ascending to
+ * idx_out[k].  n <= 2^20.  NaN scores order above +inf. */
 RC_API rc_status rc_topk(const float* score, int32_t n, int32_t k, int32_t* idx_out, void* stream);
 
 /* Threshold selection (Eq. 5 / Eq. 7): idx_out receives, ascending, every j with

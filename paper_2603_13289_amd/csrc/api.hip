@@ -129,30 +129,6 @@ rc_status check_kv_layer(const rc_kv_layer* kv) {
 }
 
 // ---------------------------------------------------------------- phases
-// A: layers before l_start; B: dense detect layers; C: sparse rectification; D: after l_end.
-enum Phase : int { PH_A = 0, PH_B = 1, PH_C = 2, PH_D = 3, PH_COUNT = 4 };
-
-struct ReqHost {
-  int P, S, nsuf, k;
-  bool carries_logits;  // no suffix: the last segment token stands in for one
-};
-
-void seg_rows_in(const ReqHost& r, Phase ph, int* mode, int* n) {
-  const int last = (r.carries_logits && r.S > 0) ? 1 : 0;
-  switch (ph) {
-    case PH_A: *mode = SEG_NONE; *n = 0; break;
-    case PH_B:
-      if (r.k > 0) { *mode = SEG_ALL; *n = r.S; }
-      else { *mode = last ? SEG_LAST : SEG_NONE; *n = last; }
-      break;
-    case PH_C:
-      if (r.k > 0) { *mode = SEG_SEL; *n = r.k + last; }
-      else { *mode = last ? SEG_LAST : SEG_NONE; *n = last; }
-      break;
-    default: *mode = last ? SEG_LAST : SEG_NONE; *n = last; break;
-  }
-}
-
 Phase phase_of_layer(int l, int l_start, int l_det, int l_end) {
   if (l < l_start) return PH_A;
   if (l < l_det) return PH_B;
@@ -160,44 +136,15 @@ Phase phase_of_layer(int l, int l_start, int l_det, int l_end) {
   return PH_D;
 }
 
-int total_rows_in(const std::vector<ReqHost>& rq, Phase ph) {
+// rows of a phase for the given static fields (a scratch copy of the table is filled)
+int total_rows_in(const ReqTable& base, Phase ph) {
   long t = 0;
-  for (const ReqHost& r : rq) {
+  for (int b = 0; b < base.n_req; ++b) {
     int mode, n;
-    seg_rows_in(r, ph, &mode, &n);
-    t += r.P + n + r.nsuf;
+    phase_seg_rows(base.r[b], ph, &mode, &n);
+    t += base.r[b].P + n + base.r[b].nsuf;
   }
   return (int)t;
-}
-
-// fills the phase-dependent fields; `prev` is the table of the phase being left (nullptr at the start)
-void fill_phase(ReqTable* t, const std::vector<ReqHost>& rq, Phase ph, const ReqTable* prev, int tile_rows) {
-  int row = 0, tile = 0;
-  for (size_t b = 0; b < rq.size(); ++b) {
-    ReqDev& r = t->r[b];
-    int mode, n;
-    seg_rows_in(rq[b], ph, &mode, &n);
-    r.seg_mode = mode;
-    r.n_seg_rows = n;
-    r.n_rows = rq[b].P + n + rq[b].nsuf;
-    r.row_base = row;
-    r.tile_base = tile;
-    row += r.n_rows;
-    tile += (r.n_rows + tile_rows - 1) / tile_rows;
-    if (prev) {
-      r.has_old = 1;
-      r.old_row_base = prev->r[b].row_base;
-      r.old_n_seg_rows = prev->r[b].n_seg_rows;
-      r.old_seg_mode = prev->r[b].seg_mode;
-    } else {
-      r.has_old = 0;
-      r.old_row_base = 0;
-      r.old_n_seg_rows = 0;
-      r.old_seg_mode = SEG_NONE;
-    }
-  }
-  t->total_rows = row;
-  t->total_tiles = tile;
 }
 
 // ---------------------------------------------------------------- attention KV-split plan of one phase
@@ -219,11 +166,10 @@ int est_row_pos(const ReqDev& r, int i) {
   return r.pos0 + r.P + r.S + (i - r.P - r.n_seg_rows);
 }
 
-AttnSplit plan_phase_split(ReqTable* t, int n_req, int n_kv_heads, int tile_rows, int max_pos) {
-  for (int b = 0; b < n_req; ++b) {
-    t->r[b].long_tile_start = 1 << 30;
-    t->r[b].part_base = 0;
-  }
+// Chooses chunk length and split threshold for a phase from the (estimated) row positions of table t; the
+// per-request slot assignment is left to assign_split_slots.  n_chunks == 1: no split.
+AttnSplit choose_phase_split(const ReqTable* t, int n_kv_heads, int tile_rows, int max_pos) {
+  const int n_req = t->n_req;
   long work = 0;
   int longest = 0;
   for (int b = 0; b < n_req; ++b) {
@@ -257,22 +203,15 @@ AttnSplit plan_phase_split(ReqTable* t, int n_req, int n_kv_heads, int tile_rows
   const int max_tiles = (max_pos + kKvTile - 1) / kKvTile;
   const int n_chunks = (max_tiles + chunk_tiles - 1) / chunk_tiles;
   if (n_chunks <= 1) return attention_no_split();
-  int base = 0;
-  for (int b = 0; b < n_req; ++b) {
-    ReqDev& r = t->r[b];
-    const int tiles = (r.n_rows + tile_rows - 1) / tile_rows;
-    int start = tiles;
-    for (int j = 0; j < tiles; ++j) {
-      const int i_last = std::min((j + 1) * tile_rows, r.n_rows) - 1;
-      // a tile of prefix rows only has exactly known positions; any other tile may reach far
-      if (i_last >= r.P || (r.pos0 + i_last) / kKvTile + 1 > thr) { start = j; break; }
-    }
-    r.long_tile_start = start;
-    r.part_base = base;
-    base += (tiles - start) * n_chunks;
-  }
-  if (base == 0) return attention_no_split();
-  AttnSplit sp = {n_chunks, chunk_tiles, thr, base};
+  AttnSplit sp = {n_chunks, chunk_tiles, thr, 0};
+  return sp;
+}
+
+// the whole plan of a phase whose row counts the host knows: decision, then slots (no capacity limit)
+AttnSplit plan_phase_split(ReqTable* t, int n_kv_heads, int tile_rows, int max_pos) {
+  AttnSplit sp = choose_phase_split(t, n_kv_heads, tile_rows, max_pos);
+  sp.total_slots = assign_split_slots(t, tile_rows, kKvTile, sp.long_thr, sp.n_chunks, 1 << 30);
+  if (sp.total_slots == 0) return attention_no_split();
   return sp;
 }
 
@@ -340,8 +279,7 @@ Workspace carve(void* base, const rc_model_desc& d, int max_rows, int max_pos, i
 // ---------------------------------------------------------------- the layer engine
 struct Job {
   const rc_model* m;
-  std::vector<ReqHost> rq;
-  ReqTable base;                  // static per-request fields
+  ReqTable base;                  // static per-request fields (P, S, nsuf, k, positions, pointers)
   int l_start, l_det, l_end;      // l_start >= n_layers: plain prefill
   const rc_paged_kv* src;
   const rc_paged_kv* dst;
@@ -385,61 +323,92 @@ hipError_t attention_dispatch<bf16>(const bf16* q, const int* row_pos, const int
 
 template <typename T>
 hipError_t gemm_any(const T* a, const T* wt, const T* wt2, void* c, int m, int n, int k, int ldc, GemmEpilogue epi,
-                    float* partial, hipStream_t st);
+                    float* partial, hipStream_t st, const int* m_live = nullptr);
 template <>
 hipError_t gemm_any<float>(const float* a, const float* wt, const float* wt2, void* c, int m, int n, int k, int ldc,
-                           GemmEpilogue epi, float*, hipStream_t st) {
-  return launch_gemm<float>(a, wt, wt2, c, m, n, k, ldc, epi, st);
+                           GemmEpilogue epi, float*, hipStream_t st, const int* m_live) {
+  return launch_gemm<float>(a, wt, wt2, c, m, n, k, ldc, epi, st, m_live);
 }
 template <>
 hipError_t gemm_any<bf16>(const bf16* a, const bf16* wt, const bf16* wt2, void* c, int m, int n, int k, int ldc,
-                          GemmEpilogue epi, float* partial, hipStream_t st) {
-  return launch_gemm_bf16(a, wt, wt2, c, m, n, k, ldc, epi, partial, st);
+                          GemmEpilogue epi, float* partial, hipStream_t st, const int* m_live) {
+  return launch_gemm_bf16(a, wt, wt2, c, m, n, k, ldc, epi, partial, st, m_live);
 }
 template <typename T>
 hipError_t gemm_qkv_any(const T* a, const T* wq, int nq, const T* wk, const T* wv, int nkv, float* c, int m, int k,
-                        float* partial, hipStream_t st);
+                        float* partial, hipStream_t st, const int* m_live);
 template <>
 hipError_t gemm_qkv_any<float>(const float* a, const float* wq, int nq, const float* wk, const float* wv, int nkv,
-                               float* c, int m, int k, float*, hipStream_t st) {
-  return launch_gemm_qkv<float>(a, wq, nq, wk, wv, nkv, c, m, k, st);
+                               float* c, int m, int k, float*, hipStream_t st, const int* m_live) {
+  return launch_gemm_qkv<float>(a, wq, nq, wk, wv, nkv, c, m, k, st, m_live);
 }
 template <>
 hipError_t gemm_qkv_any<bf16>(const bf16* a, const bf16* wq, int nq, const bf16* wk, const bf16* wv, int nkv, float* c,
-                              int m, int k, float* partial, hipStream_t st) {
-  return launch_gemm_qkv_bf16(a, wq, nq, wk, wv, nkv, c, m, k, partial, st);
+                              int m, int k, float* partial, hipStream_t st, const int* m_live) {
+  return launch_gemm_qkv_bf16(a, wq, nq, wk, wv, nkv, c, m, k, partial, st, m_live);
+}
+
+// Partial-attention slots the sparse phase (and the phase after it) may use when the threshold selector decides the
+// row counts on the device: planned for a nominal selection of a fifth of every segment, with room for twice that;
+// a selection that needs more attends unsplit.
+struct ThresholdSplit { AttnSplit sp[PH_COUNT]; int cap[PH_COUNT]; };
+ThresholdSplit plan_threshold_split(const ReqTable& base, int n_kv_heads, int tile_rows, int max_pos, bool bf16_model) {
+  ThresholdSplit ts;
+  for (int p = 0; p < PH_COUNT; ++p) { ts.sp[p] = attention_no_split(); ts.cap[p] = 0; }
+  if (!bf16_model) return ts;
+  for (int p = PH_C; p <= PH_D; ++p) {
+    ReqTable t = base;
+    for (int b = 0; b < t.n_req; ++b)
+      if (t.r[b].k > 0) t.r[b].k = std::max(1, t.r[b].S / 5);
+    fill_phase_table(&t, p, nullptr, tile_rows);
+    AttnSplit sp = choose_phase_split(&t, n_kv_heads, tile_rows, max_pos);
+    if (sp.n_chunks <= 1) continue;
+    for (int b = 0; b < t.n_req; ++b)
+      if (t.r[b].k > 0) t.r[b].k = std::min(t.r[b].S, 2 * t.r[b].k);
+    fill_phase_table(&t, p, nullptr, tile_rows);
+    const int cap = assign_split_slots(&t, tile_rows, kKvTile, sp.long_thr, sp.n_chunks, 1 << 30);
+    if (cap <= 0) continue;
+    sp.total_slots = cap;
+    ts.sp[p] = sp;
+    ts.cap[p] = cap;
+  }
+  return ts;
 }
 
 template <typename T>
 rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
   const rc_model_desc& d = job.m->d;
-  const int n_req = (int)job.rq.size();
+  const int n_req = job.base.n_req;
   const int D = d.d_model, nq = d.n_q_heads * d.head_dim, nkv = d.n_kv_heads * d.head_dim, F = d.d_ffn;
   const int tile_rows = attention_tile_rows(d.dtype, d.n_q_heads, d.n_kv_heads);
   const KvGeom gd = geom_of(*job.dst, d);
   const bool has_seg = job.max_seg > 0;
+  const bool by_threshold = job.selector == RC_SELECT_THRESHOLD;
 
   ReqTable tabs[PH_COUNT];
   AttnSplit splits[PH_COUNT];
+  bool on_device[PH_COUNT] = {false, false, false, false};   // table already written (and finalized) on the device
   for (int p = 0; p < PH_COUNT; ++p) tabs[p] = job.base;
 
   RC_LAUNCH(PC_TABLES, launch_rope_table(w.rope_tab, job.max_pos, d.head_dim / 2, (double)d.rope_base, st));
 
   int cur = -1;   // phase whose rows are live in w.h[hbuf]
   int hbuf = 0;
+  // Row counts of the phase: exact on the host, or (threshold selector, from the sparse phase on) an upper bound
+  // that sizes the grids while the kernels read the live counts from the device table.
+  auto live = [&](int ph) -> const int* { return on_device[ph] ? &(w.tables + ph)->total_rows : nullptr; };
   auto enter_phase = [&](Phase ph) -> rc_status {
-    fill_phase(&tabs[ph], job.rq, ph, cur >= 0 ? &tabs[cur] : nullptr, tile_rows);
-    splits[ph] = d.dtype == RC_BF16 ? plan_phase_split(&tabs[ph], n_req, d.n_kv_heads, tile_rows, job.max_pos)
-                                    : attention_no_split();
-    if (attention_partial_floats(splits[ph].total_slots, d.n_q_heads) > w.attn_part_floats) {
-      // the plan was made for other row counts than the workspace was sized for: attend unsplit
-      for (int b = 0; b < n_req; ++b) {
-        tabs[ph].r[b].long_tile_start = 1 << 30;
-        tabs[ph].r[b].part_base = 0;
+    if (!on_device[ph]) {
+      fill_phase_table(&tabs[ph], ph, cur >= 0 ? &tabs[cur] : nullptr, tile_rows);
+      splits[ph] = d.dtype == RC_BF16 ? plan_phase_split(&tabs[ph], d.n_kv_heads, tile_rows, job.max_pos)
+                                      : attention_no_split();
+      if (attention_partial_floats(splits[ph].total_slots, d.n_q_heads) > w.attn_part_floats) {
+        // the plan was made for other row counts than the workspace was sized for: attend unsplit
+        assign_split_slots(&tabs[ph], tile_rows, kKvTile, 1 << 24, 1, 0);
+        splits[ph] = attention_no_split();
       }
-      splits[ph] = attention_no_split();
+      RC_LAUNCH(PC_TABLES, launch_upload_table(tabs[ph], w.tables + ph, st));
     }
-    RC_LAUNCH(PC_TABLES, launch_upload_table(tabs[ph], w.tables + ph, st));
     const int nb = cur >= 0 ? 1 - hbuf : hbuf;
     RC_LAUNCH(PC_ROWS, launch_build_rows<T>(w.tables + ph, tabs[ph].total_rows, w.h[hbuf], w.h[nb], w.row_pos, w.row_req,
                                 job.sel_idx, D, st));
@@ -475,7 +444,7 @@ rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
     // detection layer: fresh values of every segment token -> Eq. (1) -> selection
     if (ph == PH_C && cur != PH_C) {
       bool any = false;
-      for (const ReqHost& r : job.rq) any = any || r.k > 0;
+      for (int b = 0; b < n_req; ++b) any = any || job.base.r[b].k > 0;
       if (any) {
         const int rows_b = tabs[cur].total_rows;
         RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(w.h[hbuf], (const T*)lw.g_attn, (T*)w.a, rows_b, D, d.rms_eps, st));
@@ -483,28 +452,33 @@ rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
         float* sc = job.scores_out ? job.scores_out : w.scores;
         RC_LAUNCH(PC_SCORE, launch_vdev_score<T>((const T*)w.vfresh, nkv, (const T*)job.dst->v_pool[l], gd, w.tables + cur,
                                     n_req, job.max_seg, sc, st));
-        for (int b = 0; b < n_req; ++b) {
-          const ReqHost& r = job.rq[b];
-          if (r.k <= 0) continue;
-          const int sb = job.base.r[b].sel_base;
-          if (job.selector == RC_SELECT_THRESHOLD)
-            RC_LAUNCH(PC_SELECT, launch_final_select(sc + job.base.r[b].score_base, job.s_inf[b], r.S, job.tau_dev, job.tau_inf,
-                                                     job.k_suf, job.sel_idx + sb, job.sel_cnt + b, st));
-          else if (job.forced_idx) RC_LAUNCH(PC_SELECT, launch_copy_i32(job.forced_idx + sb, job.sel_idx + sb, r.k, st));
-          else RC_LAUNCH(PC_SELECT, launch_topk(sc + job.base.r[b].score_base, r.S, r.k, job.sel_idx + sb, st));
-        }
-        if (job.selector == RC_SELECT_THRESHOLD) {
-          // the number of rows of the sparse layers depends on the scores: fetch the counts, then go on
-          int32_t cnt[RC_MAX_REQ];
-          if (hipMemcpyAsync(cnt, job.sel_cnt, sizeof(int32_t) * n_req, hipMemcpyDeviceToHost, st) != hipSuccess ||
-              hipStreamSynchronize(st) != hipSuccess)
-            return RC_E_HIP;
-          for (int b = 0; b < n_req; ++b) {
-            if (job.rq[b].k <= 0) continue;
-            const int c = std::min(std::max(cnt[b], 0), job.rq[b].S);
-            job.rq[b].k = c;
-            for (int p = PH_C; p < PH_COUNT; ++p) tabs[p].r[b].k = c;
+        // one launch for all requests (the table of the dense phase carries score_base, S, k and sel_base)
+        if (by_threshold) {
+          InfluenceIn inf;
+          for (int b = 0; b < RC_MAX_REQ; ++b) inf.s_inf[b] = b < n_req ? job.s_inf[b] : nullptr;
+          RC_LAUNCH(PC_SELECT, launch_final_select_batch(sc, inf, w.tables + cur, n_req, job.tau_dev, job.tau_inf, job.k_suf,
+                                                         job.sel_idx, job.sel_cnt, st));
+          // The rows of the sparse layers depend on the scores.  The tables of the two remaining phases go to the
+          // device with every token counted as selected (the bound that sizes all grids from here on) and a
+          // one-thread kernel rewrites their counts, row offsets and attention slots from sel_cnt: nothing comes
+          // back to the host, the call stays asynchronous.
+          const ThresholdSplit ts = plan_threshold_split(job.base, d.n_kv_heads, tile_rows, job.max_pos, d.dtype == RC_BF16);
+          int phase_before = cur;
+          for (int p = PH_C; p <= PH_D; ++p) {
+            fill_phase_table(&tabs[p], p, &tabs[phase_before], tile_rows);
+            splits[p] = ts.sp[p];
+            if (attention_partial_floats(splits[p].total_slots, d.n_q_heads) > w.attn_part_floats) splits[p] = attention_no_split();
+            RC_LAUNCH(PC_TABLES, launch_upload_table(tabs[p], w.tables + p, st));
+            on_device[p] = true;
+            phase_before = p;
           }
+          RC_LAUNCH(PC_TABLES, launch_finalize_tables(w.tables, job.sel_cnt, tile_rows, kKvTile, splits[PH_C].long_thr,
+                                                      splits[PH_C].n_chunks, splits[PH_C].total_slots, splits[PH_D].long_thr,
+                                                      splits[PH_D].n_chunks, splits[PH_D].total_slots, st));
+        } else if (job.forced_idx) {
+          RC_LAUNCH(PC_SELECT, launch_copy_sel_batch(job.forced_idx, w.tables + cur, n_req, job.sel_idx, st));
+        } else {
+          RC_LAUNCH(PC_SELECT, launch_topk_batch(sc, w.tables + cur, n_req, job.sel_idx, st));
         }
       }
       RC_TRY(enter_phase(PH_C));
@@ -512,12 +486,13 @@ rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
 
     const int rows = tabs[cur].total_rows;
     if (rows == 0) continue;
+    const int* m_live = live(cur);
     if (l == job.capture_layer) RC_LAUNCH(PC_ROWS, launch_capture_rows<T>(w.tables + cur, rows, w.h[hbuf], w.row_req, D, st));
 
     float* h = w.h[hbuf];
-    RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(h, (const T*)lw.g_attn, (T*)w.a, rows, D, d.rms_eps, st));
+    RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(h, (const T*)lw.g_attn, (T*)w.a, rows, D, d.rms_eps, st, m_live));
     RC_LAUNCH(PC_GEMM_QKV, gemm_qkv_any<T>((const T*)w.a, (const T*)lw.wq, nq, (const T*)lw.wk, (const T*)lw.wv, nkv,
-                                              w.qkv, rows, D, w.gemm_part, st));
+                                              w.qkv, rows, D, w.gemm_part, st, m_live));
     // rotary on q/k at the rows' absolute positions; fresh K/V written into the cache before anyone attends
     RC_LAUNCH(PC_ROPE_SCATTER, launch_rope_scatter<T>(w.qkv, rows, w.row_pos, w.row_req, w.tables + cur, w.rope_tab, (T*)w.q,
                                   (T*)job.dst->k_pool[l], (T*)job.dst->v_pool[l],
@@ -536,10 +511,10 @@ rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
     if (job.any_inf)
       RC_LAUNCH(PC_INFLUENCE, launch_influence_finish(w.row_pos, w.row_req, rows, d.n_q_heads, job.max_pos, job.inf,
                                                       w.inf_scratch, scores_from_attention, st));
-    RC_LAUNCH(PC_GEMM_O, gemm_any<T>((const T*)w.o, (const T*)lw.wo, nullptr, h, rows, D, nq, D, EPI_ADD_F32, w.gemm_part, st));
-    RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(h, (const T*)lw.g_ffn, (T*)w.a, rows, D, d.rms_eps, st));
-    RC_LAUNCH(PC_GEMM_GATE_UP, gemm_any<T>((const T*)w.a, (const T*)lw.w_gate, (const T*)lw.w_up, w.act, rows, F, D, F, EPI_SWIGLU_T, w.gemm_part, st));
-    RC_LAUNCH(PC_GEMM_DOWN, gemm_any<T>((const T*)w.act, (const T*)lw.w_down, nullptr, h, rows, D, F, D, EPI_ADD_F32, w.gemm_part, st));
+    RC_LAUNCH(PC_GEMM_O, gemm_any<T>((const T*)w.o, (const T*)lw.wo, nullptr, h, rows, D, nq, D, EPI_ADD_F32, w.gemm_part, st, m_live));
+    RC_LAUNCH(PC_RMSNORM, launch_rmsnorm<T>(h, (const T*)lw.g_ffn, (T*)w.a, rows, D, d.rms_eps, st, m_live));
+    RC_LAUNCH(PC_GEMM_GATE_UP, gemm_any<T>((const T*)w.a, (const T*)lw.w_gate, (const T*)lw.w_up, w.act, rows, F, D, F, EPI_SWIGLU_T, w.gemm_part, st, m_live));
+    RC_LAUNCH(PC_GEMM_DOWN, gemm_any<T>((const T*)w.act, (const T*)lw.w_down, nullptr, h, rows, D, F, D, EPI_ADD_F32, w.gemm_part, st, m_live));
   }
 
   // first-token logits from the last position of each request
@@ -581,7 +556,6 @@ rc_status prepare_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req
   job->forced_idx = plan->forced_idx;
   job->k_pre_pool = nullptr;
   job->capture_layer = -1;
-  job->rq.clear();
   job->base = ReqTable();
   job->base.n_req = n_req;
   int sel = 0, seg = 0, max_pos = 0, max_seg = 0;
@@ -597,12 +571,9 @@ rc_status prepare_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req
     if (k < 0 || k > q.n_seg) return RC_E_INVALID_ARG;
     job->s_inf[b] = by_threshold ? q.s_inf : nullptr;
     if (q.src_offset < 0 || q.seg_old_start_pos < 0 || q.n_cached < 0) return RC_E_INVALID_ARG;
-    ReqHost h;
-    h.P = q.n_prefix; h.S = q.n_seg; h.nsuf = q.n_suffix; h.k = k;
-    h.carries_logits = q.n_suffix == 0 && !q.no_logits;
-    job->rq.push_back(h);
     ReqDev& r = job->base.r[b];
-    r.P = h.P; r.S = h.S; r.nsuf = h.nsuf; r.k = k;
+    r.P = q.n_prefix; r.S = q.n_seg; r.nsuf = q.n_suffix; r.k = k;
+    r.carries_logits = (q.n_suffix == 0 && !q.no_logits) ? 1 : 0;
     r.pos0 = q.n_cached;
     r.dst_seq = q.dst_seq; r.src_seq = q.src_seq; r.src_offset = q.src_offset;
     r.k_is_pre_rope = q.k_is_pre_rope ? 1 : 0;
@@ -625,25 +596,26 @@ size_t attn_part_need(const Job& job) {
   if (d.dtype != RC_BF16) return 0;
   const int tile_rows = attention_tile_rows(d.dtype, d.n_q_heads, d.n_kv_heads);
   size_t need = 0;
-  ReqTable t = job.base;
-  std::vector<ReqHost> rq = job.rq;
-  // threshold selector: the sparse phase's row count is not known yet; size for a ladder of counts
-  // (a plan that still does not fit falls back to unsplit attention when the layers run)
-  const int rungs = job.selector == RC_SELECT_THRESHOLD ? 8 : 1;
-  for (int rung = 0; rung < rungs; ++rung) {
-    for (int p = 0; p < PH_COUNT; ++p) {
-      fill_phase(&t, rq, (Phase)p, nullptr, tile_rows);
-      const AttnSplit sp = plan_phase_split(&t, (int)rq.size(), d.n_kv_heads, tile_rows, job.max_pos);
-      need = std::max(need, attention_partial_floats(sp.total_slots, d.n_q_heads));
+  const bool by_threshold = job.selector == RC_SELECT_THRESHOLD;
+  // threshold selector: the row counts of the sparse phase and the one after it are decided on the device
+  ThresholdSplit ts{};
+  if (by_threshold) ts = plan_threshold_split(job.base, d.n_kv_heads, tile_rows, job.max_pos, true);
+  for (int p = 0; p < PH_COUNT; ++p) {
+    if (by_threshold && p >= PH_C) {
+      need = std::max(need, attention_partial_floats(ts.cap[p], d.n_q_heads));
+      continue;
     }
-    for (ReqHost& r : rq) r.k = std::max(r.k / 2, r.k > 0 ? 1 : 0);
+    ReqTable t = job.base;
+    fill_phase_table(&t, p, nullptr, tile_rows);
+    const AttnSplit sp = plan_phase_split(&t, d.n_kv_heads, tile_rows, job.max_pos);
+    need = std::max(need, attention_partial_floats(sp.total_slots, d.n_q_heads));
   }
   return need;
 }
 
 int max_rows_of(const Job& job) {
   int r = 0;
-  for (int p = 0; p < PH_COUNT; ++p) r = std::max(r, total_rows_in(job.rq, (Phase)p));
+  for (int p = 0; p < PH_COUNT; ++p) r = std::max(r, total_rows_in(job.base, (Phase)p));
   return r;
 }
 
@@ -751,7 +723,7 @@ rc_status rc_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req, con
   RC_TRY(check_paged(dst, m->d.n_layers));
   if (!logits) return RC_E_INVALID_ARG;
   int sum_k = 0;
-  for (const ReqHost& r : job.rq) sum_k += r.k;
+  for (int b = 0; b < n_req; ++b) sum_k += job.base.r[b].k;
   if (sum_k > 0 && !sel_idx) return RC_E_INVALID_ARG;
   if (sum_k > 0 && job.selector == RC_SELECT_THRESHOLD && !sel_cnt) return RC_E_INVALID_ARG;
   if (job.max_seg > 0) RC_TRY(check_paged(src, m->d.n_layers));
@@ -762,6 +734,21 @@ rc_status rc_reuse(const rc_model* m, const rc_request* reqs, int32_t n_req, con
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RC_E_WORKSPACE;
   Workspace w = carve(workspace, m->d, max_rows_of(job), job.max_pos, n_req, job.sum_seg, attn_part_need(job));
   if (w.bytes > workspace_bytes) return RC_E_WORKSPACE;
+  // Source and destination in the same pools: the take-over reads a segment row and writes it at its new position.
+  // That is only safe when every row lands on the slot it came from (same block size, segment moved by a whole
+  // number of blocks; whether the blocks themselves coincide is the caller's block tables' business).
+  if (job.max_seg > 0) {
+    bool shared = false;
+    for (int l = 0; l < m->d.n_layers; ++l)
+      shared = shared || src->k_pool[l] == dst->k_pool[l] || src->v_pool[l] == dst->v_pool[l] ||
+               src->k_pool[l] == dst->v_pool[l] || src->v_pool[l] == dst->k_pool[l];
+    if (shared) {
+      if (src->block_size != dst->block_size) return RC_E_UNSUPPORTED;
+      for (int b = 0; b < n_req; ++b)
+        if (reqs[b].n_seg > 0 && (reqs[b].n_cached + reqs[b].n_prefix - reqs[b].src_offset) % dst->block_size != 0)
+          return RC_E_UNSUPPORTED;
+    }
+  }
   job.src = src;
   job.dst = dst;
   job.logits = logits;
@@ -781,22 +768,18 @@ static rc_status prepare_prefill(const rc_model* m, const void* const* x, const 
   job->l_start = job->l_det = job->l_end = m->d.n_layers;   // every layer is a "before l_start" layer
   job->forced_idx = nullptr;
   job->selector = RC_SELECT_BUDGET;
-  job->rq.clear();
   job->base = ReqTable();
   job->base.n_req = n_req;
   int max_pos = 0;
   for (int b = 0; b < n_req; ++b) {
     if (n_tokens[b] < 1) return RC_E_INVALID_ARG;
     if (x && !x[b]) return RC_E_INVALID_ARG;
-    ReqHost h;
-    h.P = n_tokens[b]; h.S = 0; h.nsuf = 0; h.k = 0; h.carries_logits = false;
-    job->rq.push_back(h);
     ReqDev& r = job->base.r[b];
-    r.P = h.P;
+    r.P = n_tokens[b];
     r.dst_seq = dst_seq ? dst_seq[b] : 0;
     r.x_prefix = x ? x[b] : nullptr;
     r.h_capture = h_capture ? h_capture[b] : nullptr;
-    max_pos = std::max(max_pos, h.P);
+    max_pos = std::max(max_pos, r.P);
   }
   job->max_pos = max_pos;
   job->sum_seg = 0;
@@ -847,7 +830,6 @@ static rc_status prepare_decode(const rc_model* m, const rc_decode_req* reqs, in
   job->selector = RC_SELECT_BUDGET;
   job->takeover = false;
   job->any_inf = false;
-  job->rq.clear();
   job->base = ReqTable();
   job->base.n_req = n_req;
   int max_pos = 0, max_seg = 0;
@@ -856,9 +838,6 @@ static rc_status prepare_decode(const rc_model* m, const rc_decode_req* reqs, in
     if (!q.x || q.pos < 0) return RC_E_INVALID_ARG;
     // the cached rows 0..pos-1 play the part of a reused segment that is already in place; the new token
     // is the one-row suffix behind it
-    ReqHost h;
-    h.P = 0; h.S = q.pos; h.nsuf = 1; h.k = 0; h.carries_logits = false;
-    job->rq.push_back(h);
     ReqDev& r = job->base.r[b];
     r.P = 0; r.S = q.pos; r.nsuf = 1; r.k = 0;
     r.dst_seq = q.seq; r.src_seq = q.seq;
@@ -877,7 +856,7 @@ static rc_status prepare_decode(const rc_model* m, const rc_decode_req* reqs, in
 }
 
 static size_t decode_inf_floats(const Job& job) {
-  return job.any_inf ? influence_scratch_floats((int)job.rq.size(), job.m->d.n_q_heads, job.max_pos) : 0;
+  return job.any_inf ? influence_scratch_floats(job.base.n_req, job.m->d.n_q_heads, job.max_pos) : 0;
 }
 
 size_t rc_decode_workspace_bytes(const rc_model* m, const rc_decode_req* reqs, int32_t n_req) {

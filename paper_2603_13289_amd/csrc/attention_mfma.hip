@@ -78,7 +78,12 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   // grid (a longest-first schedule), and with 8 KV heads every XCD (workgroup id mod 8) keeps to one head's K/V.
   const int kvh = (int)blockIdx.x % g.n_kv_heads;
   const int item = (int)blockIdx.x / g.n_kv_heads;
+  if (table) {   // the host's counts may be upper bounds (rows selected on the device): the table has the live ones
+    total_tiles = table->total_tiles;
+    total_rows = table->total_rows;
+  }
   const int tile = total_tiles - 1 - item / sp.n_chunks;
+  if (tile < 0) return;
   const int chunk = item % sp.n_chunks;
   const int n_q_heads = g.n_kv_heads * G;
   int r0, n_valid, seq, split_tile = tile, part_base = 0;   // split_tile < 0: this tile is never split
@@ -395,11 +400,12 @@ attn_merge_kernel(const int* __restrict__ row_pos, const int* __restrict__ row_r
                   const float2* __restrict__ part_ml, bf16* __restrict__ out, float2* __restrict__ score_ml) {
   const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
+  if (table) total_rows = table->total_rows;
   if (item >= total_rows * n_q_heads) return;
   const int r = item / n_q_heads, head = item - r * n_q_heads;
   int split_tile, ql, part_base = 0, tile_last_row;
   if (table) {
-    const ReqDev& rq = table->r[row_req[r]];
+    const ReqDev& rq = table->r[row_req[r] & kRowReqMask];
     const int lt = (r - rq.row_base) / BQ;
     split_tile = lt - rq.long_tile_start;
     ql = (r - rq.row_base) % BQ;

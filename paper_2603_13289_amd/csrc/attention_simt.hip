@@ -15,10 +15,11 @@ attn_simt_kernel(const T* __restrict__ q, const int* __restrict__ row_pos, const
   __shared__ float p_s[64];
   const int lane = threadIdx.x;
   const int r = blockIdx.x / n_q_heads, hq = blockIdx.x - r * n_q_heads;
+  if (table && r >= table->total_rows) return;   // the grid may be sized for an upper bound of the row count
   const int kvh = hq / (n_q_heads / g.n_kv_heads);
   const int dh = g.head_dim;
   const int pos = row_pos[r];
-  const int seq = table ? table->r[row_req[r]].dst_seq : fixed_seq;
+  const int seq = table ? table->r[row_req[r] & kRowReqMask].dst_seq : fixed_seq;
   const T* qrow = q + ((size_t)r * n_q_heads + hq) * dh;
   for (int c = lane; c < dh; c += 64) q_s[c] = to_f32(qrow[c]);
   __syncthreads();

@@ -119,7 +119,8 @@ enum SegMode : int { SEG_NONE = 0, SEG_ALL = 1, SEG_SEL = 2, SEG_LAST = 3 };
 
 struct ReqDev {
   int P, S, nsuf, k;
-  int pos0, pad0;   // position of the request's first row (rows 0..pos0-1 of the sequence are already final)
+  int pos0;             // position of the request's first row (rows 0..pos0-1 of the sequence are already final)
+  int carries_logits;   // 1: no suffix, so the last segment token stays live to the end and yields the logits
   int row_base, n_seg_rows, n_rows, seg_mode;           // current phase
   int old_row_base, old_n_seg_rows, old_seg_mode, has_old;  // phase being left (has_old = 0: inputs)
   int dst_seq, src_seq, src_offset, rot_delta;           // rot_delta valid when keys are rotated
@@ -131,10 +132,97 @@ struct ReqDev {
   void* h_capture;
 };
 
+// row_req[r] holds the row's request index in its low bits and, for the one live row per request that is a second
+// copy of a selected token (the logits-carrying last segment token when the selection already contains it), the
+// flag below: such a row runs through the layers like any other but leaves the cache writes to its twin, so that
+// the cache row has exactly one writer and the result does not depend on which of two bit-different sums lands last.
+constexpr int kRowReqMask = 0xff;
+constexpr int kRowNoCacheWrite = 0x100;
+static_assert(RC_MAX_REQ <= kRowReqMask + 1, "request index must fit the mask");
+
 struct ReqTable {
   int n_req, total_rows, total_tiles, pad;
   ReqDev r[RC_MAX_REQ];
 };
+
+// ------------------------------------------------------------------ phases of a call
+// A: layers before l_start (new tokens only); B: dense detect layers [l_start, l_det) (all segment rows);
+// C: sparse rectification [l_det, l_end] (selected rows); D: layers after l_end.
+enum Phase : int { PH_A = 0, PH_B = 1, PH_C = 2, PH_D = 3, PH_COUNT = 4 };
+
+// which segment rows of a request are live in a phase, and how many
+__host__ __device__ inline void phase_seg_rows(const ReqDev& r, int ph, int* mode, int* n) {
+  const int last = (r.carries_logits && r.S > 0) ? 1 : 0;
+  if (ph == PH_B && r.k > 0) { *mode = SEG_ALL; *n = r.S; }
+  else if (ph == PH_C && r.k > 0) { *mode = SEG_SEL; *n = r.k + last; }
+  else if (ph == PH_A) { *mode = SEG_NONE; *n = 0; }
+  else { *mode = last ? SEG_LAST : SEG_NONE; *n = last; }
+}
+
+// Fills the phase-dependent fields of a table whose static fields (P, S, nsuf, k, ...) are in place; `prev` is
+// the table of the phase being left (nullptr at the start of a call).  Runs on the host when the row counts are
+// known there, and on the device when they depend on a selection made on the device.
+__host__ __device__ inline void fill_phase_table(ReqTable* t, int ph, const ReqTable* prev, int tile_rows) {
+  int row = 0, tile = 0;
+  for (int b = 0; b < t->n_req; ++b) {
+    ReqDev& r = t->r[b];
+    int mode, n;
+    phase_seg_rows(r, ph, &mode, &n);
+    r.seg_mode = mode;
+    r.n_seg_rows = n;
+    r.n_rows = r.P + n + r.nsuf;
+    r.row_base = row;
+    r.tile_base = tile;
+    row += r.n_rows;
+    tile += (r.n_rows + tile_rows - 1) / tile_rows;
+    if (prev) {
+      r.has_old = 1;
+      r.old_row_base = prev->r[b].row_base;
+      r.old_n_seg_rows = prev->r[b].n_seg_rows;
+      r.old_seg_mode = prev->r[b].seg_mode;
+    } else {
+      r.has_old = 0;
+      r.old_row_base = 0;
+      r.old_n_seg_rows = 0;
+      r.old_seg_mode = SEG_NONE;
+    }
+  }
+  t->total_rows = row;
+  t->total_tiles = tile;
+}
+
+// Attention KV split of one phase, per-request part: the first query tile of each request that may be split
+// (a tile of new-prefix rows only has exactly known, short ranges and stays whole) and the request's base in the
+// array of partial-result slots.  Returns the slots the phase needs; with more than `capacity` slots the split
+// is switched off for the phase (every tile is then done by one workgroup) and 0 is returned.
+__host__ __device__ inline int assign_split_slots(ReqTable* t, int tile_rows, int kv_tile, int long_thr, int n_chunks,
+                                                  int capacity) {
+  int base = 0;
+  for (int b = 0; b < t->n_req; ++b) {
+    ReqDev& r = t->r[b];
+    const int tiles = (r.n_rows + tile_rows - 1) / tile_rows;
+    int start = tiles;
+    for (int j = 0; j < tiles; ++j) {
+      const int i_last = ((j + 1) * tile_rows < r.n_rows ? (j + 1) * tile_rows : r.n_rows) - 1;
+      if (i_last >= r.P || (r.pos0 + i_last) / kv_tile + 1 > long_thr) { start = j; break; }
+    }
+    r.long_tile_start = start;
+    r.part_base = base;
+    base += (tiles - start) * n_chunks;
+  }
+  if (n_chunks <= 1 || base == 0 || base > capacity) {
+    for (int b = 0; b < t->n_req; ++b) {
+      t->r[b].long_tile_start = 1 << 30;
+      t->r[b].part_base = 0;
+    }
+    return 0;
+  }
+  return base;
+}
+
+// Row count of a launch: the host's figure, or, when the count is only known on the device (rows selected by a
+// threshold), the device value, of which the host's figure is an upper bound that sized the grid.
+__device__ inline int live_count(int bound, const int* live) { return live ? min(bound, *live) : bound; }
 
 // ------------------------------------------------------------------ launchers (host)
 // Every launcher enqueues on `st` and returns hipGetLastError().
@@ -162,32 +250,37 @@ template <typename T>
 hipError_t launch_capture_rows(const ReqTable* table, int total_rows, const float* h, const int* row_req,
                                int d, hipStream_t st);
 
+// m_live (optional, device): the live row count when `rows` is only an upper bound
 template <typename T>
-hipError_t launch_rmsnorm(const float* h, const T* gain, T* out, int rows, int d, float eps, hipStream_t st);
+hipError_t launch_rmsnorm(const float* h, const T* gain, T* out, int rows, int d, float eps, hipStream_t st,
+                          const int* m_live = nullptr);
 
 enum GemmEpilogue : int { EPI_STORE_F32 = 0, EPI_STORE_T = 1, EPI_ADD_F32 = 2, EPI_SWIGLU_T = 3 };
 // C[M][ldc] (op)= A[M][K] * W[N][K]^T ; W2 only for EPI_SWIGLU_T (gate = W, up = W2)
+// m_live (optional, device): the live row count when m is only an upper bound (rows selected on the device);
+// the launch then covers m rows' worth of tiles and workgroups past the live rows leave at once
 template <typename T>
 hipError_t launch_gemm(const T* a, const T* w, const T* w2, void* c, int m, int n, int k, int ldc,
-                       GemmEpilogue epi, hipStream_t st);
+                       GemmEpilogue epi, hipStream_t st, const int* m_live = nullptr);
 
 // few-row variant (M <= 32, weights streamed once); columns < ns1 come from w, < ns2 from w2, the rest from w3
 bool gemm_skinny_applies(int m, int n, int k, int ns1, int ns2);
 hipError_t launch_gemm_skinny_bf16(const bf16* a, const bf16* w, const bf16* w2, const bf16* w3, int ns1, int ns2,
-                                   void* c, int m, int n, int k, int ldc, GemmEpilogue epi, hipStream_t st);
+                                   void* c, int m, int n, int k, int ldc, GemmEpilogue epi, hipStream_t st,
+                                   const int* m_live = nullptr);
 
 // C[M][nq + 2 nkv] (float) = A * [wq; wk; wv]^T
 template <typename T>
 hipError_t launch_gemm_qkv(const T* a, const T* wq, int nq, const T* wk, const T* wv, int nkv, float* c, int m,
-                           int k, hipStream_t st);
+                           int k, hipStream_t st, const int* m_live = nullptr);
 
 // bf16 GEMMs with a scratch buffer (gemm_partial_bytes()) for the K-split tail of the tile schedule;
 // partial == nullptr: every tile is done by one workgroup.
 size_t gemm_partial_bytes();
 hipError_t launch_gemm_bf16(const bf16* a, const bf16* w, const bf16* w2, void* c, int m, int n, int k, int ldc,
-                            GemmEpilogue epi, float* partial, hipStream_t st);
+                            GemmEpilogue epi, float* partial, hipStream_t st, const int* m_live = nullptr);
 hipError_t launch_gemm_qkv_bf16(const bf16* a, const bf16* wq, int nq, const bf16* wk, const bf16* wv, int nkv, float* c,
-                                int m, int k, float* partial, hipStream_t st);
+                                int m, int k, float* partial, hipStream_t st, const int* m_live = nullptr);
 void set_gemm_xcd_remap(int on);
 int check_grid_plan(int m, int n, int k, bool dual, int tile, int n_cus, bool with_partial, int* n_blocks_out);
 void set_gemm_thin_tiles(int on);   // 1: a ragged last tile row of at most 64 rows goes to the thin tile body
@@ -231,6 +324,20 @@ hipError_t launch_vdev_score(const T* v_fresh, int fresh_row_stride, const T* v_
                              const ReqTable* table, int n_req, int max_seg, float* scores, hipStream_t st);
 
 hipError_t launch_topk(const float* score, int n, int k, int* idx_out, hipStream_t st);
+// All requests of a call in one launch (one workgroup per request, read from the table: scores at score_base,
+// S of them, output at sel_base).  Budget: the r.k largest.  Threshold: Eq. (5)-(10) with the requests' influence
+// vectors (nullptr: none), counts to sel_cnt[b].  Requests with k <= 0 are skipped.
+struct InfluenceIn { const float* s_inf[RC_MAX_REQ]; };
+hipError_t launch_topk_batch(const float* scores, const ReqTable* table, int n_req, int* sel_idx, hipStream_t st);
+hipError_t launch_final_select_batch(const float* scores, const InfluenceIn& inf, const ReqTable* table, int n_req,
+                                     float tau_dev, float tau_inf, int k_suf, int* sel_idx, int* sel_cnt,
+                                     hipStream_t st);
+hipError_t launch_copy_sel_batch(const int* forced, const ReqTable* table, int n_req, int* sel_idx, hipStream_t st);
+// Threshold selector: turns the device-side counts into the tables of the sparse phase and the phase after it
+// (tabs[PH_C], tabs[PH_D], uploaded with their static fields and k = S), so that no count has to travel to the host.
+struct AttnSplit;
+hipError_t launch_finalize_tables(ReqTable* tabs, const int* sel_cnt, int tile_rows, int kv_tile, int thr_c,
+                                  int chunks_c, int cap_c, int thr_d, int chunks_d, int cap_d, hipStream_t st);
 hipError_t launch_threshold_select(const float* score, int n, float tau, int* idx_out, int* count_out,
                                    hipStream_t st);
 // per-request influence vectors (Eq. 6), passed to the accumulation kernel by value; nullptr: not tracked

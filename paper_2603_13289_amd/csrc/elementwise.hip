@@ -20,6 +20,34 @@ hipError_t launch_upload_table(const ReqTable& host_table, ReqTable* dev_slot, h
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ threshold selector: tables from device counts
+// One thread (a few dozen requests at most).  tabs[PH_C] and tabs[PH_D] arrive with their static fields and with
+// every token counted as selected; the counts the selector left in sel_cnt replace that, and everything that
+// depends on them (row counts, row and tile offsets, links to the phase before, attention slots) is recomputed
+// with the same functions the host uses when it knows the counts.
+__global__ void finalize_tables_kernel(ReqTable* tabs, const int* __restrict__ sel_cnt, int tile_rows, int kv_tile,
+                                       int thr_c, int chunks_c, int cap_c, int thr_d, int chunks_d, int cap_d) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  ReqTable* c = tabs + PH_C;
+  ReqTable* dd = tabs + PH_D;
+  for (int b = 0; b < c->n_req; ++b) {
+    if (c->r[b].k <= 0) continue;            // a request without a segment takes no part in the selection
+    const int k = min(max(sel_cnt[b], 0), c->r[b].S);
+    c->r[b].k = k;
+    dd->r[b].k = k;
+  }
+  fill_phase_table(c, PH_C, tabs + PH_B, tile_rows);
+  assign_split_slots(c, tile_rows, kv_tile, thr_c, chunks_c, cap_c);
+  fill_phase_table(dd, PH_D, c, tile_rows);
+  assign_split_slots(dd, tile_rows, kv_tile, thr_d, chunks_d, cap_d);
+}
+
+hipError_t launch_finalize_tables(ReqTable* tabs, const int* sel_cnt, int tile_rows, int kv_tile, int thr_c,
+                                  int chunks_c, int cap_c, int thr_d, int chunks_d, int cap_d, hipStream_t st) {
+  finalize_tables_kernel<<<1, 64, 0, st>>>(tabs, sel_cnt, tile_rows, kv_tile, thr_c, chunks_c, cap_c, thr_d, chunks_d, cap_d);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ rotary tables
 // tab[pos][i] = (cos, sin)(pos * base^(-2i/dh)), evaluated in double so that positions in the tens
 // of thousands keep full float accuracy.
@@ -125,11 +153,12 @@ __global__ void __launch_bounds__(kThreads)
 build_rows_kernel(const ReqTable* __restrict__ table, const float* __restrict__ h_old, float* __restrict__ h_new,
                   int* __restrict__ row_pos, int* __restrict__ row_req, const int* __restrict__ sel_idx, int d) {
   const int r = blockIdx.x;
+  if (r >= table->total_rows) return;   // the grid may be sized for an upper bound of the row count
   int b = 0;
   while (b + 1 < table->n_req && r >= table->r[b].row_base + table->r[b].n_rows) ++b;
   const ReqDev& rq = table->r[b];
   const int i = r - rq.row_base;
-  int pos;
+  int pos, flags = 0;
   const T* src_t = nullptr;      // input tensor row (T)
   const float* src_f = nullptr;  // row of the previous phase's buffer
   if (i < rq.P) {
@@ -140,8 +169,11 @@ build_rows_kernel(const ReqTable* __restrict__ table, const float* __restrict__ 
     const int si = i - rq.P;
     int j;
     if (rq.seg_mode == SEG_ALL) j = si;
-    else if (rq.seg_mode == SEG_SEL) j = (si < rq.k) ? sel_idx[rq.sel_base + si] : rq.S - 1;
-    else j = rq.S - 1;
+    else if (rq.seg_mode == SEG_SEL) {
+      j = (si < rq.k) ? sel_idx[rq.sel_base + si] : rq.S - 1;
+      // the extra row of the last token, when the (ascending) selection ends with that token as well
+      if (si >= rq.k && rq.k > 0 && sel_idx[rq.sel_base + rq.k - 1] == rq.S - 1) flags = kRowNoCacheWrite;
+    } else j = rq.S - 1;
     j = min(max(j, 0), rq.S - 1);
     pos = rq.pos0 + rq.P + j;
     if (rq.old_seg_mode == SEG_ALL) src_f = h_old + (size_t)(rq.old_row_base + rq.P + j) * d;
@@ -156,7 +188,7 @@ build_rows_kernel(const ReqTable* __restrict__ table, const float* __restrict__ 
   }
   if (threadIdx.x == 0) {
     row_pos[r] = pos;
-    row_req[r] = b;
+    row_req[r] = b | flags;
   }
   float* dst = h_new + (size_t)r * d;
   if (src_f) {
@@ -185,7 +217,8 @@ __global__ void __launch_bounds__(kThreads)
 capture_rows_kernel(const ReqTable* __restrict__ table, const float* __restrict__ h,
                     const int* __restrict__ row_req, int d) {
   const int r = blockIdx.x;
-  const ReqDev& rq = table->r[row_req[r]];
+  if (r >= table->total_rows) return;
+  const ReqDev& rq = table->r[row_req[r] & kRowReqMask];
   if (rq.h_capture == nullptr) return;
   T* dst = reinterpret_cast<T*>(rq.h_capture) + (size_t)(r - rq.row_base) * d;
   const float* src = h + (size_t)r * d;
@@ -239,8 +272,10 @@ __device__ inline void load4(const bf16* p, float* v) {
 constexpr int kNormKeep = 8;
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
-rmsnorm_kernel(const float* __restrict__ h, const T* __restrict__ gain, T* __restrict__ out, int d, float eps) {
+rmsnorm_kernel(const float* __restrict__ h, const T* __restrict__ gain, T* __restrict__ out, int d, float eps,
+               const int* __restrict__ m_live) {
   __shared__ float red[kThreads / 64];
+  if (m_live && (int)blockIdx.x >= *m_live) return;
   const float* x = h + (size_t)blockIdx.x * d;
   float4 keep[kNormKeep];
   float ss = 0.f;
@@ -279,13 +314,14 @@ rmsnorm_kernel(const float* __restrict__ h, const T* __restrict__ gain, T* __res
 }
 
 template <typename T>
-hipError_t launch_rmsnorm(const float* h, const T* gain, T* out, int rows, int d, float eps, hipStream_t st) {
+hipError_t launch_rmsnorm(const float* h, const T* gain, T* out, int rows, int d, float eps, hipStream_t st,
+                          const int* m_live) {
   if (rows <= 0) return hipSuccess;
-  rmsnorm_kernel<T><<<rows, kThreads, 0, st>>>(h, gain, out, d, eps);
+  rmsnorm_kernel<T><<<rows, kThreads, 0, st>>>(h, gain, out, d, eps, m_live);
   return hipGetLastError();
 }
-template hipError_t launch_rmsnorm<float>(const float*, const float*, float*, int, int, float, hipStream_t);
-template hipError_t launch_rmsnorm<bf16>(const float*, const bf16*, bf16*, int, int, float, hipStream_t);
+template hipError_t launch_rmsnorm<float>(const float*, const float*, float*, int, int, float, hipStream_t, const int*);
+template hipError_t launch_rmsnorm<bf16>(const float*, const bf16*, bf16*, int, int, float, hipStream_t, const int*);
 
 // ------------------------------------------------------------------ rotary on fresh q/k + K7: paged scatter
 // One workgroup per live row.  qkv is the float output of the three projections laid out
@@ -298,8 +334,10 @@ rope_scatter_kernel(const float* __restrict__ qkv, const int* __restrict__ row_p
                     T* __restrict__ k_pool, T* __restrict__ v_pool, T* __restrict__ k_pre_pool, KvGeom g,
                     int n_q_heads) {
   const int r = blockIdx.x;
+  if (r >= table->total_rows) return;
   const int pos = row_pos[r];
-  const int seq = table->r[row_req[r]].dst_seq;
+  const int seq = table->r[row_req[r] & kRowReqMask].dst_seq;
+  const bool write_cache = (row_req[r] & kRowNoCacheWrite) == 0;
   const int dh = g.head_dim, half = dh / 2, quads = half / 4;
   const int nq = n_q_heads * dh, nkv = g.n_kv_heads * dh;
   const float* row = qkv + (size_t)r * (nq + 2 * nkv);
@@ -327,7 +365,7 @@ rope_scatter_kernel(const float* __restrict__ qkv, const int* __restrict__ row_p
         T* o = q_out + (size_t)r * nq + head * dh;
         store4(o + i, lo);
         store4(o + half + i, hi);
-      } else {
+      } else if (write_cache) {
         // rotated into the cache (and optionally un-rotated into the pre-RoPE pool)
         const size_t off = kv_row_offset(g, seq, pos, head - n_q_heads);
         store4(k_pool + off + i, lo);
@@ -337,7 +375,7 @@ rope_scatter_kernel(const float* __restrict__ qkv, const int* __restrict__ row_p
           store4(k_pre_pool + off + half + i, b);
         }
       }
-    } else {
+    } else if (write_cache) {
       const int vi = item - n_rot;
       const int head = vi / (dh / 4), i = (vi - head * (dh / 4)) * 4;
       const float4 v4 = *reinterpret_cast<const float4*>(row + nq + nkv + head * dh + i);

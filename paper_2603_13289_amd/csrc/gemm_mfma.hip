@@ -98,7 +98,7 @@ __device__ __host__ inline void tile_of(TileOrder o, int logical, int* tile_m, i
   *tile_n = r / h;
 }
 
-static inline TileOrder make_tile_order(int tiles_m, int tiles_n) {
+__device__ __host__ inline TileOrder make_tile_order(int tiles_m, int tiles_n) {
   TileOrder o = {tiles_m, tiles_n, (tiles_m + 5) / 6};
   if (o.bands < 1) o.bands = 1;
   return o;
@@ -108,7 +108,7 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, bool DUAL, int OCC>
 __global__ void __launch_bounds__(WAVES_M * WAVES_N * 64, OCC)
 gemm_mfma_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const bf16* __restrict__ w2,
                  const bf16* __restrict__ w3, int ns1, int ns2, void* __restrict__ c, int m, int n, int k, int ldc,
-                 int epi, TileOrder order, int total_tiles, int per_xcd) {
+                 int epi, TileOrder order, int total_tiles, int per_xcd, const int* __restrict__ m_live) {
   constexpr int NT = WAVES_M * WAVES_N * 64;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   constexpr int FM = WTM / 32, FN = WTN / 32;
@@ -125,6 +125,8 @@ gemm_mfma_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const b
   int tile_m, tile_n;
   tile_of(order, logical, &tile_m, &tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN_OUT;
+  m = live_count(m, m_live);
+  if (m0 >= m) return;   // uniform: the grid may be sized for an upper bound of the row count
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -496,8 +498,25 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, bool DUAL, int OCC, bool THI
 __global__ void __launch_bounds__(WAVES_M * WAVES_N * 64, OCC)
 gemm_mfma_dl_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const bf16* __restrict__ w2,
                     const bf16* __restrict__ w3, int ns1, int ns2, void* __restrict__ c, int m, int n, int k, int ldc,
-                    int epi, GridPlan plan, float* __restrict__ partial) {
+                    int epi, GridPlan plan, float* __restrict__ partial, const int* __restrict__ m_live) {
   constexpr int BN_OUT = DUAL ? BN / 2 : BN;
+  if (m_live) {
+    // The row count lives on the device (rows selected by a threshold) and the host's m only sized the grid.  The
+    // schedule is rebuilt here for the live count, in its plain form: every tile whole, by one workgroup, ids
+    // regrouped per XCD over the live tiles (so that all XCDs share them), no K-split tail, no thin tiles.
+    m = min(m, *m_live);
+    if (m <= 0) return;
+    const int tiles_m = (m + BM - 1) / BM, tiles_n = plan.order.tiles_n;
+    const int total = tiles_m * tiles_n, per_xcd = (total + XCDS - 1) / XCDS;
+    const int x = (int)blockIdx.x % XCDS, j = (int)blockIdx.x / XCDS;
+    const int logical = plan.per_xcd > 0 ? x * per_xcd + j : (int)blockIdx.x;
+    if ((plan.per_xcd > 0 && j >= per_xcd) || logical >= total) return;
+    int tile_m, tile_n;
+    tile_of(make_tile_order(tiles_m, tiles_n), logical, &tile_m, &tile_n);
+    gemm_tile_body<BM, BN, WAVES_M, WAVES_N, DUAL>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, tile_m * BM, tile_n * BN_OUT,
+                                                   0, k, -1, partial);
+    return;
+  }
   const BlockWork bw = block_work(plan, (int)blockIdx.x, k);
   if (bw.kind == 0) return;
   if constexpr (THIN) {
@@ -664,7 +683,9 @@ static GridPlan make_grid_plan(int m, int tiles_n, int bm, int ksteps, int slots
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int OCC>
 static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const bf16* w3, int ns1, int ns2, void* c,
-                            int m, int n, int k, int ldc, GemmEpilogue epi, float* partial, hipStream_t st) {
+                            int m, int n, int k, int ldc, GemmEpilogue epi, float* partial, hipStream_t st,
+                            const int* m_live) {
+  if (m_live) partial = nullptr;   // the kernel rebuilds the plain schedule for the live row count
   const bool dual = epi == EPI_SWIGLU_T;
   const int bn_out = dual ? BN / 2 : BN;
   const int tiles_n = (n + bn_out - 1) / bn_out;
@@ -673,7 +694,7 @@ static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const 
   constexpr bool THIN = BM == 256 && BN == 256 && OCC == 1;
   int n_blocks = 0, rem_tiles = 0;
   const GridPlan plan = make_grid_plan(m, tiles_n, BM, k / BK, num_cus() * OCC, BN == 192 ? kStep192 : kStep256,
-                                       partial != nullptr && OCC == 1, THIN, &n_blocks, &rem_tiles);
+                                       partial != nullptr && OCC == 1, THIN && m_live == nullptr, &n_blocks, &rem_tiles);
   const int normal_full = plan.full_tiles - plan.n_thin;
   const dim3 grid((unsigned)n_blocks);
   constexpr int NT = WAVES_M * WAVES_N * 64;
@@ -684,7 +705,7 @@ static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const 
     static std::atomic<unsigned long long> told{0};
     e = allow_dynamic_lds((const void*)kern, (int)lds_bytes, told);
     if (e != hipSuccess) return e;
-    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, plan, partial);
+    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, plan, partial, m_live);
     if (rem_tiles > 0)
       gemm_fixup_kernel<BM, BN, WAVES_M, WAVES_N, true><<<rem_tiles * (BM / WAVES_M / 16) * (BN / WAVES_N / 32), NT, 0, st>>>(
           c, m, n, ldc, (int)epi, plan.order, normal_full, plan.split, partial);
@@ -693,7 +714,7 @@ static hipError_t launch_dl(const bf16* a, const bf16* w, const bf16* w2, const 
     static std::atomic<unsigned long long> told{0};
     e = allow_dynamic_lds((const void*)kern, (int)lds_bytes, told);
     if (e != hipSuccess) return e;
-    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, plan, partial);
+    kern<<<grid, NT, lds_bytes, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, plan, partial, m_live);
     if (rem_tiles > 0)
       gemm_fixup_kernel<BM, BN, WAVES_M, WAVES_N, false><<<rem_tiles * (BM / WAVES_M / 16) * (BN / WAVES_N / 16), NT, 0, st>>>(
           c, m, n, ldc, (int)epi, plan.order, normal_full, plan.split, partial);
@@ -746,7 +767,7 @@ void set_gemm_tile(int t) { g_gemm_tile = t; }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int OCC>
 static hipError_t launch_cfg(const bf16* a, const bf16* w, const bf16* w2, const bf16* w3, int ns1, int ns2, void* c,
-                             int m, int n, int k, int ldc, GemmEpilogue epi, hipStream_t st) {
+                             int m, int n, int k, int ldc, GemmEpilogue epi, hipStream_t st, const int* m_live) {
   const bool dual = epi == EPI_SWIGLU_T;
   const int bn_out = dual ? BN / 2 : BN;
   const int tiles_m = (m + BM - 1) / BM, tiles_n = (n + bn_out - 1) / bn_out;
@@ -757,19 +778,21 @@ static hipError_t launch_cfg(const bf16* a, const bf16* w, const bf16* w2, const
   constexpr int NT = WAVES_M * WAVES_N * 64;
   if (dual)
     gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, true, OCC><<<grid, NT, 0, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc,
-                                                                              (int)epi, make_tile_order(tiles_m, tiles_n), total, per_xcd);
+                                                                              (int)epi, make_tile_order(tiles_m, tiles_n), total, per_xcd, m_live);
   else
     gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, false, OCC><<<grid, NT, 0, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc,
-                                                                               (int)epi, make_tile_order(tiles_m, tiles_n), total, per_xcd);
+                                                                               (int)epi, make_tile_order(tiles_m, tiles_n), total, per_xcd, m_live);
   return hipGetLastError();
 }
 
 static hipError_t dispatch(const bf16* a, const bf16* w, const bf16* w2, const bf16* w3, int ns1, int ns2, void* c,
-                           int m, int n, int k, int ldc, GemmEpilogue epi, float* partial, hipStream_t st) {
+                           int m, int n, int k, int ldc, GemmEpilogue epi, float* partial, hipStream_t st,
+                           const int* m_live) {
   if (m <= 0 || n <= 0) return hipSuccess;
   int tile = g_gemm_tile;
   if (tile == 0 && gemm_skinny_applies(m, n, k, ns1, ns2))
-    return launch_gemm_skinny_bf16(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);
+    return launch_gemm_skinny_bf16(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st, m_live);
+  if (m_live) partial = nullptr;   // live row count on the device: plain schedule, priced as such
   if (tile == 0) {
     if (k % BK != 0) {
       tile = 3;
@@ -795,39 +818,39 @@ static hipError_t dispatch(const bf16* a, const bf16* w, const bf16* w2, const b
   }
   if (tile >= 5 && (k % BK) != 0) tile = 3;   // the direct-load kernels need whole K steps
   switch (tile) {
-    case 5: return launch_dl<256, 256, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st);
-    case 6: return launch_dl<128, 128, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, nullptr, st);
-    case 7: return launch_dl<256, 192, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st);
-    case 8: return launch_dl<256, 256, 2, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st);
-    case 2: return launch_cfg<256, 256, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);
-    case 3: return launch_cfg<128, 128, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);
-    default: return launch_cfg<128, 256, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st);
+    case 5: return launch_dl<256, 256, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st, m_live);
+    case 6: return launch_dl<128, 128, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, nullptr, st, m_live);
+    case 7: return launch_dl<256, 192, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st, m_live);
+    case 8: return launch_dl<256, 256, 2, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st, m_live);
+    case 2: return launch_cfg<256, 256, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st, m_live);
+    case 3: return launch_cfg<128, 128, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st, m_live);
+    default: return launch_cfg<128, 256, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st, m_live);
   }
 }
 
 template <>
 hipError_t launch_gemm<bf16>(const bf16* a, const bf16* w, const bf16* w2, void* c, int m, int n, int k, int ldc,
-                             GemmEpilogue epi, hipStream_t st) {
-  return dispatch(a, w, w2, nullptr, n, n, c, m, n, k, ldc, epi, nullptr, st);
+                             GemmEpilogue epi, hipStream_t st, const int* m_live) {
+  return dispatch(a, w, w2, nullptr, n, n, c, m, n, k, ldc, epi, nullptr, st, m_live);
 }
 
 hipError_t launch_gemm_bf16(const bf16* a, const bf16* w, const bf16* w2, void* c, int m, int n, int k, int ldc,
-                            GemmEpilogue epi, float* partial, hipStream_t st) {
-  return dispatch(a, w, w2, nullptr, n, n, c, m, n, k, ldc, epi, partial, st);
+                            GemmEpilogue epi, float* partial, hipStream_t st, const int* m_live) {
+  return dispatch(a, w, w2, nullptr, n, n, c, m, n, k, ldc, epi, partial, st, m_live);
 }
 
 hipError_t launch_gemm_qkv_bf16(const bf16* a, const bf16* wq, int nq, const bf16* wk, const bf16* wv, int nkv, float* c,
-                                int m, int k, float* partial, hipStream_t st) {
+                                int m, int k, float* partial, hipStream_t st, const int* m_live) {
   const int n = nq + 2 * nkv;
-  return dispatch(a, wq, wk, wv, nq, nq + nkv, c, m, n, k, n, EPI_STORE_F32, partial, st);
+  return dispatch(a, wq, wk, wv, nq, nq + nkv, c, m, n, k, n, EPI_STORE_F32, partial, st, m_live);
 }
 
 // q | k | v projections of the same rows as one GEMM over the concatenated output columns
 template <>
 hipError_t launch_gemm_qkv<bf16>(const bf16* a, const bf16* wq, int nq, const bf16* wk, const bf16* wv, int nkv,
-                                 float* c, int m, int k, hipStream_t st) {
+                                 float* c, int m, int k, hipStream_t st, const int* m_live) {
   const int n = nq + 2 * nkv;
-  return dispatch(a, wq, wk, wv, nq, nq + nkv, c, m, n, k, n, EPI_STORE_F32, nullptr, st);
+  return dispatch(a, wq, wk, wv, nq, nq + nkv, c, m, n, k, n, EPI_STORE_F32, nullptr, st, m_live);
 }
 
 }  // namespace rc

@@ -12,9 +12,11 @@ __device__ inline float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 template <typename T, bool DUAL>
 __global__ void __launch_bounds__(256)
 gemm_simt_kernel(const T* __restrict__ a, const T* __restrict__ w, const T* __restrict__ w2, void* __restrict__ c,
-                 int m, int n, int k, int ldc, int epi) {
+                 int m, int n, int k, int ldc, int epi, const int* __restrict__ m_live) {
   constexpr int VEC = Vec16<T>::N;
   constexpr int LPR = BK / VEC;  // 16-byte loads per tile row
+  m = live_count(m, m_live);
+  if ((int)blockIdx.y * BM >= m) return;   // uniform: the grid may be sized for an upper bound of the row count
   __shared__ float As[BK][BM + PAD];
   __shared__ float Bs[BK][BN + PAD];
   __shared__ float Bs2[DUAL ? BK : 1][BN + PAD];
@@ -81,31 +83,31 @@ gemm_simt_kernel(const T* __restrict__ a, const T* __restrict__ w, const T* __re
 
 template <typename T>
 hipError_t launch_gemm_simt(const T* a, const T* w, const T* w2, void* c, int m, int n, int k, int ldc,
-                            GemmEpilogue epi, hipStream_t st) {
+                            GemmEpilogue epi, hipStream_t st, const int* m_live) {
   if (m <= 0 || n <= 0) return hipSuccess;
   dim3 grid((unsigned)((n + BN - 1) / BN), (unsigned)((m + BM - 1) / BM));
   if (epi == EPI_SWIGLU_T)
-    gemm_simt_kernel<T, true><<<grid, 256, 0, st>>>(a, w, w2, c, m, n, k, ldc, (int)epi);
+    gemm_simt_kernel<T, true><<<grid, 256, 0, st>>>(a, w, w2, c, m, n, k, ldc, (int)epi, m_live);
   else
-    gemm_simt_kernel<T, false><<<grid, 256, 0, st>>>(a, w, w2, c, m, n, k, ldc, (int)epi);
+    gemm_simt_kernel<T, false><<<grid, 256, 0, st>>>(a, w, w2, c, m, n, k, ldc, (int)epi, m_live);
   return hipGetLastError();
 }
 
 template <>
 hipError_t launch_gemm<float>(const float* a, const float* w, const float* w2, void* c, int m, int n, int k,
-                              int ldc, GemmEpilogue epi, hipStream_t st) {
-  return launch_gemm_simt<float>(a, w, w2, c, m, n, k, ldc, epi, st);
+                              int ldc, GemmEpilogue epi, hipStream_t st, const int* m_live) {
+  return launch_gemm_simt<float>(a, w, w2, c, m, n, k, ldc, epi, st, m_live);
 }
 
 template <>
 hipError_t launch_gemm_qkv<float>(const float* a, const float* wq, int nq, const float* wk, const float* wv, int nkv,
-                                  float* c, int m, int k, hipStream_t st) {
+                                  float* c, int m, int k, hipStream_t st, const int* m_live) {
   const int n = nq + 2 * nkv;
-  hipError_t e = launch_gemm_simt<float>(a, wq, nullptr, c, m, nq, k, n, EPI_STORE_F32, st);
+  hipError_t e = launch_gemm_simt<float>(a, wq, nullptr, c, m, nq, k, n, EPI_STORE_F32, st, m_live);
   if (e != hipSuccess) return e;
-  e = launch_gemm_simt<float>(a, wk, nullptr, c + nq, m, nkv, k, n, EPI_STORE_F32, st);
+  e = launch_gemm_simt<float>(a, wk, nullptr, c + nq, m, nkv, k, n, EPI_STORE_F32, st, m_live);
   if (e != hipSuccess) return e;
-  return launch_gemm_simt<float>(a, wv, nullptr, c + nq + nkv, m, nkv, k, n, EPI_STORE_F32, st);
+  return launch_gemm_simt<float>(a, wv, nullptr, c + nq + nkv, m, nkv, k, n, EPI_STORE_F32, st, m_live);
 }
 
 }  // namespace rc

@@ -22,8 +22,10 @@ template <bool DUAL>
 __global__ void __launch_bounds__(kSkinnyWaves * 64)
 gemm_skinny_kernel(const bf16* __restrict__ a, const bf16* __restrict__ w, const bf16* __restrict__ w2,
                    const bf16* __restrict__ w3, int ns1, int ns2, void* __restrict__ c, int m, int n, int k, int ldc,
-                   int epi) {
+                   int epi, const int* __restrict__ m_live) {
   __shared__ float part[kSkinnyWaves][4][64][4];   // [wave][tile: gate/rows 0-15, gate/16-31, up/0-15, up/16-31][lane][e]
+  m = live_count(m, m_live);
+  if (m <= 0) return;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n0 = (int)blockIdx.x * 16;
@@ -103,12 +105,13 @@ bool gemm_skinny_applies(int m, int n, int k, int ns1, int ns2) {
 }
 
 hipError_t launch_gemm_skinny_bf16(const bf16* a, const bf16* w, const bf16* w2, const bf16* w3, int ns1, int ns2,
-                                   void* c, int m, int n, int k, int ldc, GemmEpilogue epi, hipStream_t st) {
+                                   void* c, int m, int n, int k, int ldc, GemmEpilogue epi, hipStream_t st,
+                                   const int* m_live) {
   const dim3 grid((unsigned)(n / 16));
   if (epi == EPI_SWIGLU_T)
-    gemm_skinny_kernel<true><<<grid, kSkinnyWaves * 64, 0, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi);
+    gemm_skinny_kernel<true><<<grid, kSkinnyWaves * 64, 0, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, m_live);
   else
-    gemm_skinny_kernel<false><<<grid, kSkinnyWaves * 64, 0, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi);
+    gemm_skinny_kernel<false><<<grid, kSkinnyWaves * 64, 0, st>>>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, (int)epi, m_live);
   return hipGetLastError();
 }
 

@@ -37,7 +37,7 @@ influence_scores_kernel(const T* __restrict__ q, const int* __restrict__ row_pos
   const int sub = threadIdx.x % lpr;         // my 16-byte piece of the row
   const int keys_per_pass = kInfThreads / lpr;
   const float scale = rsqrtf((float)dh);
-  const int seq = table->r[row_req[row]].dst_seq;
+  const int seq = table->r[row_req[row] & kRowReqMask].dst_seq;
   const int j_end = min(j0 + kInfKeys, pos + 1);
   const bool contig = g.max_blocks == 1;     // one block per sequence: rows are a linear function of the position
   const T* kbase = contig ? k_pool + kv_row_offset(g, seq, 0, hk) + sub * VEC : nullptr;
@@ -113,7 +113,7 @@ influence_add_kernel(const float* __restrict__ scores, const float2* __restrict_
   const int row = blockIdx.y;
   const int j = blockIdx.x * kInfThreads + threadIdx.x;
   if (j > row_pos[row]) return;
-  float* dst = out.s_inf[row_req[row]];
+  float* dst = out.s_inf[row_req[row] & kRowReqMask];
   if (dst == nullptr) return;
   float acc = 0.f;
   for (int h = 0; h < n_q_heads; ++h) {

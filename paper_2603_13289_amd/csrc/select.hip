@@ -42,8 +42,7 @@ __device__ inline int block_exclusive_scan(int v, int* lds /* kSelWaves + 1 ints
   return lds[w] + inc - v;
 }
 
-__global__ void __launch_bounds__(kSelThreads)
-topk_kernel(const float* __restrict__ score, int n, int k, int* __restrict__ idx_out) {
+__device__ __forceinline__ void topk_body(const float* __restrict__ score, int n, int k, int* __restrict__ idx_out) {
   __shared__ int hist[256];
   __shared__ int scan_lds[kSelWaves + 1];
   __shared__ uint32_t s_prefix;
@@ -103,6 +102,39 @@ topk_kernel(const float* __restrict__ score, int n, int k, int* __restrict__ idx
   }
 }
 
+__global__ void __launch_bounds__(kSelThreads)
+topk_kernel(const float* __restrict__ score, int n, int k, int* __restrict__ idx_out) {
+  topk_body(score, n, k, idx_out);
+}
+
+// one workgroup per request of a call; requests without a budget (or not in the dense phase) are skipped
+__global__ void __launch_bounds__(kSelThreads)
+topk_batch_kernel(const float* __restrict__ scores, const ReqTable* __restrict__ table, int* __restrict__ sel_idx) {
+  const ReqDev& rq = table->r[blockIdx.x];
+  if (rq.k <= 0 || rq.S <= 0) return;      // uniform for the workgroup
+  topk_body(scores + rq.score_base, rq.S, min(rq.k, rq.S), sel_idx + rq.sel_base);
+}
+
+hipError_t launch_topk_batch(const float* scores, const ReqTable* table, int n_req, int* sel_idx, hipStream_t st) {
+  if (n_req <= 0) return hipSuccess;
+  topk_batch_kernel<<<n_req, kSelThreads, 0, st>>>(scores, table, sel_idx);
+  return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(256)
+copy_sel_batch_kernel(const int* __restrict__ forced, const ReqTable* __restrict__ table, int* __restrict__ sel_idx) {
+  const ReqDev& rq = table->r[blockIdx.y];
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < rq.k) sel_idx[rq.sel_base + i] = forced[rq.sel_base + i];
+}
+
+hipError_t launch_copy_sel_batch(const int* forced, const ReqTable* table, int n_req, int* sel_idx, hipStream_t st) {
+  if (n_req <= 0) return hipSuccess;
+  // k <= S <= 2^20 entries per request
+  copy_sel_batch_kernel<<<dim3(4096, (unsigned)n_req), 256, 0, st>>>(forced, table, sel_idx);
+  return hipGetLastError();
+}
+
 hipError_t launch_topk(const float* score, int n, int k, int* idx_out, hipStream_t st) {
   if (k <= 0 || n <= 0) return hipSuccess;
   topk_kernel<<<1, kSelThreads, 0, st>>>(score, n, k, idx_out);
@@ -144,9 +176,9 @@ threshold_select_kernel(const float* __restrict__ score, int n, float tau, int* 
 // Eq. (5)-(10) in one pass: I_dev (deviation >= tau_dev * mean) united with I_inf-score (influence >=
 // tau_inf * mean, when influence scores are given) and the last k_suf tokens; ascending; count out.
 // Means are accumulated in double in a fixed order, comparisons are made in double.
-__global__ void __launch_bounds__(kSelThreads)
-final_select_kernel(const float* __restrict__ s_dev, const float* __restrict__ s_inf, int n, float tau_dev,
-                    float tau_inf, int k_suf, int* __restrict__ idx_out, int* __restrict__ count_out) {
+__device__ __forceinline__ void final_select_body(const float* __restrict__ s_dev, const float* __restrict__ s_inf, int n,
+                                                  float tau_dev, float tau_inf, int k_suf, int* __restrict__ idx_out,
+                                                  int* __restrict__ count_out) {
   __shared__ double part[2][kSelWaves];
   __shared__ int scan_lds[kSelWaves + 1];
   __shared__ double s_thr[2];
@@ -185,6 +217,30 @@ final_select_kernel(const float* __restrict__ s_dev, const float* __restrict__ s
   for (int i = lo; i < hi; ++i)
     if (chosen(i)) idx_out[out++] = i;
   if (threadIdx.x == 0) *count_out = total;
+}
+
+__global__ void __launch_bounds__(kSelThreads)
+final_select_kernel(const float* __restrict__ s_dev, const float* __restrict__ s_inf, int n, float tau_dev,
+                    float tau_inf, int k_suf, int* __restrict__ idx_out, int* __restrict__ count_out) {
+  final_select_body(s_dev, s_inf, n, tau_dev, tau_inf, k_suf, idx_out, count_out);
+}
+
+__global__ void __launch_bounds__(kSelThreads)
+final_select_batch_kernel(const float* __restrict__ scores, InfluenceIn inf, const ReqTable* __restrict__ table,
+                          float tau_dev, float tau_inf, int k_suf, int* __restrict__ sel_idx,
+                          int* __restrict__ sel_cnt) {
+  const ReqDev& rq = table->r[blockIdx.x];
+  if (rq.k <= 0 || rq.S <= 0) return;
+  final_select_body(scores + rq.score_base, inf.s_inf[blockIdx.x], rq.S, tau_dev, tau_inf, k_suf,
+                    sel_idx + rq.sel_base, sel_cnt + blockIdx.x);
+}
+
+hipError_t launch_final_select_batch(const float* scores, const InfluenceIn& inf, const ReqTable* table, int n_req,
+                                     float tau_dev, float tau_inf, int k_suf, int* sel_idx, int* sel_cnt,
+                                     hipStream_t st) {
+  if (n_req <= 0) return hipSuccess;
+  final_select_batch_kernel<<<n_req, kSelThreads, 0, st>>>(scores, inf, table, tau_dev, tau_inf, k_suf, sel_idx, sel_cnt);
+  return hipGetLastError();
 }
 
 hipError_t launch_final_select(const float* s_dev, const float* s_inf, int n, float tau_dev, float tau_inf, int k_suf,

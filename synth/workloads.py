@@ -95,6 +95,8 @@ _add(Workload("qwen32b_32k", _QWEN32, 4096, 32768, 2048, 15, 16, 48, 10))
 # Parity-sized relatives: same structure, sizes the CPU oracle finishes in seconds.
 _add(Workload("tiny_f32_paged", _TINY, 100, 203, 77, 0, 1, 1, 20, block_size=16,
               note="ragged sizes, paged"))
+_add(Workload("tiny_f32_inplace", _TINY, 112, 203, 80, 0, 1, 1, 20, block_size=16,
+              note="the segment moves by exactly two 16-token blocks (80 -> 112): a take-over in place is allowed"))
 _TINY5 = ModelShape(5, 256, 4, 2, 64, 688, 512, 1.0e4, dtype="f32")
 _add(Workload("tiny5_f32", _TINY5, 70, 150, 33, 1, 2, 3, 20, block_size=16,
               note="5 layers so that every phase (before / dense / sparse / after) has at least one layer"))

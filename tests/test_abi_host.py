@@ -101,6 +101,36 @@ def test_reuse_argument_errors_are_reported_before_any_launch():
     m.close()
 
 
+def test_reuse_in_shared_pools_needs_a_block_aligned_move():
+    """Source and destination in the same pools: allowed only when the segment moves by whole blocks."""
+    m = _cpu_model(SHAPE)
+    table = [[0, 1, 2, 3], [4, 5, 6, 7]]
+    kv = rc.PagedKV(3, 8, 4, 1, 64, rc.RC_F32, table, device="cpu")
+    other = rc.PagedKV(3, 8, 4, 1, 64, rc.RC_F32, table, device="cpu")
+    logits = torch.zeros((1, 32)); sel = torch.zeros(8, dtype=torch.int32)
+    raw = torch.zeros((1 << 22) + 256, dtype=torch.uint8)
+    ws = raw[(-raw.data_ptr()) % 256:]                    # the workspace check wants 256-byte alignment
+    plan = rc.Plan(0, 1, 2, [2])
+
+    def status(req, src, dst):
+        try:
+            rc.rc_reuse(m, [req], plan, src, dst, logits, sel, None, ws)
+        except rc.RcError as e:
+            return e.status
+        return rc.RC_OK
+
+    t = lambda n: torch.zeros((n, SHAPE.d_model))
+    moved_by_3 = rc.Request(t(5), t(6), None, src_seq=0, src_offset=2, dst_seq=1)          # 5 - 2 = 3, blocks of 4
+    assert status(moved_by_3, kv, kv) == rc.RC_E_UNSUPPORTED
+    cached = rc.Request(t(1), t(6), None, src_seq=0, src_offset=2, dst_seq=1, n_cached=2)  # 2 + 1 - 2 = 1
+    assert status(cached, kv, kv) == rc.RC_E_UNSUPPORTED
+    mixed = rc.PagedKV.from_pools(kv.k, other.v, kv.block_table, rc.RC_F32)                 # only the key pools shared
+    assert status(moved_by_3, kv, mixed) == rc.RC_E_UNSUPPORTED
+    # (an aligned move in shared pools and any move between separate caches pass this check; they go on to launch
+    # kernels, which the GPU tests cover)
+    m.close()
+
+
 def test_stage_argument_errors():
     def status(fn):
         with pytest.raises(rc.RcError) as e:

@@ -109,6 +109,53 @@ def test_f32_all_phases_and_edge_shapes(name, k, n_suffix):
     _check_against_oracle(case, run, wants, TOL["f32"])
 
 
+def test_take_over_in_place_equals_take_over_by_copy():
+    """Source and destination in the same pools, the destination's block table naming the very blocks the earlier
+    agent's segment sits in (allowed because the segment moves by whole blocks): keys are rotated where they are,
+    values are not moved at all, and the result equals the ordinary copy into a separate cache bit for bit."""
+    import torch
+    from paper_2603_13289_amd import binding as rc
+    case = build_case("tiny_f32_inplace")
+    want = oracle_relay(case)
+    ref = hip_relay(case)
+    w, sh, rq = case.w, case.w.shape, case.reqs[0]
+    bs = w.block_size
+    assert (rq.P - rq.A) % bs == 0 and rq.A % bs == 0
+    dt = rc.rc_dtype_of(sh.dtype)
+    up = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda().contiguous()
+    n_alt, n_seg, n_pre = rq.A // bs, -(-rq.S // bs), rq.P // bs
+    n_blocks = n_alt + n_seg + n_pre + 2
+    src_tab = np.arange(n_alt + n_seg, dtype=np.int32)[None, :]
+    dst_tab = np.concatenate([np.arange(n_alt + n_seg, n_alt + n_seg + n_pre), np.arange(n_alt, n_alt + n_seg)]).astype(np.int32)[None, :]
+    src = rc.PagedKV(sh.n_layers, n_blocks, bs, sh.n_kv_heads, sh.head_dim, dt, src_tab)
+    dst = rc.PagedKV.from_pools(src.k, src.v, torch.from_numpy(dst_tab).cuda(), dt)
+    for l in range(sh.n_layers):
+        src.write("k", l, 0, up(rq.seg.k[l]), start=rq.A)
+        src.write("v", l, 0, up(rq.seg.v[l]), start=rq.A)
+    model = rc.rc_model_create(sh, case.weights)
+    req = rc.Request(up(rq.xp), up(rq.seg.h_start), None, src_seq=0, src_offset=rq.A, k_is_pre_rope=True,
+                     seg_old_start_pos=rq.A, dst_seq=0)
+    plan = rc.Plan(w.l_start, w.l_det, w.l_end, [rq.k])
+    ws = rc.alloc_workspace(rc.rc_reuse_workspace_bytes(model, [req], plan))
+    logits = torch.zeros((1, sh.vocab), dtype=torch.float32, device="cuda")
+    sel = torch.full((rq.k,), -1, dtype=torch.int32, device="cuda")
+    rc.rc_reuse(model, [req], plan, src, dst, logits, sel, None, ws)
+    torch.cuda.synchronize()
+    T = rq.P + rq.S
+    assert np.array_equal(sel.cpu().numpy(), ref.sel[0]) and np.array_equal(ref.sel[0], want.sel_idx)
+    for l in range(sh.n_layers):
+        assert np.array_equal(dst.read("k", l, 0, T).cpu().numpy(), ref.k_cache[0][l][:T])
+        assert np.array_equal(dst.read("v", l, 0, T).cpu().numpy(), ref.v_cache[0][l][:T])
+    assert np.array_equal(logits.cpu().numpy(), ref.logits)
+    # a move that is not a whole number of blocks is refused before anything is launched
+    bad = rc.Request(up(rq.xp[:-3]), up(rq.seg.h_start), None, src_seq=0, src_offset=rq.A, k_is_pre_rope=True,
+                     seg_old_start_pos=rq.A, dst_seq=0)
+    with pytest.raises(rc.RcError) as e:
+        rc.rc_reuse(model, [bad], plan, src, dst, logits, sel, None, ws)
+    assert e.value.status == rc.RC_E_UNSUPPORTED
+    model.close()
+
+
 # ------------------------------------------------------------------ the paper's own selector, Eq. (5)-(10)
 def _safe_tau(score, tau):
     """Nudge tau until no score sits within MARGIN of the cut (the two sides score in different precisions)."""
@@ -232,6 +279,30 @@ def test_determinism_same_inputs_twice():
         assert np.array_equal(a.k_cache[0][l], b.k_cache[0][l])
 
 
+def test_determinism_when_the_last_token_is_selected_too():
+    """The paper's selector always selects the segment's last token (k_suf >= 1), which is also the row kept live for
+    the logits: two live rows of one token.  The cut is chosen so that the twins fall into different 256-row GEMM
+    tiles (150 new rows + 106 selected = rows 0..255, the extra copy is row 256), where their sums may differ in the
+    last bit; only one of them writes the cache, so two runs agree bit for bit and the cache row is the twin's."""
+    case = build_case("small_bf16")
+    rq = case.reqs[0]
+    probe = hip_relay(case)                                      # the library's own scores
+    score = probe.scores[0].astype(np.float64)
+    want_cnt = 256 - rq.P                                        # selected rows incl. the last token
+    k_suf = 4
+    head = np.sort(score[:rq.S - k_suf])[::-1]
+    cut = 0.5 * (head[want_cnt - k_suf - 1] + head[want_cnt - k_suf])
+    tau = cut / float(np.mean(score))
+    runs = [hip_relay(case, thresholds=(tau, 1.45, k_suf)) for _ in range(2)]
+    a, b = runs
+    assert len(a.sel[0]) == want_cnt and a.sel[0][-1] == rq.S - 1
+    assert np.array_equal(a.sel[0], b.sel[0]) and np.array_equal(a.logits, b.logits)
+    for l in range(case.w.shape.n_layers):
+        assert np.array_equal(a.k_cache[0][l], b.k_cache[0][l]) and np.array_equal(a.v_cache[0][l], b.v_cache[0][l])
+    want = oracle_relay(case, forced_idx=a.sel[0])
+    _check_against_oracle(case, a, [want], TOL["bf16"])
+
+
 # ------------------------------------------------------------------ several reused segments (relay chain)
 @pytest.mark.parametrize("name,ends_with_segment", [("tiny5_f32", False), ("tiny5_f32", True), ("small_bf16", False)])
 def test_multi_segment_prompt_by_chained_calls(name, ends_with_segment):
@@ -308,10 +379,12 @@ def test_multi_segment_prompt_by_chained_calls(name, ends_with_segment):
 
 
 # ------------------------------------------------------------------ graph capture
-def test_reuse_call_can_be_captured_in_a_graph_and_replayed():
-    """rc_reuse with the budget selector only enqueues kernels on the caller's stream (no allocation, no copy, no
-    wait), so a caller may capture it in a HIP graph.  Every replay, with eager work in between, reproduces the
-    eager result bit for bit."""
+@pytest.mark.parametrize("selector", ["budget", "threshold"])
+def test_reuse_call_can_be_captured_in_a_graph_and_replayed(selector):
+    """rc_reuse only enqueues kernels on the caller's stream (no allocation, no copy, no wait), with the budget
+    selector and with the paper's threshold selector alike (the selected rows' count stays on the device), so a
+    caller may capture it in a HIP graph.  Every replay, with eager work in between, reproduces the eager result
+    bit for bit."""
     import torch
     from paper_2603_13289_amd import binding as rc
     from synth import WORKLOADS, make_hidden, make_weights
@@ -333,18 +406,27 @@ def test_reuse_call_can_be_captured_in_a_graph_and_replayed():
     record = rc.PagedKV.from_pools(old_pre.k, old.v, old.block_table, dt)
     dst = rc.PagedKV.contiguous(sh.n_layers, 1, P + S, sh.n_kv_heads, sh.head_dim, dt)
     req = rc.Request(x_new, h_cap[A:].contiguous(), None, src_seq=0, src_offset=A, k_is_pre_rope=True, seg_old_start_pos=A)
-    plan = rc.Plan(w.l_start, w.l_det, w.l_end, [k])
+    if selector == "budget":
+        plan = rc.Plan(w.l_start, w.l_det, w.l_end, [k])
+        sel = torch.zeros(k, dtype=torch.int32, device="cuda")
+        cnt = None
+    else:
+        plan = rc.Plan(w.l_start, w.l_det, w.l_end, None, None, rc.RC_SELECT_THRESHOLD, 1.5, 1.45, 10)
+        sel = torch.zeros(S, dtype=torch.int32, device="cuda")
+        cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
     ws = rc.alloc_workspace(rc.rc_reuse_workspace_bytes(model, [req], plan))
     logits = torch.zeros((1, sh.vocab), dtype=torch.float32, device="cuda")
-    sel = torch.zeros(k, dtype=torch.int32, device="cuda")
     scores = torch.zeros(S, dtype=torch.float32, device="cuda")
 
     def call(stream=None):
-        rc.rc_reuse(model, [req], plan, record, dst, logits, sel, scores, ws, stream=stream)
+        rc.rc_reuse(model, [req], plan, record, dst, logits, sel, scores, ws, stream=stream, sel_cnt=cnt)
 
+    outs = [logits, sel, scores] + ([] if cnt is None else [cnt]) + dst.k + dst.v
     call()
     torch.cuda.synchronize()
-    ref = [logits.clone(), sel.clone(), scores.clone()] + [t.clone() for t in dst.k] + [t.clone() for t in dst.v]
+    ref = [t.clone() for t in outs]
+    if cnt is not None:
+        assert 10 <= int(cnt[0]) < S
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
@@ -355,12 +437,18 @@ def test_reuse_call_can_be_captured_in_a_graph_and_replayed():
         call(torch.cuda.current_stream())
     torch.cuda.synchronize()
     for rep in range(3):
-        for t in [logits, scores] + dst.k + dst.v:     # eager work between the replays: wipe the outputs
-            t.zero_()
-        sel.fill_(-1)
+        for t in outs:                                 # eager work between the replays: wipe the outputs
+            if t.dtype == torch.int32:
+                t.fill_(-1)
+            else:
+                t.zero_()
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        now = [logits, sel, scores] + dst.k + dst.v
-        assert all(torch.equal(a, b) for a, b in zip(now, ref)), rep
+        for a, b in zip(outs, ref):
+            if a is sel and cnt is not None:             # only the first sel_cnt entries are written
+                n_sel = int(ref[3][0])
+                assert torch.equal(a[:n_sel], b[:n_sel]), rep
+            else:
+                assert torch.equal(a, b), rep
     model.close()
