@@ -399,6 +399,18 @@ RC_API rc_status rc_gemm_rows_fused(int32_t dtype, int32_t epilogue, const void*
                                     void* c, int32_t m, int32_t n, int32_t k, void* workspace,
                                     size_t workspace_bytes, void* stream);
 
+/* The step of the hot path between the q|k|v projection and attention, on its own (the kernel rc_reuse runs in
+ * every layer; Figure "Overview", item 3: recomputed rows are written back into the cache): qkv [n][Hq*dh | Hkv*dh |
+ * Hkv*dh] float holds the projections of n live rows at positions pos[i] (device int32, each below the capacity of
+ * `seq`); queries and keys are rotated to their positions (pairs (i, i + dh/2), angle pos * base^(-2i/dh)), the
+ * rotated queries go to q_out [n][Hq][dh] of T, rotated keys and the values into the cache rows pos[i] of `seq`.
+ * workspace: device scratch of rc_rope_scatter_workspace_bytes(n, dst) (request table and the rotary table of the
+ * whole sequence capacity, at most 2^24 positions, else RC_E_CAPACITY). */
+RC_API size_t rc_rope_scatter_workspace_bytes(int32_t n, const rc_kv_layer* dst);
+RC_API rc_status rc_rope_scatter(const float* qkv, const int32_t* pos, int32_t n, int32_t n_q_heads, float rope_base,
+                          const rc_kv_layer* dst, int32_t seq, void* q_out, void* workspace,
+                          size_t workspace_bytes, void* stream);
+
 /* Write n recomputed rows into one layer of a paged cache: k_rows/v_rows [n][Hkv][dh] of T go to
  * positions pos[i] of `seq` (keys as given, i.e. already rotated). */
 RC_API rc_status rc_scatter_paged(const void* k_rows, const void* v_rows, const int32_t* pos, int32_t n,

@@ -30,6 +30,7 @@ EXPORTS = [
     "rc_scatter_paged", "rc_profile_enable", "rc_profile_class_count", "rc_profile_class_name", "rc_profile_read",
     "rc_tune_set", "rc_sparse_attention_workspace_bytes",
     "rc_gemm_workspace_bytes", "rc_rope_rerotate_static", "rc_rope_rerotate_static_scratch_bytes",
+    "rc_rope_scatter", "rc_rope_scatter_workspace_bytes",
 ]
 
 
@@ -128,6 +129,10 @@ def _load() -> C.CDLL:
                                             i32, i32, C.c_float, vp]
     lib.rc_rope_rerotate_static_scratch_bytes.restype = sz
     lib.rc_rope_rerotate_static_scratch_bytes.argtypes = []
+    lib.rc_rope_scatter_workspace_bytes.restype = sz
+    lib.rc_rope_scatter_workspace_bytes.argtypes = [i32, C.POINTER(rc_kv_layer)]
+    lib.rc_rope_scatter.restype = C.c_int
+    lib.rc_rope_scatter.argtypes = [vp, vp, i32, i32, C.c_float, C.POINTER(rc_kv_layer), i32, vp, vp, sz, vp]
     lib.rc_vdev_score.restype = C.c_int
     lib.rc_vdev_score.argtypes = [vp, C.POINTER(rc_kv_layer), i32, i32, i32, vp, vp, sz, vp]
     lib.rc_topk.restype = C.c_int
@@ -553,6 +558,17 @@ def rc_gemm_rows_fused(dtype: int, epilogue: int, a: torch.Tensor, w: torch.Tens
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.rc_gemm_rows_fused(dtype, epilogue, _ptr(a), _ptr(w), _ptr(w2), _ptr(c), m, n, k, _ptr(workspace),
                                   nbytes, _stream(stream)), "rc_gemm_rows_fused")
+
+
+def rc_rope_scatter_workspace_bytes(n: int, dst: rc_kv_layer) -> int:
+    return int(lib.rc_rope_scatter_workspace_bytes(n, C.byref(dst)))
+
+
+def rc_rope_scatter(qkv: torch.Tensor, pos: torch.Tensor, n: int, n_q_heads: int, rope_base: float, dst: rc_kv_layer,
+                    seq: int, q_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    _check(lib.rc_rope_scatter(_ptr(qkv), _ptr(pos), n, n_q_heads, rope_base, C.byref(dst), seq, _ptr(q_out),
+                               _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "rc_rope_scatter")
 
 
 def rc_scatter_paged(k_rows: torch.Tensor, v_rows: torch.Tensor, pos: torch.Tensor, n: int, dst: rc_kv_layer,

@@ -658,7 +658,7 @@ rc_status rc_model_create(const rc_model_desc* desc, const rc_layer_w* layers, c
 }
 
 rc_status rc_tune_set(int32_t key, int32_t value) {
-  if (key == RC_TUNE_GEMM_TILE && (value == 0 || value == 1 || value == 2 || value == 3 || value == 5 || value == 6 || value == 7 || value == 8)) {
+  if (key == RC_TUNE_GEMM_TILE && (value == 0 || value == 1 || value == 2 || value == 3 || value == 5 || value == 6 || value == 7)) {
     set_gemm_tile(value);
     return RC_OK;
   }
@@ -1173,6 +1173,46 @@ rc_status rc_gemm_rows_fused(int32_t dtype, int32_t epilogue, const void* a, con
                           reinterpret_cast<float*>(workspace), st));
   else
     RC_HIP(gemm_any<float>((const float*)a, (const float*)w, (const float*)w2, c, m, n, k, n, epi, nullptr, st));
+  return RC_OK;
+}
+
+size_t rc_rope_scatter_workspace_bytes(int32_t n, const rc_kv_layer* dst) {
+  if (!dst || n < 0 || dst->max_blocks_per_seq < 1 || dst->block_size < 1 || dst->head_dim < 2) return 0;
+  const long capacity = (long)dst->max_blocks_per_seq * dst->block_size;
+  if (capacity > (1 << 24)) return 0;
+  return rc_stage_workspace_bytes((int)capacity, dst->head_dim);
+}
+
+rc_status rc_rope_scatter(const float* qkv, const int32_t* pos, int32_t n, int32_t n_q_heads, float rope_base,
+                          const rc_kv_layer* dst, int32_t seq, void* q_out, void* workspace, size_t workspace_bytes,
+                          void* stream) {
+  RC_TRY(check_kv_layer(dst));
+  if (!qkv || !pos || !q_out || n < 0 || n_q_heads < 1 || n_q_heads % dst->n_kv_heads || !(rope_base > 0.f))
+    return RC_E_INVALID_ARG;
+  if (seq < 0 || seq >= dst->n_seq) return RC_E_CAPACITY;
+  const size_t need = rc_rope_scatter_workspace_bytes(n, dst);
+  if (need == 0) return RC_E_CAPACITY;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || need > workspace_bytes) return RC_E_WORKSPACE;
+  if (n == 0) return RC_OK;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const int capacity = dst->max_blocks_per_seq * dst->block_size;
+  char* p = reinterpret_cast<char*>(workspace);
+  ReqTable* dt = reinterpret_cast<ReqTable*>(p);
+  float2* rope_tab = reinterpret_cast<float2*>(p + align_up(sizeof(ReqTable)));
+  ReqTable t = ReqTable();
+  t.n_req = 1;
+  t.total_rows = n;
+  t.r[0].dst_seq = seq;
+  t.r[0].n_rows = n;
+  RC_HIP(launch_upload_table(t, dt, st));
+  RC_HIP(launch_rope_table(rope_tab, capacity, dst->head_dim / 2, (double)rope_base, st));
+  const int* row_req = nullptr;   // every row belongs to request 0
+  if (dst->dtype == RC_BF16)
+    RC_HIP(launch_rope_scatter<bf16>(qkv, n, pos, row_req, dt, rope_tab, (bf16*)q_out, (bf16*)dst->k, (bf16*)dst->v, nullptr,
+                                     geom_of(*dst), n_q_heads, st));
+  else
+    RC_HIP(launch_rope_scatter<float>(qkv, n, pos, row_req, dt, rope_tab, (float*)q_out, (float*)dst->k, (float*)dst->v,
+                                      nullptr, geom_of(*dst), n_q_heads, st));
   return RC_OK;
 }
 

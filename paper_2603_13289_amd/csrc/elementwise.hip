@@ -336,8 +336,9 @@ rope_scatter_kernel(const float* __restrict__ qkv, const int* __restrict__ row_p
   const int r = blockIdx.x;
   if (r >= table->total_rows) return;
   const int pos = row_pos[r];
-  const int seq = table->r[row_req[r] & kRowReqMask].dst_seq;
-  const bool write_cache = (row_req[r] & kRowNoCacheWrite) == 0;
+  const int rr = row_req ? row_req[r] : 0;     // no per-row request array: all rows belong to request 0
+  const int seq = table->r[rr & kRowReqMask].dst_seq;
+  const bool write_cache = (rr & kRowNoCacheWrite) == 0;
   const int dh = g.head_dim, half = dh / 2, quads = half / 4;
   const int nq = n_q_heads * dh, nkv = g.n_kv_heads * dh;
   const float* row = qkv + (size_t)r * (nq + 2 * nkv);

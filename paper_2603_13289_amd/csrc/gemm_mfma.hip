@@ -821,7 +821,6 @@ static hipError_t dispatch(const bf16* a, const bf16* w, const bf16* w2, const b
     case 5: return launch_dl<256, 256, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st, m_live);
     case 6: return launch_dl<128, 128, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, nullptr, st, m_live);
     case 7: return launch_dl<256, 192, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st, m_live);
-    case 8: return launch_dl<256, 256, 2, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, partial, st, m_live);
     case 2: return launch_cfg<256, 256, 4, 2, 1>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st, m_live);
     case 3: return launch_cfg<128, 128, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st, m_live);
     default: return launch_cfg<128, 256, 2, 2, 2>(a, w, w2, w3, ns1, ns2, c, m, n, k, ldc, epi, st, m_live);

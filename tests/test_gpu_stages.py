@@ -418,6 +418,35 @@ def test_scatter_paged(dtype, hkv, dh, block_size):
     assert np.array_equal(to_np(cache.read("k", 0, 1, 33)), ks[1])     # other sequences untouched
 
 
+@pytest.mark.parametrize("dtype,hq,hkv,dh", [("f32", 4, 2, 64), ("bf16", 32, 8, 128), ("bf16", 10, 2, 128)])
+@pytest.mark.parametrize("block_size", [0, 16])
+def test_rope_scatter_of_the_hot_path(dtype, hq, hkv, dh, block_size):
+    """The kernel rc_reuse runs between the q|k|v projection and attention, through its own stage call: rotary on
+    queries and keys at scattered positions, fresh K/V rows written into the paged cache."""
+    rc = _rc()
+    T, n = 700, 131
+    base = 10000.0 if dtype == "f32" else 1.0e6
+    cache, ks, vs = _cache(dtype, hkv, dh, [T, 40], block_size, "rs")
+    g = stream_rng("stage", "rs_pos")
+    pos = np.sort(g.choice(T, size=n, replace=False)).astype(np.int32)
+    nq, nkv = hq * dh, hkv * dh
+    qkv = stream_rng("stage", "rs_qkv").standard_normal((n, nq + 2 * nkv), dtype=np.float32)
+    q_out = torch.zeros((n, hq, dh), dtype=_td(dtype), device="cuda")
+    ws = rc.alloc_workspace(rc.rc_rope_scatter_workspace_bytes(n, cache.layer(0)))
+    rc.rc_rope_scatter(torch.from_numpy(qkv).cuda(), torch.from_numpy(pos).cuda(), n, hq, base, cache.layer(0), 0, q_out, ws)
+    torch.cuda.synchronize()
+    q_want = R.rope_rotate(qkv[:, :nq].reshape(n, hq, dh), pos, base)
+    k_want = R.rope_rotate(qkv[:, nq:nq + nkv].reshape(n, hkv, dh), pos, base)
+    v_want = qkv[:, nq + nkv:].reshape(n, hkv, dh)
+    tol = 1e-6 if dtype == "f32" else 4e-3                   # one rounding to bf16
+    assert rel_err(to_np(q_out), q_want) <= tol
+    got_k, got_v = to_np(cache.read("k", 0, 0, T)), to_np(cache.read("v", 0, 0, T))
+    assert rel_err(got_k[pos], k_want) <= tol and rel_err(got_v[pos], v_want) <= tol
+    rest = np.setdiff1d(np.arange(T), pos)
+    assert np.array_equal(got_k[rest], ks[0][rest]) and np.array_equal(got_v[rest], vs[0][rest])   # other rows untouched
+    assert np.array_equal(to_np(cache.read("k", 0, 1, 40)), ks[1])
+
+
 # ------------------------------------------------------------------ machine ceilings (benchmark report helpers)
 def test_ceiling_kernels_run_and_copy_is_exact():
     rc = _rc()
