@@ -168,48 +168,68 @@ int est_row_pos(const ReqDev& r, int i) {
 
 // Chooses chunk length and split threshold for a phase from the (estimated) row positions of table t; the
 // per-request slot assignment is left to assign_split_slots.  n_chunks == 1: no split.
-AttnSplit choose_phase_split(const ReqTable* t, int n_kv_heads, int tile_rows, int max_pos) {
-  const int n_req = t->n_req;
-  long work = 0;
+//
+// A workgroup serves one (query tile, KV head[, KV chunk]) and costs its KV tiles plus a fixed part (prologue, first
+// tile's latency); two workgroups share a compute unit.  Candidates (no split, chunks of 16 ... 128 KV tiles; a tile is
+// split when its range is longer than one chunk) are priced by a list-scheduling estimate: the busier of "the longest
+// workgroup" and "all work spread over the slots", plus half a longest workgroup for the ragged end of the launch,
+// plus the merge pass over the partial results of the split rows.  Units: one KV tile step of one slot (~2.2 us).
+// Measured on the 2048 + 16384-token workload: its sparse layers (1639 selected rows, up to 288 KV tiles each) take
+// 520 us unsplit and 182 + 33 us with chunks of 32; the dense layer and the short prefix-only layers are best left whole.
+constexpr float kWgFixedSteps = 3.f;       // fixed cost of a workgroup
+constexpr float kMergeFixedSteps = 3.5f;   // launch of the merge kernel
+constexpr float kMergeBytesPerStep = 8.8e6f;
+
+float price_split(const ReqTable* t, int n_kv_heads, int n_q_heads, int tile_rows, int chunk /* 0: none */, int slots) {
+  double work = 0.0, merge_bytes = 0.0;
   int longest = 0;
-  for (int b = 0; b < n_req; ++b) {
+  for (int b = 0; b < t->n_req; ++b) {
     const ReqDev& r = t->r[b];
     for (int i0 = 0; i0 < r.n_rows; i0 += tile_rows) {
-      const int n = est_row_pos(r, std::min(i0 + tile_rows, r.n_rows) - 1) / kKvTile + 1;
-      work += n;
-      longest = std::max(longest, n);
+      const int rows = std::min(tile_rows, r.n_rows - i0);
+      const int n = est_row_pos(r, i0 + rows - 1) / kKvTile + 1;
+      if (chunk > 0 && n > chunk) {
+        const int parts = (n + chunk - 1) / chunk;
+        work += (double)(n + kWgFixedSteps * parts) * n_kv_heads;
+        longest = std::max(longest, chunk);
+        merge_bytes += (double)rows * n_q_heads * parts * (128 + 2) * 4;
+      } else {
+        work += (double)(n + kWgFixedSteps) * n_kv_heads;
+        longest = std::max(longest, n);
+      }
     }
   }
-  int chunk_tiles, thr;
+  const float l = longest + kWgFixedSteps;
+  float cost = std::max(l, (float)(work / slots)) + 0.5f * l;
+  if (merge_bytes > 0.0) cost += kMergeFixedSteps + (float)(merge_bytes / kMergeBytesPerStep);
+  return cost;
+}
+
+AttnSplit choose_phase_split(const ReqTable* t, int n_kv_heads, int n_q_heads, int tile_rows, int max_pos) {
+  int chunk_tiles = 0;
   const int forced = attention_forced_chunk_tiles();
   if (forced > 0) {
-    chunk_tiles = thr = forced;
+    chunk_tiles = forced;
   } else {
-    const long balanced = work * n_kv_heads / 512;      // KV tiles per workgroup slot if perfectly spread
-    if (longest <= kLongKvTiles || longest <= 2 * balanced) return attention_no_split();
-    thr = kLongKvTiles;
-    for (chunk_tiles = 16; chunk_tiles > 4; chunk_tiles /= 2) {
-      long wgs = 0;
-      for (int b = 0; b < n_req; ++b) {
-        const ReqDev& r = t->r[b];
-        for (int i0 = 0; i0 < r.n_rows; i0 += tile_rows) {
-          const int n = est_row_pos(r, std::min(i0 + tile_rows, r.n_rows) - 1) / kKvTile + 1;
-          if (n > thr) wgs += (long)((n + chunk_tiles - 1) / chunk_tiles) * n_kv_heads;
-        }
-      }
-      if (wgs >= 512) break;
+    // query-head groups of up to four wavefronts run two workgroups per compute unit, wider ones one
+    const int slots = (n_q_heads / n_kv_heads <= 4 ? 2 : 1) * 256;
+    float best = price_split(t, n_kv_heads, n_q_heads, tile_rows, 0, slots);
+    for (int c : {16, 24, 32, 48, 64, 96, 128}) {
+      const float p = price_split(t, n_kv_heads, n_q_heads, tile_rows, c, slots);
+      if (p < 0.97f * best) { best = p; chunk_tiles = c; }     // a split has to pay for itself
     }
+    if (chunk_tiles == 0) return attention_no_split();
   }
   const int max_tiles = (max_pos + kKvTile - 1) / kKvTile;
   const int n_chunks = (max_tiles + chunk_tiles - 1) / chunk_tiles;
   if (n_chunks <= 1) return attention_no_split();
-  AttnSplit sp = {n_chunks, chunk_tiles, thr, 0};
+  AttnSplit sp = {n_chunks, chunk_tiles, chunk_tiles, 0};
   return sp;
 }
 
 // the whole plan of a phase whose row counts the host knows: decision, then slots (no capacity limit)
-AttnSplit plan_phase_split(ReqTable* t, int n_kv_heads, int tile_rows, int max_pos) {
-  AttnSplit sp = choose_phase_split(t, n_kv_heads, tile_rows, max_pos);
+AttnSplit plan_phase_split(ReqTable* t, int n_kv_heads, int n_q_heads, int tile_rows, int max_pos) {
+  AttnSplit sp = choose_phase_split(t, n_kv_heads, n_q_heads, tile_rows, max_pos);
   sp.total_slots = assign_split_slots(t, tile_rows, kKvTile, sp.long_thr, sp.n_chunks, 1 << 30);
   if (sp.total_slots == 0) return attention_no_split();
   return sp;
@@ -352,7 +372,7 @@ hipError_t gemm_qkv_any<bf16>(const bf16* a, const bf16* wq, int nq, const bf16*
 // row counts on the device: planned for a nominal selection of a fifth of every segment, with room for twice that;
 // a selection that needs more attends unsplit.
 struct ThresholdSplit { AttnSplit sp[PH_COUNT]; int cap[PH_COUNT]; };
-ThresholdSplit plan_threshold_split(const ReqTable& base, int n_kv_heads, int tile_rows, int max_pos, bool bf16_model) {
+ThresholdSplit plan_threshold_split(const ReqTable& base, int n_kv_heads, int n_q_heads, int tile_rows, int max_pos, bool bf16_model) {
   ThresholdSplit ts;
   for (int p = 0; p < PH_COUNT; ++p) { ts.sp[p] = attention_no_split(); ts.cap[p] = 0; }
   if (!bf16_model) return ts;
@@ -361,7 +381,7 @@ ThresholdSplit plan_threshold_split(const ReqTable& base, int n_kv_heads, int ti
     for (int b = 0; b < t.n_req; ++b)
       if (t.r[b].k > 0) t.r[b].k = std::max(1, t.r[b].S / 5);
     fill_phase_table(&t, p, nullptr, tile_rows);
-    AttnSplit sp = choose_phase_split(&t, n_kv_heads, tile_rows, max_pos);
+    AttnSplit sp = choose_phase_split(&t, n_kv_heads, n_q_heads, tile_rows, max_pos);
     if (sp.n_chunks <= 1) continue;
     for (int b = 0; b < t.n_req; ++b)
       if (t.r[b].k > 0) t.r[b].k = std::min(t.r[b].S, 2 * t.r[b].k);
@@ -400,13 +420,13 @@ rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
   auto enter_phase = [&](Phase ph) -> rc_status {
     if (!on_device[ph]) {
       fill_phase_table(&tabs[ph], ph, cur >= 0 ? &tabs[cur] : nullptr, tile_rows);
-      splits[ph] = d.dtype == RC_BF16 ? plan_phase_split(&tabs[ph], d.n_kv_heads, tile_rows, job.max_pos)
+      splits[ph] = d.dtype == RC_BF16 ? plan_phase_split(&tabs[ph], d.n_kv_heads, d.n_q_heads, tile_rows, job.max_pos)
                                       : attention_no_split();
       if (attention_partial_floats(splits[ph].total_slots, d.n_q_heads) > w.attn_part_floats) {
         // the plan was made for other row counts than the workspace was sized for: attend unsplit
-        assign_split_slots(&tabs[ph], tile_rows, kKvTile, 1 << 24, 1, 0);
         splits[ph] = attention_no_split();
       }
+      if (splits[ph].n_chunks <= 1) assign_split_slots(&tabs[ph], tile_rows, kKvTile, 1 << 24, 1, 0);   // items = tiles
       RC_LAUNCH(PC_TABLES, launch_upload_table(tabs[ph], w.tables + ph, st));
     }
     const int nb = cur >= 0 ? 1 - hbuf : hbuf;
@@ -462,12 +482,19 @@ rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
           // device with every token counted as selected (the bound that sizes all grids from here on) and a
           // one-thread kernel rewrites their counts, row offsets and attention slots from sel_cnt: nothing comes
           // back to the host, the call stays asynchronous.
-          const ThresholdSplit ts = plan_threshold_split(job.base, d.n_kv_heads, tile_rows, job.max_pos, d.dtype == RC_BF16);
+          const ThresholdSplit ts = plan_threshold_split(job.base, d.n_kv_heads, d.n_q_heads, tile_rows, job.max_pos, d.dtype == RC_BF16);
           int phase_before = cur;
           for (int p = PH_C; p <= PH_D; ++p) {
             fill_phase_table(&tabs[p], p, &tabs[phase_before], tile_rows);
             splits[p] = ts.sp[p];
             if (attention_partial_floats(splits[p].total_slots, d.n_q_heads) > w.attn_part_floats) splits[p] = attention_no_split();
+            // work items of the attention grid, as an upper bound over every possible selection: all tiles whole, or
+            // the tiles that stay whole plus as many (tile, chunk) pairs as there are slots
+            assign_split_slots(&tabs[p], tile_rows, kKvTile, splits[p].long_thr, splits[p].n_chunks, 1 << 30);
+            int whole = 0;
+            for (int b = 0; b < n_req; ++b)
+              whole += std::min(tabs[p].r[b].long_tile_start, (tabs[p].r[b].n_rows + tile_rows - 1) / tile_rows);
+            tabs[p].total_items = std::max(tabs[p].total_tiles, whole + splits[p].total_slots);
             RC_LAUNCH(PC_TABLES, launch_upload_table(tabs[p], w.tables + p, st));
             on_device[p] = true;
             phase_before = p;
@@ -505,7 +532,7 @@ rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
                                                          (const T*)job.dst->k_pool[l], gd, d.n_q_heads, job.max_pos,
                                                          w.inf_scratch, st));
     RC_LAUNCH(PC_ATTENTION, attention_dispatch<T>((const T*)w.q, w.row_pos, w.row_req, w.tables + cur, rows,
-                                 tabs[cur].total_tiles, (const T*)job.dst->k_pool[l],
+                                 tabs[cur].total_items, (const T*)job.dst->k_pool[l],
                                  (const T*)job.dst->v_pool[l], gd, d.n_q_heads, (T*)w.o, splits[cur], w.attn_part, st,
                                  scores_from_attention ? w.inf_scratch : nullptr, job.max_pos));
     if (job.any_inf)
@@ -599,7 +626,7 @@ size_t attn_part_need(const Job& job) {
   const bool by_threshold = job.selector == RC_SELECT_THRESHOLD;
   // threshold selector: the row counts of the sparse phase and the one after it are decided on the device
   ThresholdSplit ts{};
-  if (by_threshold) ts = plan_threshold_split(job.base, d.n_kv_heads, tile_rows, job.max_pos, true);
+  if (by_threshold) ts = plan_threshold_split(job.base, d.n_kv_heads, d.n_q_heads, tile_rows, job.max_pos, true);
   for (int p = 0; p < PH_COUNT; ++p) {
     if (by_threshold && p >= PH_C) {
       need = std::max(need, attention_partial_floats(ts.cap[p], d.n_q_heads));
@@ -607,7 +634,7 @@ size_t attn_part_need(const Job& job) {
     }
     ReqTable t = job.base;
     fill_phase_table(&t, p, nullptr, tile_rows);
-    const AttnSplit sp = plan_phase_split(&t, d.n_kv_heads, tile_rows, job.max_pos);
+    const AttnSplit sp = plan_phase_split(&t, d.n_kv_heads, d.n_q_heads, tile_rows, job.max_pos);
     need = std::max(need, attention_partial_floats(sp.total_slots, d.n_q_heads));
   }
   return need;

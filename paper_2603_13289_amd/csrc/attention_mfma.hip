@@ -38,6 +38,7 @@ static constexpr int VROW = BKV * 2 + 16;  // bytes between V^T rows in LDS
 static constexpr int K_TILE_BYTES = BKV * KROW;
 static constexpr int V_TILE_BYTES = DH * VROW;
 static constexpr int ATTN_LDS_BYTES = 2 * (K_TILE_BYTES + V_TILE_BYTES);
+static constexpr int PROW = DH + 16;         // floats between the rows of a partial result (see attention_partial_floats)
 static constexpr int kFragAhead = 4;       // LDS operand fragments in flight ahead of the MFMA that uses them
 static constexpr float kRescaleSlack = 8.f;   // log2 units the running maximum may lead the reference exponent
 
@@ -78,28 +79,46 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   // grid (a longest-first schedule), and with 8 KV heads every XCD (workgroup id mod 8) keeps to one head's K/V.
   const int kvh = (int)blockIdx.x % g.n_kv_heads;
   const int item = (int)blockIdx.x / g.n_kv_heads;
-  if (table) {   // the host's counts may be upper bounds (rows selected on the device): the table has the live ones
-    total_tiles = table->total_tiles;
-    total_rows = table->total_rows;
-  }
-  const int tile = total_tiles - 1 - item / sp.n_chunks;
-  if (tile < 0) return;
-  const int chunk = item % sp.n_chunks;
   const int n_q_heads = g.n_kv_heads * G;
-  int r0, n_valid, seq, split_tile = tile, part_base = 0;   // split_tile < 0: this tile is never split
+  int r0, n_valid, seq, chunk, split_tile, part_base = 0;   // split_tile < 0: this tile is never split
   if (table) {
-    int b = 0;
-    while (b + 1 < table->n_req && tile >= table->r[b + 1].tile_base) ++b;
+    // Work items: requests last to first; inside a request first the query tiles that may be split (one item per
+    // tile and KV chunk), then the whole tiles, late ones first.  The host's counts may be upper bounds
+    // (rows selected on the device): the table has the live ones.
+    if (item >= table->total_items) return;
+    int b = table->n_req - 1;                              // item_base is 0 for the last request and grows towards the first
+    while (b > 0 && item >= table->r[b - 1].item_base) --b;
     const ReqDev& rq = table->r[b];
-    r0 = rq.row_base + (tile - rq.tile_base) * BQ;
+    const int tiles = (rq.n_rows + BQ - 1) / BQ;
+    const int start = min(rq.long_tile_start, tiles);
+    const int j = item - rq.item_base;
+    const int n_split_items = (tiles - start) * sp.n_chunks;
+    int lt;
+    if (j < n_split_items) {
+      // chunk-major: chunk 0 of every such tile (late tiles first), then chunk 1, ...  Tiles whose range ends before a
+      // chunk have nothing to do there; in this order those empty items sit together at the end of each chunk's run
+      // instead of at every n_chunks-th position of the grid (where, for even chunk counts, they kept landing on the
+      // same half of the machine and left the other half with all the work)
+      chunk = j / (tiles - start);
+      lt = tiles - 1 - j % (tiles - start);
+    } else {
+      lt = start - 1 - (j - n_split_items);
+      chunk = 0;
+    }
+    if (lt < 0) return;
+    r0 = rq.row_base + lt * BQ;
     n_valid = min(BQ, rq.row_base + rq.n_rows - r0);
     seq = rq.dst_seq;
-    split_tile = tile - rq.tile_base - rq.long_tile_start;
+    split_tile = lt - rq.long_tile_start;
     part_base = rq.part_base;
   } else {
+    chunk = item / total_tiles;
+    const int tile = total_tiles - 1 - item % total_tiles;
+    if (chunk >= sp.n_chunks) return;
     r0 = tile * BQ;
     n_valid = min(BQ, total_rows - r0);
     seq = fixed_seq;
+    split_tile = tile;
   }
   if (n_valid <= 0) return;
 
@@ -363,7 +382,7 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
     // partial result of this chunk: un-normalised O, running maximum (log2 domain) and sum
     const size_t slot = ((size_t)(part_base + split_tile * sp.n_chunks + chunk) * n_q_heads + head) * BQ + ql;
     if (half == 0) part_ml[slot] = make_float2(m_run, l_tot);
-    float* po = part_o + slot * DH;
+    float* po = part_o + slot * PROW;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -436,7 +455,7 @@ attn_merge_kernel(const int* __restrict__ row_pos, const int* __restrict__ row_r
     for (int u = 0; u < 4; ++u) {
       const size_t slot = slot0 + (c + u) * cstride;
       ml[u] = part_ml[slot];
-      o[u] = *reinterpret_cast<const float2*>(part_o + slot * DH + 2 * lane);
+      o[u] = *reinterpret_cast<const float2*>(part_o + slot * PROW + 2 * lane);
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -451,7 +470,7 @@ attn_merge_kernel(const int* __restrict__ row_pos, const int* __restrict__ row_r
     const float2 ml = part_ml[slot];
     const float wgt = (ml.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml.x - m);
     l += ml.y * wgt;
-    const float2 o = *reinterpret_cast<const float2*>(part_o + slot * DH + 2 * lane);
+    const float2 o = *reinterpret_cast<const float2*>(part_o + slot * PROW + 2 * lane);
     o0 += o.x * wgt;
     o1 += o.y * wgt;
   }
@@ -465,17 +484,24 @@ static int g_force_chunk_tiles = 0;   // 0: by shape; > 0: this many KV tiles pe
 void set_attention_chunk_tiles(int t) { g_force_chunk_tiles = t; }
 int attention_forced_chunk_tiles() { return g_force_chunk_tiles; }
 
+// Partial results: per (slot, head, query row) DH un-normalised output floats, stored PROW floats apart, and one
+// (reference exponent, sum) pair behind all of them.  The row pitch is not a power of two on purpose: with 512-byte
+// rows the slots of one KV chunk of successive query tiles lie a multiple of 1 MiB apart whenever the chunk count is
+// even, and the workgroups that finish together (same chunk, neighbouring tiles) then write to the same memory
+// channels (measured: even chunk counts ran the split layers up to twice as slow).
 size_t attention_partial_floats(int total_slots, int n_q_heads) {
-  return (size_t)total_slots * n_q_heads * BQ * (DH + 2);
+  return (size_t)total_slots * n_q_heads * BQ * (PROW + 2);
 }
 
 template <int G>
 static hipError_t launch_g(const bf16* q, const int* row_pos, const ReqTable* table, int fixed_seq, int total_rows,
                            int total_tiles, const bf16* k_pool, const bf16* v_pool, KvGeom g, bf16* out,
                            AttnSplit sp, float* part, float* scores, int scores_len, hipStream_t st) {
-  dim3 grid((unsigned)(total_tiles * sp.n_chunks * g.n_kv_heads));
+  // with a table, total_tiles is the phase's number of work items (ReqTable::total_items, or an upper bound of it)
+  const long items = table ? (long)total_tiles : (long)total_tiles * sp.n_chunks;
+  dim3 grid((unsigned)(items * g.n_kv_heads));
   float* part_o = part;
-  float2* part_ml = reinterpret_cast<float2*>(part + (size_t)sp.total_slots * g.n_kv_heads * G * BQ * DH);
+  float2* part_ml = reinterpret_cast<float2*>(part + (size_t)sp.total_slots * g.n_kv_heads * G * BQ * PROW);
   // more than the 64 KB a kernel gets without asking
   static std::atomic<unsigned long long> told_scores{0}, told_plain{0};
   hipError_t e = scores ? allow_dynamic_lds((const void*)attn_mfma_kernel<G, true>, ATTN_LDS_BYTES, told_scores)
@@ -511,7 +537,7 @@ hipError_t launch_attention_bf16(const bf16* q, const int* row_pos, const int* r
                                          n_q_heads, out, st);
   }
   if (e != hipSuccess || sp.n_chunks == 1) return e;
-  const float2* part_ml = reinterpret_cast<const float2*>(part + (size_t)sp.total_slots * n_q_heads * BQ * DH);
+  const float2* part_ml = reinterpret_cast<const float2*>(part + (size_t)sp.total_slots * n_q_heads * BQ * PROW);
   const int items = total_rows * n_q_heads;
   attn_merge_kernel<<<(items + 3) / 4, 256, 0, st>>>(row_pos, row_req, table, total_rows, n_q_heads, sp, part, part_ml,
                                                      out, scores ? influence_pairs(scores, total_rows, n_q_heads, scores_len) : nullptr);

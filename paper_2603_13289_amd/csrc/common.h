@@ -126,6 +126,7 @@ struct ReqDev {
   int dst_seq, src_seq, src_offset, rot_delta;           // rot_delta valid when keys are rotated
   int sel_base, score_base, tile_base, k_is_pre_rope;
   int long_tile_start, part_base;   // attention KV split: first local tile that may be split, its slot base
+  int item_base, pad1;              // attention grid: first work item of this request (requests are served last to first)
   const void* x_prefix;
   const void* h_start;
   const void* x_suffix;
@@ -141,7 +142,8 @@ constexpr int kRowNoCacheWrite = 0x100;
 static_assert(RC_MAX_REQ <= kRowReqMask + 1, "request index must fit the mask");
 
 struct ReqTable {
-  int n_req, total_rows, total_tiles, pad;
+  int n_req, total_rows, total_tiles;
+  int total_items;   // attention grid: work items = whole query tiles + (query tile, KV chunk) pairs of the tiles that may be split
   ReqDev r[RC_MAX_REQ];
 };
 
@@ -210,13 +212,25 @@ __host__ __device__ inline int assign_split_slots(ReqTable* t, int tile_rows, in
     r.part_base = base;
     base += (tiles - start) * n_chunks;
   }
-  if (n_chunks <= 1 || base == 0 || base > capacity) {
+  const bool off = n_chunks <= 1 || base == 0 || base > capacity;
+  if (off) {
+    base = 0;
     for (int b = 0; b < t->n_req; ++b) {
       t->r[b].long_tile_start = 1 << 30;
       t->r[b].part_base = 0;
     }
-    return 0;
   }
+  // the attention grid: requests last to first, inside a request the tiles that may be split (the late, long ones:
+  // one item per KV chunk) before the whole ones
+  int items = 0;
+  for (int b = t->n_req - 1; b >= 0; --b) {
+    ReqDev& r = t->r[b];
+    const int tiles = (r.n_rows + tile_rows - 1) / tile_rows;
+    const int start = r.long_tile_start < tiles ? r.long_tile_start : tiles;
+    r.item_base = items;
+    items += (tiles - start) * (off ? 1 : n_chunks) + start;
+  }
+  t->total_items = items;
   return base;
 }
 
@@ -306,6 +320,8 @@ int attention_tile_rows(int dtype, int n_q_heads, int n_kv_heads);  // query row
 
 // bf16 attention with an optional split of every query tile's KV range into chunks (partial results
 // in `part`, merged by a second kernel).  part == nullptr: no split.
+// With a table, total_tiles is the number of work items of the launch (ReqTable::total_items as assign_split_slots
+// left it, or an upper bound when the table is finalized on the device).
 // A query tile whose KV range spans more than long_thr tiles is cut into chunks of chunk_tiles tiles;
 // n_chunks is the grid's chunk dimension (1: no split at all), total_slots the (tile, chunk) slots of
 // partial results the plan may touch.

@@ -238,8 +238,12 @@ def test_same_prefix_reproduces_full_prefill_at_full_size(run):
     torch.cuda.synchronize()
     # identical inputs and weights: the fresh values differ from the stored ones only by bf16 rounding
     assert float(scores.max()) <= 2e-4
+    # two bf16 computations of the same quantity (different row sets per launch, so different tile schedules, KV
+    # splits and summation orders through 32 layers), each within the bf16 tolerance of the exact result: they are
+    # within twice that of each other
+    tol = 2.0 * TOL["bf16"]
     for l in range(sh.n_layers):
         ek = rel_err(to_np(dst.k[l]), to_np(full.k[l]))
         ev = rel_err(to_np(dst.v[l]), to_np(full.v[l]))
-        assert ek <= TOL["bf16"] and ev <= TOL["bf16"], (l, ek, ev)
-    assert rel_err(to_np(logits), to_np(lg_full)) <= TOL["bf16"]
+        assert ek <= tol and ev <= tol, (l, ek, ev)
+    assert rel_err(to_np(logits), to_np(lg_full)) <= tol
