@@ -37,7 +37,8 @@ static constexpr int KROW = DH * 2 + 16;   // bytes between K rows in LDS
 static constexpr int VROW = BKV * 2 + 16;  // bytes between V^T rows in LDS
 static constexpr int K_TILE_BYTES = BKV * KROW;
 static constexpr int V_TILE_BYTES = DH * VROW;
-static constexpr int ATTN_LDS_BYTES = 2 * (K_TILE_BYTES + V_TILE_BYTES);
+static constexpr int kLdsTableEntries = 2048;   // block-table entries of the workgroup's KV range kept in LDS (paged caches)
+static constexpr int ATTN_LDS_BYTES = 2 * (K_TILE_BYTES + V_TILE_BYTES) + kLdsTableEntries * 4;
 static constexpr int PROW = DH + 16;         // floats between the rows of a partial result (see attention_partial_floats)
 static constexpr int kFragAhead = 4;       // LDS operand fragments in flight ahead of the MFMA that uses them
 static constexpr float kRescaleSlack = 8.f;   // log2 units the running maximum may lead the reference exponent
@@ -165,6 +166,19 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
     kbase = k_pool + o + kch * 8;
     vbase = v_pool + o;
   }
+  // Paged cache with power-of-two blocks: the block ids of this workgroup's KV range are copied into LDS once
+  // (lds_tab, filled below when the range is known), so that a row's address costs one LDS read instead of a
+  // block-table load from memory in front of every K/V load (a dependent pair of global loads has twice the
+  // latency the one-tile look-ahead of the fetches has to cover).  Ranges with more blocks than fit, and block
+  // sizes that are no power of two, take the general path.
+  int* const lds_tab = reinterpret_cast<int*>(lds_attn + 2 * (K_TILE_BYTES + V_TILE_BYTES));
+  bool tab_in_lds = false;
+  int tab_first = 0;                               // block index of lds_tab[0]
+  auto row_offset = [&](int pos) -> size_t {
+    if (!tab_in_lds) return kv_row_offset(g, seq, pos, kvh);
+    const int blk = lds_tab[(pos >> g.bs_shift) - tab_first];
+    return (((size_t)blk * g.n_kv_heads + kvh) * g.block_size + (pos & (g.block_size - 1))) * (size_t)DH;
+  };
   // the tile fetched during step t is staged during step t + 1 and multiplied in step t + 2
   uint4 rk[KPER], rv[VPER][4];
   auto fetch_k = [&](int kv0) {
@@ -175,7 +189,7 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
       const int pos = kv0 + row;
       rk[i] = make_uint4(0, 0, 0, 0);
       if (row < BKV && (full || pos <= last_pos)) {
-        const bf16* src = contig ? kbase + (size_t)pos * DH : k_pool + kv_row_offset(g, seq, pos, kvh) + kch * 8;
+        const bf16* src = contig ? kbase + (size_t)pos * DH : k_pool + row_offset(pos) + kch * 8;
         rk[i] = *reinterpret_cast<const uint4*>(src);
       }
     }
@@ -190,7 +204,7 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
         const int pos = kv0 + vquad * 4 + kk;
         rv[i][kk] = make_uint4(0, 0, 0, 0);
         if (dch < 16 && (full || pos <= last_pos)) {
-          const bf16* src = contig ? vbase + (size_t)pos * DH + dch * 8 : v_pool + kv_row_offset(g, seq, pos, kvh) + dch * 8;
+          const bf16* src = contig ? vbase + (size_t)pos * DH + dch * 8 : v_pool + row_offset(pos) + dch * 8;
           rv[i][kk] = *reinterpret_cast<const uint4*>(src);
         }
       }
@@ -239,6 +253,18 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   const int t_begin = is_split ? chunk * sp.chunk_tiles : 0;
   const int t_end = is_split ? min(n_kv_tiles, t_begin + sp.chunk_tiles) : n_kv_tiles;
   if (t_begin >= t_end || (!is_split && chunk != 0)) return;   // nothing for this workgroup (uniform)
+  if (!contig && g.bs_shift >= 0) {
+    tab_first = (t_begin * BKV) >> g.bs_shift;
+    const int n_blk = min(((t_end * BKV - 1) >> g.bs_shift), g.max_blocks - 1) - tab_first + 1;
+    if (n_blk <= kLdsTableEntries) {   // uniform
+      for (int i = tid; i < n_blk; i += NT) {
+        const int blk = g.block_table[(size_t)seq * g.max_blocks + tab_first + i];
+        lds_tab[i] = min(max(blk, 0), g.n_blocks - 1);
+      }
+      tab_in_lds = true;
+      __syncthreads();
+    }
+  }
   const std::integral_constant<int, 0> buf0;
   const std::integral_constant<int, 1> buf1;
   // prologue: the first tile goes to buffer 0, the second one is on its way in registers
