@@ -172,16 +172,18 @@ int est_row_pos(const ReqDev& r, int i) {
 // A workgroup serves one (query tile, KV head[, KV chunk]) and costs its KV tiles plus a fixed part (prologue, first
 // tile's latency); two workgroups share a compute unit.  Candidates (no split, chunks of 16 ... 128 KV tiles; a tile is
 // split when its range is longer than one chunk) are priced by a list-scheduling estimate: the busier of "the longest
-// workgroup" and "all work spread over the slots", plus half a longest workgroup for the ragged end of the launch,
+// workgroup" and "all work spread over the slots", plus half a longest workgroup for the ragged end of a launch with
+// more workgroups than slots,
 // plus the merge pass over the partial results of the split rows.  Units: one KV tile step of one slot (~2.2 us).
 // Measured on the 2048 + 16384-token workload: its sparse layers (1639 selected rows, up to 288 KV tiles each) take
 // 520 us unsplit and 182 + 33 us with chunks of 32; the dense layer and the short prefix-only layers are best left whole.
-constexpr float kWgFixedSteps = 3.f;       // fixed cost of a workgroup
+constexpr float kWgFixedSteps = 4.f;       // fixed cost of a workgroup
 constexpr float kMergeFixedSteps = 3.5f;   // launch of the merge kernel
 constexpr float kMergeBytesPerStep = 8.8e6f;
 
 float price_split(const ReqTable* t, int n_kv_heads, int n_q_heads, int tile_rows, int chunk /* 0: none */, int slots) {
   double work = 0.0, merge_bytes = 0.0;
+  long wgs = 0;
   int longest = 0;
   for (int b = 0; b < t->n_req; ++b) {
     const ReqDev& r = t->r[b];
@@ -191,16 +193,19 @@ float price_split(const ReqTable* t, int n_kv_heads, int n_q_heads, int tile_row
       if (chunk > 0 && n > chunk) {
         const int parts = (n + chunk - 1) / chunk;
         work += (double)(n + kWgFixedSteps * parts) * n_kv_heads;
+        wgs += (long)parts * n_kv_heads;
         longest = std::max(longest, chunk);
         merge_bytes += (double)rows * n_q_heads * parts * (128 + 2) * 4;
       } else {
         work += (double)(n + kWgFixedSteps) * n_kv_heads;
+        wgs += n_kv_heads;
         longest = std::max(longest, n);
       }
     }
   }
   const float l = longest + kWgFixedSteps;
-  float cost = std::max(l, (float)(work / slots)) + 0.5f * l;
+  float cost = std::max(l, (float)(work / slots));
+  if (wgs > slots) cost += 0.5f * l;     // later rounds of workgroups end raggedly; a launch that fits the slots does not
   if (merge_bytes > 0.0) cost += kMergeFixedSteps + (float)(merge_bytes / kMergeBytesPerStep);
   return cost;
 }
@@ -324,11 +329,11 @@ template <typename T>
 hipError_t attention_dispatch(const T* q, const int* row_pos, const int* row_req, const ReqTable* table,
                               int total_rows, int total_tiles, const T* k_pool, const T* v_pool, KvGeom g,
                               int n_q_heads, T* out, AttnSplit sp, float* part, hipStream_t st, float* scores,
-                              int scores_len);
+                              int scores_len, int merge_rows);
 template <>
 hipError_t attention_dispatch<float>(const float* q, const int* row_pos, const int* row_req, const ReqTable* table,
                                      int total_rows, int total_tiles, const float* k_pool, const float* v_pool,
-                                     KvGeom g, int n_q_heads, float* out, AttnSplit, float*, hipStream_t st, float*, int) {
+                                     KvGeom g, int n_q_heads, float* out, AttnSplit, float*, hipStream_t st, float*, int, int) {
   return launch_attention<float>(q, row_pos, row_req, table, 0, total_rows, total_tiles, k_pool, v_pool, g,
                                  n_q_heads, out, st);
 }
@@ -336,9 +341,9 @@ template <>
 hipError_t attention_dispatch<bf16>(const bf16* q, const int* row_pos, const int* row_req, const ReqTable* table,
                                     int total_rows, int total_tiles, const bf16* k_pool, const bf16* v_pool,
                                     KvGeom g, int n_q_heads, bf16* out, AttnSplit sp, float* part, hipStream_t st,
-                                    float* scores, int scores_len) {
+                                    float* scores, int scores_len, int merge_rows) {
   return launch_attention_bf16(q, row_pos, row_req, table, 0, total_rows, total_tiles, k_pool, v_pool, g, n_q_heads,
-                               out, sp, part, st, scores, scores_len);
+                               out, sp, part, st, scores, scores_len, merge_rows);
 }
 
 template <typename T>
@@ -534,7 +539,7 @@ rc_status run_job(Job& job, Workspace& w, hipStream_t st) {
     RC_LAUNCH(PC_ATTENTION, attention_dispatch<T>((const T*)w.q, w.row_pos, w.row_req, w.tables + cur, rows,
                                  tabs[cur].total_items, (const T*)job.dst->k_pool[l],
                                  (const T*)job.dst->v_pool[l], gd, d.n_q_heads, (T*)w.o, splits[cur], w.attn_part, st,
-                                 scores_from_attention ? w.inf_scratch : nullptr, job.max_pos));
+                                 scores_from_attention ? w.inf_scratch : nullptr, job.max_pos, tabs[cur].total_merge_rows));
     if (job.any_inf)
       RC_LAUNCH(PC_INFLUENCE, launch_influence_finish(w.row_pos, w.row_req, rows, d.n_q_heads, job.max_pos, job.inf,
                                                       w.inf_scratch, scores_from_attention, st));

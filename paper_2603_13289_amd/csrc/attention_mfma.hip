@@ -445,18 +445,27 @@ attn_merge_kernel(const int* __restrict__ row_pos, const int* __restrict__ row_r
                   const float2* __restrict__ part_ml, bf16* __restrict__ out, float2* __restrict__ score_ml) {
   const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  if (table) total_rows = table->total_rows;
-  if (item >= total_rows * n_q_heads) return;
-  const int r = item / n_q_heads, head = item - r * n_q_heads;
-  int split_tile, ql, part_base = 0, tile_last_row;
+  int r, head, split_tile, ql, part_base = 0, tile_last_row;
   if (table) {
-    const ReqDev& rq = table->r[row_req[r] & kRowReqMask];
-    const int lt = (r - rq.row_base) / BQ;
+    // items run over the rows of the tiles that may be split only (the late tiles of every request)
+    const int mr = item / n_q_heads;
+    head = item - mr * n_q_heads;
+    if (mr >= table->total_merge_rows) return;
+    int b = 0;
+    while (b + 1 < table->n_req && mr >= table->r[b + 1].merge_base) ++b;
+    const ReqDev& rq = table->r[b];
+    const int local = min(rq.long_tile_start, 1 << 20) * BQ + (mr - rq.merge_base);     // row inside the request
+    if (local >= rq.n_rows) return;
+    r = rq.row_base + local;
+    const int lt = local / BQ;
     split_tile = lt - rq.long_tile_start;
-    ql = (r - rq.row_base) % BQ;
+    ql = local % BQ;
     part_base = rq.part_base;
     tile_last_row = min(rq.row_base + (lt + 1) * BQ, rq.row_base + rq.n_rows) - 1;
   } else {
+    if (item >= total_rows * n_q_heads) return;
+    r = item / n_q_heads;
+    head = item - r * n_q_heads;
     split_tile = r / BQ;
     ql = r % BQ;
     tile_last_row = min((split_tile + 1) * BQ, total_rows) - 1;
@@ -546,7 +555,7 @@ static hipError_t launch_g(const bf16* q, const int* row_pos, const ReqTable* ta
 hipError_t launch_attention_bf16(const bf16* q, const int* row_pos, const int* row_req, const ReqTable* table,
                                  int fixed_seq, int total_rows, int total_tiles, const bf16* k_pool,
                                  const bf16* v_pool, KvGeom g, int n_q_heads, bf16* out, AttnSplit sp, float* part,
-                                 hipStream_t st, float* scores, int scores_len) {
+                                 hipStream_t st, float* scores, int scores_len, int merge_rows) {
   if (total_rows <= 0) return hipSuccess;
   const int G = n_q_heads / g.n_kv_heads;
   if (!part || sp.total_slots <= 0) sp = attention_no_split();
@@ -564,7 +573,9 @@ hipError_t launch_attention_bf16(const bf16* q, const int* row_pos, const int* r
   }
   if (e != hipSuccess || sp.n_chunks == 1) return e;
   const float2* part_ml = reinterpret_cast<const float2*>(part + (size_t)sp.total_slots * n_q_heads * BQ * PROW);
-  const int items = total_rows * n_q_heads;
+  // with a table, merge_rows (the rows of the tiles that may be split, or an upper bound) sizes the merge grid
+  const int items = (table ? merge_rows : total_rows) * n_q_heads;
+  if (items <= 0) return hipSuccess;
   attn_merge_kernel<<<(items + 3) / 4, 256, 0, st>>>(row_pos, row_req, table, total_rows, n_q_heads, sp, part, part_ml,
                                                      out, scores ? influence_pairs(scores, total_rows, n_q_heads, scores_len) : nullptr);
   return hipGetLastError();

@@ -126,7 +126,8 @@ struct ReqDev {
   int dst_seq, src_seq, src_offset, rot_delta;           // rot_delta valid when keys are rotated
   int sel_base, score_base, tile_base, k_is_pre_rope;
   int long_tile_start, part_base;   // attention KV split: first local tile that may be split, its slot base
-  int item_base, pad1;              // attention grid: first work item of this request (requests are served last to first)
+  int item_base;                    // attention grid: first work item of this request (requests are served last to first)
+  int merge_base;                   // merge grid: rows of the tiles that may be split, counted over the requests before this one
   const void* x_prefix;
   const void* h_start;
   const void* x_suffix;
@@ -144,6 +145,8 @@ static_assert(RC_MAX_REQ <= kRowReqMask + 1, "request index must fit the mask");
 struct ReqTable {
   int n_req, total_rows, total_tiles;
   int total_items;   // attention grid: work items = whole query tiles + (query tile, KV chunk) pairs of the tiles that may be split
+  int total_merge_rows;   // rows of the tiles that may be split (the merge pass visits only those)
+  int pad_[3];
   ReqDev r[RC_MAX_REQ];
 };
 
@@ -231,6 +234,14 @@ __host__ __device__ inline int assign_split_slots(ReqTable* t, int tile_rows, in
     items += (tiles - start) * (off ? 1 : n_chunks) + start;
   }
   t->total_items = items;
+  int mrows = 0;
+  for (int b = 0; b < t->n_req; ++b) {
+    ReqDev& r = t->r[b];
+    r.merge_base = mrows;
+    const long first = (long)r.long_tile_start * tile_rows;
+    if (first < r.n_rows) mrows += r.n_rows - (int)first;
+  }
+  t->total_merge_rows = mrows;
   return base;
 }
 
@@ -333,7 +344,7 @@ size_t attention_partial_floats(int total_slots, int n_q_heads);
 hipError_t launch_attention_bf16(const bf16* q, const int* row_pos, const int* row_req, const ReqTable* table,
                                  int fixed_seq, int total_rows, int total_tiles, const bf16* k_pool,
                                  const bf16* v_pool, KvGeom g, int n_q_heads, bf16* out, AttnSplit sp, float* part,
-                                 hipStream_t st, float* scores = nullptr, int scores_len = 0);
+                                 hipStream_t st, float* scores = nullptr, int scores_len = 0, int merge_rows = 0);
 
 template <typename T>
 hipError_t launch_vdev_score(const T* v_fresh, int fresh_row_stride, const T* v_pool, KvGeom g,
