@@ -170,13 +170,14 @@ int est_row_pos(const ReqDev& r, int i) {
 // per-request slot assignment is left to assign_split_slots.  n_chunks == 1: no split.
 //
 // A workgroup serves one (query tile, KV head[, KV chunk]) and costs its KV tiles plus a fixed part (prologue, first
-// tile's latency); two workgroups share a compute unit.  Candidates (no split, chunks of 16 ... 128 KV tiles; a tile is
+// tile's latency); two workgroups share a compute unit.  Candidates (no split, chunks of 4 ... 128 KV tiles; a tile is
 // split when its range is longer than one chunk) are priced by a list-scheduling estimate: the busier of "the longest
 // workgroup" and "all work spread over the slots", plus half a longest workgroup for the ragged end of a launch with
 // more workgroups than slots,
 // plus the merge pass over the partial results of the split rows.  Units: one KV tile step of one slot (~2.2 us).
 // Measured on the 2048 + 16384-token workload: its sparse layers (1639 selected rows, up to 288 KV tiles each) take
 // 520 us unsplit and 182 + 33 us with chunks of 32; the dense layer and the short prefix-only layers are best left whole.
+// A decoding step (one row per sequence, 8 KV heads, 80 KV tiles) gets chunks of 4: 160 workgroups instead of 40.
 constexpr float kWgFixedSteps = 4.f;       // fixed cost of a workgroup
 constexpr float kMergeFixedSteps = 3.5f;   // launch of the merge kernel
 constexpr float kMergeBytesPerStep = 8.8e6f;
@@ -219,7 +220,7 @@ AttnSplit choose_phase_split(const ReqTable* t, int n_kv_heads, int n_q_heads, i
     // query-head groups of up to four wavefronts run two workgroups per compute unit, wider ones one
     const int slots = (n_q_heads / n_kv_heads <= 4 ? 2 : 1) * 256;
     float best = price_split(t, n_kv_heads, n_q_heads, tile_rows, 0, slots);
-    for (int c : {16, 24, 32, 48, 64, 96, 128}) {
+    for (int c : {4, 8, 12, 16, 24, 32, 48, 64, 96, 128}) {
       const float p = price_split(t, n_kv_heads, n_q_heads, tile_rows, c, slots);
       if (p < 0.97f * best) { best = p; chunk_tiles = c; }     // a split has to pay for itself
     }
