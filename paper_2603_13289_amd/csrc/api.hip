@@ -220,7 +220,14 @@ AttnSplit choose_phase_split(const ReqTable* t, int n_kv_heads, int n_q_heads, i
     // query-head groups of up to four wavefronts run two workgroups per compute unit, wider ones one
     const int slots = (n_q_heads / n_kv_heads <= 4 ? 2 : 1) * 256;
     float best = price_split(t, n_kv_heads, n_q_heads, tile_rows, 0, slots);
+    // chunks shorter than 16 tiles only for phases of a handful of query tiles (decoding steps): with a few hundred
+    // workgroups already there, the model's fixed costs are too coarse to tell a gain of a few tile steps from the
+    // price of the merge pass (prefix-only layers of 1024 rows: 36 us whole, 30 + 13 us in chunks of 8)
+    long whole_wgs = 0;
+    for (int b = 0; b < t->n_req; ++b) whole_wgs += (long)((t->r[b].n_rows + tile_rows - 1) / tile_rows) * n_kv_heads;
+    const int min_chunk = whole_wgs * 8 <= slots ? 4 : 16;
     for (int c : {4, 8, 12, 16, 24, 32, 48, 64, 96, 128}) {
+      if (c < min_chunk) continue;
       const float p = price_split(t, n_kv_heads, n_q_heads, tile_rows, c, slots);
       if (p < 0.97f * best) { best = p; chunk_tiles = c; }     // a split has to pay for itself
     }
