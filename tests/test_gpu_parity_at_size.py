@@ -13,6 +13,7 @@ import numpy as np
 import pytest
 
 from oracle import relay_oracle as R
+from synth import make_influence
 from tests.harness import TOL, build_case, hip_relay, oracle_relay, rel_err, row_rel_err
 
 pytestmark = pytest.mark.gpu
@@ -64,3 +65,25 @@ def test_headline_token_counts_match_oracle_end_to_end(name):
         assert np.array_equal(forced.sel[b], want.sel_idx)
     worst = _compare(case, forced, wants)
     print(f"{name}: worst per-tensor error {worst:.2e}")
+
+
+def test_headline_token_counts_with_the_threshold_selector():
+    """The paper's own selector (Eq. 5-10) at the headline token counts.  The number of selected rows is only known on the
+    device: every grid after the selection is sized for the bound (all 4096 tokens), the kernels read the live count
+    from the device table and the GEMMs rebuild their schedule for it.  The selection must equal the oracle's selector
+    applied to the library's own scores bit for bit, and every layer's K and V and the logits must equal the oracle
+    run on exactly those rows."""
+    case = build_case("mistral7b_4k_trunc")
+    rq = case.reqs[0]
+    s_inf = [make_influence(case.w, rq.S, 0)]
+    th = (1.5, 1.45, 16)
+    run = hip_relay(case, thresholds=th, s_inf=s_inf)
+    sel = R.final_selection(run.scores[0], s_inf[0], *th)
+    assert np.array_equal(run.sel[0], sel)
+    # a count that is neither trivial nor a multiple of the 256-row GEMM tile or the 32-row attention tile
+    assert 64 < len(sel) < rq.S // 2, len(sel)
+    assert sel[-1] == rq.S - 1        # k_suf > 0 always selects the last token: the twin-row case of the logits row
+    rq.k = len(sel)
+    want = oracle_relay(case, 0, forced_idx=sel)
+    worst = _compare(case, run, [want])
+    print(f"threshold selector: {len(sel)} of {rq.S} tokens selected, worst per-tensor error {worst:.2e}")
