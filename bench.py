@@ -107,6 +107,15 @@ def machine_ceilings():
     ev1.record()
     torch.cuda.synchronize()
     copy_gbs = 5 * 2 * n / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    # the same copy in launches of 20 MB (read + write = 40 MB, what one rmsnorm or rope + scatter launch of the
+    # workload moves), walking through the buffer so that no launch finds its data in a cache
+    piece = 20 << 20
+    ev0.record()
+    for i in range(48):
+        rc.rc_ceiling_stream_copy(src[i * piece:], dst[i * piece:], piece)
+    ev1.record()
+    torch.cuda.synchronize()
+    small_gbs = 48 * 2 * piece / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
     del src, dst
     n_cu = torch.cuda.get_device_properties(0).multi_processor_count
     out = torch.empty(rc.rc_ceiling_mfma_loop_out_bytes(n_cu) // 4, dtype=torch.float32, device="cuda")
@@ -117,9 +126,9 @@ def machine_ceilings():
     ev1.record()
     torch.cuda.synchronize()
     mfma_tf = flops / (ev0.elapsed_time(ev1) * 1e-3) / 1e12
-    return {"stream_copy_gb_s": copy_gbs, "mfma_loop_bf16_tflop_s": mfma_tf,
-            "note": "this board: 1 GiB copy with 16-byte accesses; 16x16x32 bf16 MFMAs on register operands, "
-                    "8 wavefronts per CU, pseudo-random operands"}
+    return {"stream_copy_gb_s": copy_gbs, "stream_copy_20mb_launches_gb_s": small_gbs, "mfma_loop_bf16_tflop_s": mfma_tf,
+            "note": "this board: 1 GiB copy with 16-byte accesses, in one launch and in back-to-back launches of 20 MB; "
+                    "16x16x32 bf16 MFMAs on register operands, 8 wavefronts per CU, pseudo-random operands"}
 
 
 def cpu_baseline(w, budget_s=20.0):
