@@ -87,3 +87,21 @@ def test_headline_token_counts_with_the_threshold_selector():
     want = oracle_relay(case, 0, forced_idx=sel)
     worst = _compare(case, run, [want])
     print(f"threshold selector: {len(sel)} of {rq.S} tokens selected, worst per-tensor error {worst:.2e}")
+
+
+def test_threshold_selection_larger_than_the_planned_attention_split():
+    """The attention KV split of the sparse layers is planned on the host for a nominal selection (a fifth of the
+    segment, partial-result slots for twice that) because the real count only exists on the device.  A low cut selects
+    more than the slots allow: the device-side table then switches the split off for those layers and every query tile
+    attends its whole range in one workgroup.  Same comparison as above."""
+    case = build_case("mistral7b_4k_trunc")
+    rq = case.reqs[0]
+    th = (0.6, 1e6, 0)
+    run = hip_relay(case, thresholds=th)
+    sel = R.final_selection(run.scores[0], None, *th)
+    assert np.array_equal(run.sel[0], sel)
+    assert 2 * (rq.S // 5) < len(sel) < rq.S, len(sel)
+    rq.k = len(sel)
+    want = oracle_relay(case, 0, forced_idx=sel)
+    worst = _compare(case, run, [want])
+    print(f"low cut: {len(sel)} of {rq.S} tokens selected, worst per-tensor error {worst:.2e}")
