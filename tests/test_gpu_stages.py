@@ -257,6 +257,29 @@ def test_sparse_attention_wide_score_range(case, split):
         assert rel_err(got, np.repeat(want_mean, hq // hkv, axis=1)) <= 1e-2
 
 
+@pytest.mark.parametrize("split", [False, True])
+def test_sparse_attention_over_more_blocks_than_the_lds_table_holds(split):
+    """A paged cache whose sequence spans 2063 blocks of 16 tokens.  A workgroup keeps the block-table slice of its KV
+    range in LDS when it has at most 2048 entries; an unsplit query tile near the end of this sequence needs more and
+    looks its blocks up in global memory instead.  With a workspace the range is cut into chunks whose slices fit."""
+    rc = _rc()
+    hq, hkv, dh, T = 8, 2, 128, 33001
+    cache, ks, vs = _cache("bf16", hkv, dh, [5, T], 16, "att_long")
+    g = stream_rng("stage", "att_long_pos")
+    pos = np.sort(np.concatenate([np.arange(0, 33), g.choice(np.arange(33, T), size=30, replace=False), [T - 1]]))
+    n = len(pos)
+    q = _rand((n, hq, dh), "bf16", "att_long_q", 0.5)
+    out = torch.zeros((n, hq, dh), dtype=torch.bfloat16, device="cuda")
+    ws = None
+    if split:
+        assert rc.rc_sparse_attention_workspace_bytes(n, hq, cache.layer(0)) > 0
+        ws = rc.alloc_workspace(rc.rc_sparse_attention_workspace_bytes(n, hq, cache.layer(0)))
+    rc.rc_sparse_attention(_up(q, "bf16"), torch.from_numpy(pos.astype(np.int32)).cuda(), n, hq, cache.layer(0), 1, out, ws)
+    torch.cuda.synchronize()
+    want = R.causal_gqa_attention(q.astype(np.float64), pos, ks[1].astype(np.float64), vs[1].astype(np.float64))
+    assert rel_err(to_np(out), want) <= 1e-2
+
+
 # ------------------------------------------------------------------ K3
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("m,n,k", [(1, 64, 64), (51, 192, 256), (129, 1000, 688), (300, 257, 1408), (1639, 512, 1024),
