@@ -174,15 +174,27 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   int* const lds_tab = reinterpret_cast<int*>(lds_attn + 2 * (K_TILE_BYTES + V_TILE_BYTES));
   bool tab_in_lds = false;
   int tab_first = 0;                               // block index of lds_tab[0]
+  // lds_tab[i] = block id * n_kv_heads + this workgroup's KV head: the pool row of a position is then a shift and an or
   auto row_offset = [&](int pos) -> size_t {
     if (!tab_in_lds) return kv_row_offset(g, seq, pos, kvh);
-    const int blk = lds_tab[(pos >> g.bs_shift) - tab_first];
-    return (((size_t)blk * g.n_kv_heads + kvh) * g.block_size + (pos & (g.block_size - 1))) * (size_t)DH;
+    const unsigned e = (unsigned)lds_tab[(pos >> g.bs_shift) - tab_first];
+    return ((((size_t)e) << g.bs_shift) | (unsigned)(pos & (g.block_size - 1))) * (size_t)DH;
   };
   // the tile fetched during step t is staged during step t + 1 and multiplied in step t + 2
   uint4 rk[KPER], rv[VPER][4];
+  // contiguous cache: this thread's first K chunk and V block of KV tile 0; a full tile is then fetched at constant
+  // offsets from one pointer per operand, without per-row position arithmetic or predicates
+  const bf16* const kthread = contig ? kbase + (size_t)krow0 * DH : nullptr;
+  const bf16* const vthread = contig ? vbase + (size_t)(vquad * 4) * DH + vdch0 * 8 : nullptr;
+  constexpr bool kFastFetch = KPER * KSTEP == BKV && VPER * KSTEP == 16;   // every thread owns whole rows / blocks
   auto fetch_k = [&](int kv0) {
     const bool full = kv0 + BKV - 1 <= last_pos;   // uniform: only a query tile's last KV tile can be ragged
+    if (kFastFetch && contig && full) {
+      const bf16* kp = kthread + (size_t)kv0 * DH;
+#pragma unroll
+      for (int i = 0; i < KPER; ++i) rk[i] = *reinterpret_cast<const uint4*>(kp + (size_t)i * KSTEP * DH);
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < KPER; ++i) {
       const int row = krow0 + i * KSTEP;
@@ -196,6 +208,14 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   };
   auto fetch_v = [&](int kv0) {
     const bool full = kv0 + BKV - 1 <= last_pos;
+    if (kFastFetch && contig && full) {
+      const bf16* vp = vthread + (size_t)kv0 * DH;
+#pragma unroll
+      for (int i = 0; i < VPER; ++i)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) rv[i][kk] = *reinterpret_cast<const uint4*>(vp + (size_t)i * KSTEP * 8 + (size_t)kk * DH);
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < VPER; ++i) {
       const int dch = vdch0 + i * KSTEP;
@@ -259,7 +279,7 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
     if (n_blk <= kLdsTableEntries) {   // uniform
       for (int i = tid; i < n_blk; i += NT) {
         const int blk = g.block_table[(size_t)seq * g.max_blocks + tab_first + i];
-        lds_tab[i] = min(max(blk, 0), g.n_blocks - 1);
+        lds_tab[i] = min(max(blk, 0), g.n_blocks - 1) * g.n_kv_heads + kvh;
       }
       tab_in_lds = true;
       __syncthreads();
@@ -294,11 +314,10 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
     // S^T = K Q^T : two blocks of 32 keys.  The two accumulator chains alternate and the K fragments are read
     // kFragAhead MFMAs ahead of their use, so that neither the LDS latency nor the MFMA dependency is exposed.
     f32x16 acc_s[2];
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc_s[b][e] = 0.f;
     {
+      f32x16 zero;   // the first product of each chain takes a constant-zero accumulator: no registers to clear
+#pragma unroll
+      for (int e = 0; e < 16; ++e) zero[e] = 0.f;
       auto k_frag = [&](int i) {   // step i: key block i & 1, head-dim step i >> 1
         return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(k_rd + KOFF + (i & 1) * 32 * KROW + (i >> 1) * 32));
       };
@@ -308,7 +327,7 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        acc_s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % kFragAhead], qf[i >> 1], acc_s[i & 1], 0, 0, 0);
+        acc_s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % kFragAhead], qf[i >> 1], i < 2 ? zero : acc_s[i & 1], 0, 0, 0);
         if (i + kFragAhead < 16) kf[i % kFragAhead] = k_frag(i + kFragAhead);
         staging_slice(i);
         __builtin_amdgcn_sched_barrier(0);
