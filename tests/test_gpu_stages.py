@@ -179,7 +179,11 @@ def test_final_select(n):
 
 # ------------------------------------------------------------------ K6
 @pytest.mark.parametrize("dtype,hq,hkv,dh", [("f32", 4, 2, 64), ("bf16", 8, 2, 128), ("bf16", 10, 2, 128),
-                                              ("bf16", 4, 4, 128), ("f32", 2, 1, 128)])
+                                              ("bf16", 4, 4, 128), ("f32", 2, 1, 128),
+                                              # every width of a query-head group the bf16 kernel is built for (1 ... 8), and
+                                              # one beyond (served in passes)
+                                              ("bf16", 4, 2, 128), ("bf16", 6, 2, 128), ("bf16", 12, 2, 128),
+                                              ("bf16", 14, 2, 128), ("bf16", 16, 2, 128), ("bf16", 18, 2, 128)])
 @pytest.mark.parametrize("block_size", [0, 16])
 @pytest.mark.parametrize("split", [False, True])
 def test_sparse_attention(dtype, hq, hkv, dh, block_size, split):
