@@ -57,13 +57,17 @@ __device__ inline float pair_max32(float x) {
 // the row's reference exponent and sum, score_ml[row * n_q_heads + head], unless the tile's KV range is split
 // (then attn_merge_kernel writes the merged pair).
 template <int G, bool SCORES>
-__global__ void __launch_bounds__(64 * G, (G <= 4 ? 2 : 1))
+__global__ void __launch_bounds__(64 * (G < 4 ? 4 : G), (G <= 4 ? 2 : 1))
 attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, const ReqTable* __restrict__ table,
                  int fixed_seq, int total_rows, int total_tiles, const bf16* __restrict__ k_pool,
                  const bf16* __restrict__ v_pool, KvGeom g, bf16* __restrict__ out, AttnSplit sp,
                  float* __restrict__ part_o, float2* __restrict__ part_ml, float* __restrict__ scores,
                  int scores_len, float2* __restrict__ score_ml) {
-  constexpr int NT = 64 * G;
+  // A workgroup has at least four wavefronts: with fewer, each thread would stage so much of a K/V tile that the
+  // kernel runs out of registers.  In a group of one to three query heads the wavefronts beyond the group only take
+  // their share of the staging; they multiply zeros for head 0 of the group and write nothing.
+  constexpr int NW = G < 4 ? 4 : G;
+  constexpr int NT = 64 * NW;
   // K rows are 256 + 16 bytes, V^T rows 128 + 16 bytes apart.  With 64 banks of 4 bytes, the 16 lanes
   // that fetch the same 16-byte chunk of 16 consecutive rows then hit every bank exactly once, and every
   // LDS address in the main loop is a per-thread base plus a compile-time constant.
@@ -125,8 +129,9 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ql = lane & 31, half = lane >> 5;
-  const int head = kvh * G + wave;
-  const bool q_ok = ql < n_valid;
+  const bool active = G >= 4 || wave < G;   // wave-uniform
+  const int head = kvh * G + (active ? wave : 0);
+  const bool q_ok = active && ql < n_valid;
   const int my_row = r0 + (q_ok ? ql : 0);
   const int my_pos = q_ok ? row_pos[my_row] : 0;
   const int first_pos = row_pos[r0];
@@ -425,6 +430,7 @@ attn_mfma_kernel(const bf16* __restrict__ q, const int* __restrict__ row_pos, co
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (!active) return;
   if (is_split) {
     // partial result of this chunk: un-normalised O, running maximum (log2 domain) and sum
     const size_t slot = ((size_t)(part_base + split_tile * sp.n_chunks + chunk) * n_q_heads + head) * BQ + ql;
@@ -564,11 +570,11 @@ static hipError_t launch_g(const bf16* q, const int* row_pos, const ReqTable* ta
                         : allow_dynamic_lds((const void*)attn_mfma_kernel<G, false>, ATTN_LDS_BYTES, told_plain);
   if (e != hipSuccess) return e;
   if (scores)
-    attn_mfma_kernel<G, true><<<grid, 64 * G, ATTN_LDS_BYTES, st>>>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool,
+    attn_mfma_kernel<G, true><<<grid, 64 * (G < 4 ? 4 : G), ATTN_LDS_BYTES, st>>>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool,
                                                                     v_pool, g, out, sp, part_o, part_ml, scores, scores_len,
                                                                     influence_pairs(scores, total_rows, g.n_kv_heads * G, scores_len));
   else
-    attn_mfma_kernel<G, false><<<grid, 64 * G, ATTN_LDS_BYTES, st>>>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool,
+    attn_mfma_kernel<G, false><<<grid, 64 * (G < 4 ? 4 : G), ATTN_LDS_BYTES, st>>>(q, row_pos, table, fixed_seq, total_rows, total_tiles, k_pool,
                                                                      v_pool, g, out, sp, part_o, part_ml, nullptr, 0, nullptr);
   return hipGetLastError();
 }
