@@ -252,6 +252,27 @@ __device__ inline void store_tile16(const f32x4 (&acc)[FM][FN], void* __restrict
   constexpr int WTN_OUT = DUAL ? WTN / 2 : WTN;
   const bool f32_out = !DUAL && (epi == EPI_STORE_F32 || epi == EPI_ADD_F32);
   const bool vec_ok = (ldc & 3) == 0 && (reinterpret_cast<size_t>(c) & (f32_out ? 15 : 7)) == 0;
+  if constexpr (!DUAL) {
+    // residual add with the wavefront's columns all inside C: the old values of a block row are requested together and
+    // added afterwards, so the wavefront waits for memory once per block row instead of once per 16 x 16 block
+    if (epi == EPI_ADD_F32 && vec_ok && n0 + wn * WTN + WTN <= n) {   // wave-uniform
+      float* const cf = reinterpret_cast<float*>(c);
+#pragma unroll
+      for (int i = 0; i < FM; ++i) {
+        const int row = m0 + wm * WTM + i * 16 + (lane & 15);
+        if (row >= m) continue;
+        float4* const dst = reinterpret_cast<float4*>(cf + (size_t)row * ldc + n0 + wn * WTN + 4 * (lane >> 4));
+        float4 old[FN];
+#pragma unroll
+        for (int j = 0; j < FN; ++j) old[j] = dst[j * 4];
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          dst[j * 4] = make_float4(old[j].x + acc[i][j][0], old[j].y + acc[i][j][1], old[j].z + acc[i][j][2],
+                                   old[j].w + acc[i][j][3]);
+      }
+      return;
+    }
+  }
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
     const int row = m0 + wm * WTM + i * 16 + (lane & 15);
