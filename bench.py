@@ -168,6 +168,42 @@ def cpu_baseline(w, budget_s=20.0):
                       f"workload's {full_rows} row-layers (estimated TTFT {est_ttft:.0f} s)"}
 
 
+def cpu_baseline_full(w):
+    """The CPU oracle timed directly on the whole workload (every layer, the workload's layer triple), not scaled from
+    a sample.  All layers share one layer's random weights: the values do not change the oracle's work, and the 7 G
+    parameters of 32 distinct layers would take longer to draw on the host than the pass itself.  About a minute."""
+    import numpy as np
+    from dataclasses import replace
+    from oracle import relay_oracle as R
+    from synth import make_hidden, make_weights, budget_to_k
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    sh1 = replace(w.shape, n_layers=1, vocab=1024)
+    one = make_weights(replace(w, name=w.name + "_cpu_full", shape=sh1))
+    sh = replace(w.shape, vocab=1024)
+    om = R.OracleModel.from_shape(sh, {"layers": [one["layers"][0]] * sh.n_layers, "g_final": one["g_final"],
+                                       "w_lm": one["w_lm"]})
+    P, S = w.n_prefix, w.n_seg
+    k = budget_to_k(S, w.budget_pct)
+    ws = replace(w, name=w.name + "_cpu_full", shape=sh)
+    xp = make_hidden(ws, "x_prefix", P)
+    rng = np.random.default_rng(1)
+    kv_shape = (sh.n_layers, S, sh.n_kv_heads, sh.head_dim)
+    seg = R.SegmentRecord(rng.standard_normal(kv_shape), rng.standard_normal(kv_shape),
+                          make_hidden(ws, "h_start", S).astype(np.float64), True, w.n_alt)
+    t0 = time.perf_counter()
+    res = R.relay_prefill(om, xp, seg, w.l_start, w.l_det, w.l_end, k)
+    dt = time.perf_counter() - t0
+    return {"value": (P + S) / dt, "unit": "context tokens/s", "cores": int(threads), "kind": "oracle",
+            "extrapolated": False, "ttft_s": dt,
+            "sample": f"oracle relay_prefill (numpy float64) on the whole workload: {sh.n_layers} layers (sharing one layer's "
+                      f"random weights), P={P}, S={S}, k={k}, triple ({w.l_start},{w.l_det},{w.l_end}), "
+                      f"{sum(res.active_rows)} row-layers in {dt:.1f} s"}
+
+
 def tiny_one_thread():
     """The oracle on the small float configuration (2 layers, 128 new + 256 reused tokens, 20 %), timed directly
     (no scaling) with numpy's BLAS held to one thread."""
@@ -199,6 +235,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="mistral7b_4k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline-full", action="store_true",
+                    help="also time the CPU oracle directly on the whole workload (about a minute) instead of only on the "
+                         "3-layer sample that the default run scales up")
     ap.add_argument("--no-full-prefill", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the stream-copy and MFMA-loop micro-benchmarks")
     ap.add_argument("--seed", type=int, default=20260313)
@@ -501,6 +540,8 @@ def main() -> int:
         out["roofline"]["frac_of_sustained_mfma"] = achieved / out["ceilings"]["mfma_loop_bf16_tflop_s"]
     if not args.no_cpu_baseline and n_req == 1:
         out["cpu_baseline"] = cpu_baseline(w)
+        if args.cpu_baseline_full:
+            out["cpu_baseline"]["direct"] = cpu_baseline_full(w)
     print(json.dumps(out))
     return 0
 
